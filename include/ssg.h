@@ -1,0 +1,163 @@
+/*
+ * ssg -- FP8 SwiGLU MLP block with Smooth-SwiGLU for AMD MI355X (gfx950).
+ *
+ * C ABI of libssg.so.  The block is the one the paper states in Sections 4.1
+ * and 4.4: for token t and channel i
+ *
+ *     U_ti = x_t . w1_i      (linear branch)        W1 [f,d] row-major, row i = w1_i
+ *     G_ti = x_t . w2_i      (Swish branch)         W2 [f,d]
+ *     h_ti = U_ti * G_ti * sigma(G_ti)
+ *     y_t  = sum_i w3_i h_ti (last linear layer)    W3 [d,f] row-major, column i = w3_i
+ *
+ * with every matrix product done on FP8 operands (E4M3 for activations and
+ * weights, E5M2 for gradients, Section 2 and 6.2) and fp32 accumulation.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller, 16-byte aligned,
+ *     row-major with the last index contiguous.  The library never allocates
+ *     device memory and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     only enqueue work and return; nothing is synchronised.
+ *   - A negative return value means no kernel was launched; ssg_last_error()
+ *     then returns a description (thread-local, valid until the next call on
+ *     that thread).
+ *   - Matrix extents that are contracted or vector-accessed (every rows/cols,
+ *     T, d, f, M, N, K below) must be positive multiples of 16, otherwise
+ *     SSG_ERR_SHAPE; ssg_amax / ssg_quantize accept an extent of 0 as "nothing
+ *     to do" (amax = 0, scale = 1).
+ *   - Inputs are expected to be finite.  NaN is ignored by every amax and maps
+ *     to the format's NaN code with its sign; +-Inf saturates like any value
+ *     above the largest finite one.
+ */
+#ifndef SSG_H
+#define SSG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SSG_OK = 0,
+    SSG_ERR_ARG = -1,          /* null pointer, bad enum, misaligned pointer */
+    SSG_ERR_SHAPE = -2,        /* extent not a positive multiple of 16, or too large */
+    SSG_ERR_WORKSPACE = -3,
+    SSG_ERR_HIP = -4,          /* a launch reported an error (text in ssg_last_error) */
+    SSG_ERR_UNSUPPORTED = -5
+} ssg_status;
+
+typedef enum { SSG_E4M3 = 0, SSG_E5M2 = 1 } ssg_fp8_format;      /* OCP FP8 encodings (Section 2) */
+typedef enum { SSG_BF16 = 0, SSG_F32 = 1 } ssg_dtype;
+typedef enum { SSG_SCALE_CURRENT = 0,   /* scale from this tensor's own range ("just-in-time", Section 2) */
+               SSG_SCALE_GIVEN = 1      /* caller supplies the scale, e.g. from earlier iterations ("delayed") */
+} ssg_scale_mode;
+typedef enum { SSG_ROUND_EXACT_DIV = 0, /* scale = fl32(fmax / amax) */
+               SSG_ROUND_POW2 = 1       /* scale = 2^floor(log2(fmax / amax)) */
+} ssg_scale_round;
+
+const char *ssg_last_error(void);
+const char *ssg_version(void);
+
+/* Largest absolute value of a tensor of n elements (per-tensor range, Section 2).
+ * amax_dev: out, one float.  NaN elements are ignored. */
+ssg_status ssg_amax(const void *src, ssg_dtype src_dtype, size_t n, float *amax_dev, void *stream);
+
+/* The quantization function Q of Eq. 2 for one tensor [rows, cols]:
+ *     dst[r,c] = satcast_fmt( fl32( src[r,c] * scale ) )
+ * satcast = round to nearest even, subnormals kept, magnitudes above the
+ * largest finite value clamp to it.  CURRENT: scale = fl32(fmax/amax) (1 when
+ * amax = 0, largest finite float when the division overflows), written to
+ * *scale_dev; GIVEN: *scale_dev is read.
+ *   dst     out [rows, cols] bytes
+ *   dst_t   out [cols, rows] bytes, the transposed copy (may be NULL)
+ *   amax_dev out, one float; required for CURRENT (holds the amax afterwards),
+ *           may be NULL for GIVEN */
+ssg_status ssg_quantize(const void *src, ssg_dtype src_dtype, int64_t rows, int64_t cols,
+                        ssg_fp8_format fmt, ssg_scale_mode mode, ssg_scale_round rnd,
+                        uint8_t *dst, uint8_t *dst_t, float *scale_dev, float *amax_dev, void *stream);
+
+/* One FP8 contraction with fp32 accumulation (the matrix products of Eq. 2 and
+ * of the display that follows it):
+ *     C[m,n] = ( sum_k A[m,k] * B[n,k] ) / (sa * sb)
+ * A [M,K] codes of a_fmt, B [N,K] codes of b_fmt (b_fmt must be SSG_E4M3),
+ * C [M,N] of c_dtype.  sa_dev / sb_dev: device pointers to the operands'
+ * scales (NULL = 1). */
+ssg_status ssg_gemm_fp8(const uint8_t *A, ssg_fp8_format a_fmt, const uint8_t *B, ssg_fp8_format b_fmt,
+                        int64_t M, int64_t N, int64_t K, const float *sa_dev, const float *sb_dev,
+                        void *C, ssg_dtype c_dtype, void *stream);
+
+/* SwiGLU product of Section 4.1 from stored bf16 U, G [T,f], in fp32:
+ * h = u * (g * (1 / (1 + exp(-g)))).  Debug / test entry: this is the h the
+ * fused kernels quantize.  h out [T,f] float. */
+ssg_status ssg_swiglu(const void *U, const void *G, int64_t T, int64_t f, float *h, void *stream);
+
+/* Smooth-SwiGLU quantization of the SwiGLU product (Section 4.4, Eq. 2 and the
+ * three-step per-channel recipe): from bf16 U, G [T,f]
+ *     a_i = max_t |h_ti|,  s_i = fl32(448 / a_i),  sinv_i = fl32(a_i / 448)   (both 1 when a_i = 0)
+ *     h_q[t,i] = satcast_E4M3( fl32( h_ti * s_i ) )
+ * smooth = 0 gives the plain block of Figure 4(a): one scale for the whole
+ * tensor, s_i = fl32(448 / max_i a_i) for every i and sinv_i = 1.
+ *   h_q   out [T,f];  h_qT out [f,T] (may be NULL)
+ *   s, sinv, camax  out, f floats each (camax = a_i) */
+ssg_status ssg_smooth_swiglu_quantize(const void *U, const void *G, int64_t T, int64_t f, int smooth,
+                                      uint8_t *h_q, uint8_t *h_qT, float *s, float *sinv, float *camax,
+                                      void *stream);
+
+/* Folding the inverse factor into the last linear layer, w3~_i = Q(s_i^-1 * w3_i)
+ * (the display after Eq. 2): W3 bf16 [d,f], column i scaled by sinv_i in fp32,
+ * then per-tensor E4M3 of the result.
+ *   w3_q out [d,f]; w3_qT out [f,d] (may be NULL)
+ *   w3_camax out, f floats (max_j |W3_ji|); scale_dev, amax_dev out, one float each */
+ssg_status ssg_fold_w3(const void *W3, const float *sinv, int64_t d, int64_t f,
+                       uint8_t *w3_q, uint8_t *w3_qT, float *w3_camax, float *scale_dev, float *amax_dev,
+                       void *stream);
+
+/* ---- the whole block ---------------------------------------------------- */
+
+typedef struct {
+    int64_t T, d, f;
+    int32_t smooth;          /* 1 = Smooth-SwiGLU (Figure 4b), 0 = plain per-tensor Q(h) (Figure 4a) */
+    int32_t rnd;             /* ssg_scale_round, applied to the per-tensor scales */
+    int32_t y_dtype;         /* ssg_dtype of y and dx */
+    int32_t dw_dtype;        /* ssg_dtype of dW1, dW2, dW3 */
+    int32_t reserved[4];     /* must be 0 */
+} ssg_mlp_desc;
+
+/* Sizes of the two caller-allocated device buffers.  `saved` carries what the
+ * backward pass needs (quantized operands, their transposed copies, bf16 U and
+ * G, the factors); `workspace` is scratch of the backward pass.  0 on a bad
+ * descriptor. */
+size_t ssg_mlp_saved_bytes(const ssg_mlp_desc *desc);
+size_t ssg_mlp_workspace_bytes(const ssg_mlp_desc *desc);
+
+/* Forward: y = block(x).  x [T,d], W1, W2 [f,d], W3 [d,f] bf16; y [T,d] of y_dtype. */
+ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, const void *W2,
+                       const void *W3, void *y, void *saved, void *stream);
+
+/* Backward of sum(y * dy) with the straight-through estimator through every Q
+ * and s_i held constant: dy [T,d] bf16 is quantized to E5M2; dx [T,d] y_dtype;
+ * dW1, dW2 [f,d], dW3 [d,f] of dw_dtype. */
+ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *saved, void *dx,
+                       void *dW1, void *dW2, void *dW3, void *workspace, void *stream);
+
+/* Pointers into `saved` / `workspace` for tests and reports (host struct of device pointers). */
+typedef struct {
+    const float *scales;     /* [0]=sx [1]=sw1 [2]=sw2 [3]=sw3 [4]=amax_x [5]=amax_w1 [6]=amax_w2 [7]=amax of s^-1*w3 */
+    const float *s, *sinv, *h_camax, *w3_camax;          /* f floats each */
+    const uint8_t *x_q, *x_qT, *w1_q, *w2_q, *w1_qT, *w2_qT, *h_q, *h_qT, *w3_q, *w3_qT;
+    const void *U, *G;                                   /* bf16 [T,f] */
+} ssg_mlp_saved_view;
+typedef struct {
+    const float *scales;     /* [0]=sdy [1]=sdu [2]=sdg [3]=amax_dy [4]=amax_du [5]=amax_dg */
+    const uint8_t *dy_q, *dy_qT, *du_q, *du_qT, *dg_q, *dg_qT;
+    const void *dU, *dG;                                 /* bf16 [T,f] */
+} ssg_mlp_workspace_view;
+ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_mlp_saved_view *out);
+ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspace, ssg_mlp_workspace_view *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSG_H */

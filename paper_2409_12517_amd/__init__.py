@@ -1,0 +1,186 @@
+"""Thin Python binding of libssg.so (FP8 Smooth-SwiGLU MLP block for MI355X).
+
+Argument marshalling only: every function below has the name and argument
+order of the C entry point in ``include/ssg.h`` and passes device pointers of
+``torch`` tensors straight through.  PyTorch is used for device memory and the
+current stream, nothing else; there is no fallback path -- if the library has
+not been built (``python paper_2409_12517_amd/build.py``) importing fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, c_char_p, c_float, c_int, c_int32, c_int64, c_size_t, c_uint8, c_void_p
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libssg.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python paper_2409_12517_amd/build.py` "
+        "(hipcc, --offload-arch=gfx950). There is no CPU fallback.")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+# enums of ssg.h
+SSG_OK, SSG_ERR_ARG, SSG_ERR_SHAPE, SSG_ERR_WORKSPACE, SSG_ERR_HIP, SSG_ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
+SSG_E4M3, SSG_E5M2 = 0, 1
+SSG_BF16, SSG_F32 = 0, 1
+SSG_SCALE_CURRENT, SSG_SCALE_GIVEN = 0, 1
+SSG_ROUND_EXACT_DIV, SSG_ROUND_POW2 = 0, 1
+
+EXPORTS = [
+    "ssg_last_error", "ssg_version", "ssg_amax", "ssg_quantize", "ssg_gemm_fp8", "ssg_swiglu",
+    "ssg_smooth_swiglu_quantize", "ssg_fold_w3", "ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes",
+    "ssg_mlp_fwd", "ssg_mlp_bwd", "ssg_mlp_view_saved", "ssg_mlp_view_workspace",
+]
+
+
+class ssg_mlp_desc(Structure):
+    _fields_ = [("T", c_int64), ("d", c_int64), ("f", c_int64), ("smooth", c_int32), ("rnd", c_int32),
+                ("y_dtype", c_int32), ("dw_dtype", c_int32), ("reserved", c_int32 * 4)]
+
+
+class ssg_mlp_saved_view(Structure):
+    _fields_ = [(n, c_void_p) for n in (
+        "scales", "s", "sinv", "h_camax", "w3_camax", "x_q", "x_qT", "w1_q", "w2_q", "w1_qT", "w2_qT",
+        "h_q", "h_qT", "w3_q", "w3_qT", "U", "G")]
+
+
+class ssg_mlp_workspace_view(Structure):
+    _fields_ = [(n, c_void_p) for n in ("scales", "dy_q", "dy_qT", "du_q", "du_qT", "dg_q", "dg_qT", "dU", "dG")]
+
+
+_lib.ssg_last_error.restype = c_char_p
+_lib.ssg_version.restype = c_char_p
+_lib.ssg_amax.argtypes = [c_void_p, c_int, c_size_t, c_void_p, c_void_p]
+_lib.ssg_quantize.argtypes = [c_void_p, c_int, c_int64, c_int64, c_int, c_int, c_int, c_void_p, c_void_p,
+                              c_void_p, c_void_p, c_void_p]
+_lib.ssg_gemm_fp8.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int64, c_int64, c_int64, c_void_p, c_void_p,
+                              c_void_p, c_int, c_void_p]
+_lib.ssg_swiglu.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_void_p]
+_lib.ssg_smooth_swiglu_quantize.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int, c_void_p, c_void_p,
+                                            c_void_p, c_void_p, c_void_p, c_void_p]
+_lib.ssg_fold_w3.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
+                             c_void_p, c_void_p]
+_lib.ssg_mlp_saved_bytes.argtypes = [POINTER(ssg_mlp_desc)]
+_lib.ssg_mlp_saved_bytes.restype = c_size_t
+_lib.ssg_mlp_workspace_bytes.argtypes = [POINTER(ssg_mlp_desc)]
+_lib.ssg_mlp_workspace_bytes.restype = c_size_t
+_lib.ssg_mlp_fwd.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 7
+_lib.ssg_mlp_bwd.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 8
+_lib.ssg_mlp_view_saved.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_saved_view)]
+_lib.ssg_mlp_view_workspace.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_workspace_view)]
+for _n in EXPORTS[2:]:
+    if _n not in ("ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes"):
+        getattr(_lib, _n).restype = c_int
+
+
+class SsgError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"ssg status {status}: {message}")
+        self.status = status
+
+
+def ssg_last_error() -> str:
+    return _lib.ssg_last_error().decode()
+
+
+def ssg_version() -> str:
+    return _lib.ssg_version().decode()
+
+
+def _check(status: int) -> None:
+    if status != SSG_OK:
+        raise SsgError(status, ssg_last_error())
+
+
+def _ptr(t):
+    """Device pointer of a tensor (None -> NULL); ints pass through."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def make_desc(T: int, d: int, f: int, smooth: int = 1, rnd: int = SSG_ROUND_EXACT_DIV,
+              y_dtype: int = SSG_BF16, dw_dtype: int = SSG_F32) -> ssg_mlp_desc:
+    return ssg_mlp_desc(T, d, f, smooth, rnd, y_dtype, dw_dtype, (c_int32 * 4)(0, 0, 0, 0))
+
+
+def ssg_amax(src, src_dtype, n, amax_dev, stream=None):
+    _check(_lib.ssg_amax(_ptr(src), src_dtype, n, _ptr(amax_dev), _stream(stream)))
+
+
+def ssg_quantize(src, src_dtype, rows, cols, fmt, mode, rnd, dst, dst_t, scale_dev, amax_dev, stream=None):
+    _check(_lib.ssg_quantize(_ptr(src), src_dtype, rows, cols, fmt, mode, rnd, _ptr(dst), _ptr(dst_t),
+                             _ptr(scale_dev), _ptr(amax_dev), _stream(stream)))
+
+
+def ssg_gemm_fp8(A, a_fmt, B, b_fmt, M, N, K, sa_dev, sb_dev, C, c_dtype, stream=None):
+    _check(_lib.ssg_gemm_fp8(_ptr(A), a_fmt, _ptr(B), b_fmt, M, N, K, _ptr(sa_dev), _ptr(sb_dev), _ptr(C),
+                             c_dtype, _stream(stream)))
+
+
+def ssg_swiglu(U, G, T, f, h, stream=None):
+    _check(_lib.ssg_swiglu(_ptr(U), _ptr(G), T, f, _ptr(h), _stream(stream)))
+
+
+def ssg_smooth_swiglu_quantize(U, G, T, f, smooth, h_q, h_qT, s, sinv, camax, stream=None):
+    _check(_lib.ssg_smooth_swiglu_quantize(_ptr(U), _ptr(G), T, f, smooth, _ptr(h_q), _ptr(h_qT), _ptr(s),
+                                           _ptr(sinv), _ptr(camax), _stream(stream)))
+
+
+def ssg_fold_w3(W3, sinv, d, f, w3_q, w3_qT, w3_camax, scale_dev, amax_dev, stream=None):
+    _check(_lib.ssg_fold_w3(_ptr(W3), _ptr(sinv), d, f, _ptr(w3_q), _ptr(w3_qT), _ptr(w3_camax),
+                            _ptr(scale_dev), _ptr(amax_dev), _stream(stream)))
+
+
+def ssg_mlp_saved_bytes(desc: ssg_mlp_desc) -> int:
+    return _lib.ssg_mlp_saved_bytes(ctypes.byref(desc))
+
+
+def ssg_mlp_workspace_bytes(desc: ssg_mlp_desc) -> int:
+    return _lib.ssg_mlp_workspace_bytes(ctypes.byref(desc))
+
+
+def ssg_mlp_fwd(desc, x, W1, W2, W3, y, saved, stream=None):
+    _check(_lib.ssg_mlp_fwd(ctypes.byref(desc), _ptr(x), _ptr(W1), _ptr(W2), _ptr(W3), _ptr(y), _ptr(saved),
+                            _stream(stream)))
+
+
+def ssg_mlp_bwd(desc, dy, saved, dx, dW1, dW2, dW3, workspace, stream=None):
+    _check(_lib.ssg_mlp_bwd(ctypes.byref(desc), _ptr(dy), _ptr(saved), _ptr(dx), _ptr(dW1), _ptr(dW2), _ptr(dW3),
+                            _ptr(workspace), _stream(stream)))
+
+
+def ssg_mlp_view_saved(desc, saved) -> ssg_mlp_saved_view:
+    v = ssg_mlp_saved_view()
+    _check(_lib.ssg_mlp_view_saved(ctypes.byref(desc), _ptr(saved), ctypes.byref(v)))
+    return v
+
+
+def ssg_mlp_view_workspace(desc, workspace) -> ssg_mlp_workspace_view:
+    v = ssg_mlp_workspace_view()
+    _check(_lib.ssg_mlp_view_workspace(ctypes.byref(desc), _ptr(workspace), ctypes.byref(v)))
+    return v
+
+
+def view_tensor(saved, base_ptr: int, field_ptr: int, shape, dtype):
+    """A tensor aliasing a region of a caller-owned byte buffer (`saved` or
+    `workspace`), located by the pointer a view struct returned."""
+    import torch
+    off = field_ptr - base_ptr
+    n = 1
+    for s in shape:
+        n *= s
+    nbytes = n * torch.empty((), dtype=dtype).element_size()
+    return saved[off:off + nbytes].view(dtype).view(*shape)

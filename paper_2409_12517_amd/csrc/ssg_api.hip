@@ -1,0 +1,423 @@
+// C ABI of libssg.so: argument validation, buffer layouts and the order of the
+// passes of the forward and backward block.  Host code only; every step of the
+// method runs in the kernels of ssg_quant.hip / ssg_gemm.hip.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/ssg.h"
+#include "ssg_device.h"
+#include "ssg_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+ssg_status fail(ssg_status code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool extent_ok(int64_t v) { return v > 0 && (v % 16) == 0; }
+constexpr int64_t kMaxElems = (int64_t)1 << 32;   // kernels address operand tiles with 32-bit byte offsets
+
+ssg_status check_launch(const char *what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(SSG_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return SSG_OK;
+}
+
+#define SSG_REQUIRE_PTR(p)                                                                     \
+    do {                                                                                       \
+        if ((p) == nullptr) return fail(SSG_ERR_ARG, "%s: %s is NULL", __func__, #p);          \
+        if (!aligned16(p)) return fail(SSG_ERR_ARG, "%s: %s is not 16-byte aligned", __func__, #p); \
+    } while (0)
+#define SSG_OPTIONAL_PTR(p)                                                                    \
+    do {                                                                                       \
+        if ((p) != nullptr && !aligned16(p))                                                   \
+            return fail(SSG_ERR_ARG, "%s: %s is not 16-byte aligned", __func__, #p);           \
+    } while (0)
+#define SSG_REQUIRE_SCALAR_PTR(p)                                                              \
+    do {                                                                                       \
+        if ((p) == nullptr) return fail(SSG_ERR_ARG, "%s: %s is NULL", __func__, #p);          \
+        if (reinterpret_cast<uintptr_t>(p) & 3u)                                               \
+            return fail(SSG_ERR_ARG, "%s: %s is not 4-byte aligned", __func__, #p);            \
+    } while (0)
+
+ssg::SrcKind src_kind(ssg_dtype dt) { return dt == SSG_BF16 ? ssg::SRC_BF16 : ssg::SRC_F32; }
+bool dtype_ok(int dt) { return dt == SSG_BF16 || dt == SSG_F32; }
+bool fmt_ok(int f) { return f == SSG_E4M3 || f == SSG_E5M2; }
+
+// ---- buffer layouts -----------------------------------------------------------
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct SavedLayout {
+    size_t scalars, s, sinv, h_camax, w3_camax, x_q, x_qT, w1_q, w2_q, w1_qT, w2_qT, U, G, h_q, h_qT, w3_q, w3_qT, total;
+};
+// scalar slots of `saved` (floats; amax slots are accumulated as bit patterns)
+enum { S_SX = 0, S_SW1, S_SW2, S_SW3, S_AMAX_X, S_AMAX_W1, S_AMAX_W2, S_AMAX_W3S, S_HMAX, S_COUNT = 64 };
+
+SavedLayout saved_layout(const ssg_mlp_desc &d) {
+    SavedLayout L;
+    const size_t T = d.T, dm = d.d, f = d.f;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
+    L.scalars = take(S_COUNT * 4);
+    // h_camax and w3_camax are zeroed together with the scalars: keep them adjacent
+    L.h_camax = take(f * 4); L.w3_camax = take(f * 4);
+    L.s = take(f * 4); L.sinv = take(f * 4);
+    L.x_q = take(T * dm); L.x_qT = take(T * dm);
+    L.w1_q = take(f * dm); L.w2_q = take(f * dm); L.w1_qT = take(f * dm); L.w2_qT = take(f * dm);
+    L.U = take(T * f * 2); L.G = take(T * f * 2);
+    L.h_q = take(T * f); L.h_qT = take(T * f);
+    L.w3_q = take(f * dm); L.w3_qT = take(f * dm);
+    L.total = o;
+    return L;
+}
+
+struct WorkLayout { size_t scalars, dy_q, dy_qT, dU, dG, du_q, du_qT, dg_q, dg_qT, total; };
+enum { W_SDY = 0, W_SDU, W_SDG, W_AMAX_DY, W_AMAX_DU, W_AMAX_DG, W_COUNT = 64 };
+
+WorkLayout work_layout(const ssg_mlp_desc &d) {
+    WorkLayout L;
+    const size_t T = d.T, dm = d.d, f = d.f;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
+    L.scalars = take(W_COUNT * 4);
+    L.dy_q = take(T * dm); L.dy_qT = take(T * dm);
+    L.dU = take(T * f * 2); L.dG = take(T * f * 2);
+    L.du_q = take(T * f); L.du_qT = take(T * f); L.dg_q = take(T * f); L.dg_qT = take(T * f);
+    L.total = o;
+    return L;
+}
+
+ssg_status check_desc(const ssg_mlp_desc *d, const char *who) {
+    if (!d) return fail(SSG_ERR_ARG, "%s: desc is NULL", who);
+    if (!extent_ok(d->T) || !extent_ok(d->d) || !extent_ok(d->f))
+        return fail(SSG_ERR_SHAPE, "%s: T=%lld d=%lld f=%lld must be positive multiples of 16", who,
+                    (long long)d->T, (long long)d->d, (long long)d->f);
+    if (d->T * d->f >= kMaxElems || d->f * d->d >= kMaxElems || d->T * d->d >= kMaxElems)
+        return fail(SSG_ERR_SHAPE, "%s: a matrix of this block has 2^32 or more elements", who);
+    if (d->smooth != 0 && d->smooth != 1) return fail(SSG_ERR_ARG, "%s: smooth must be 0 or 1", who);
+    if (d->rnd != SSG_ROUND_EXACT_DIV && d->rnd != SSG_ROUND_POW2) return fail(SSG_ERR_ARG, "%s: bad rnd", who);
+    if (!dtype_ok(d->y_dtype) || !dtype_ok(d->dw_dtype)) return fail(SSG_ERR_ARG, "%s: bad output dtype", who);
+    for (int i = 0; i < 4; ++i)
+        if (d->reserved[i] != 0) return fail(SSG_ERR_ARG, "%s: reserved fields must be 0", who);
+    return SSG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ssg_last_error(void) { return g_err; }
+const char *ssg_version(void) { return "ssg 0.1 (gfx950)"; }
+
+ssg_status ssg_amax(const void *src, ssg_dtype src_dtype, size_t n, float *amax_dev, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (!dtype_ok(src_dtype)) return fail(SSG_ERR_ARG, "ssg_amax: bad src_dtype");
+    SSG_REQUIRE_SCALAR_PTR(amax_dev);
+    if (n % 16) return fail(SSG_ERR_SHAPE, "ssg_amax: n=%zu must be a multiple of 16", n);
+    if (n) SSG_REQUIRE_PTR(src);
+    ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_dev), 1, 0u, st);
+    ssg::launch_amax(src, src_kind(src_dtype), n, reinterpret_cast<uint32_t *>(amax_dev), st);
+    return check_launch("ssg_amax");
+}
+
+ssg_status ssg_quantize(const void *src, ssg_dtype src_dtype, int64_t rows, int64_t cols, ssg_fp8_format fmt,
+                        ssg_scale_mode mode, ssg_scale_round rnd, uint8_t *dst, uint8_t *dst_t,
+                        float *scale_dev, float *amax_dev, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (!dtype_ok(src_dtype)) return fail(SSG_ERR_ARG, "ssg_quantize: bad src_dtype");
+    if (!fmt_ok(fmt)) return fail(SSG_ERR_ARG, "ssg_quantize: bad fmt");
+    if (mode != SSG_SCALE_CURRENT && mode != SSG_SCALE_GIVEN) return fail(SSG_ERR_ARG, "ssg_quantize: bad mode");
+    if (rnd != SSG_ROUND_EXACT_DIV && rnd != SSG_ROUND_POW2) return fail(SSG_ERR_ARG, "ssg_quantize: bad rnd");
+    if (rows < 0 || cols < 0 || rows % 16 || cols % 16)
+        return fail(SSG_ERR_SHAPE, "ssg_quantize: rows=%lld cols=%lld must be non-negative multiples of 16",
+                    (long long)rows, (long long)cols);
+    if (rows * cols >= kMaxElems) return fail(SSG_ERR_SHAPE, "ssg_quantize: 2^32 or more elements");
+    SSG_REQUIRE_SCALAR_PTR(scale_dev);
+    if (mode == SSG_SCALE_CURRENT) SSG_REQUIRE_SCALAR_PTR(amax_dev);
+    const bool empty = rows == 0 || cols == 0;
+    if (!empty) {
+        SSG_REQUIRE_PTR(src);
+        SSG_REQUIRE_PTR(dst);
+        SSG_OPTIONAL_PTR(dst_t);
+    }
+    ssg::CastArgs a;
+    a.src = src; a.kind = src_kind(src_dtype); a.rows = rows; a.cols = cols; a.fmt = fmt;
+    a.dst = dst; a.dst_t = dst_t; a.pow2 = rnd == SSG_ROUND_POW2;
+    if (mode == SSG_SCALE_CURRENT) {
+        ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_dev), 1, 0u, st);
+        ssg::launch_amax(src, a.kind, (size_t)(rows * cols), reinterpret_cast<uint32_t *>(amax_dev), st);
+        a.amax = amax_dev;
+        a.scale_out = scale_dev;
+        if (empty) ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(scale_dev), 1, 0x3f800000u, st);
+    } else {
+        a.scale_in = scale_dev;
+        if (amax_dev && !empty) {
+            ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_dev), 1, 0u, st);
+            ssg::launch_amax(src, a.kind, (size_t)(rows * cols), reinterpret_cast<uint32_t *>(amax_dev), st);
+        }
+    }
+    ssg::launch_cast(a, st);
+    return check_launch("ssg_quantize");
+}
+
+ssg_status ssg_gemm_fp8(const uint8_t *A, ssg_fp8_format a_fmt, const uint8_t *B, ssg_fp8_format b_fmt, int64_t M,
+                        int64_t N, int64_t K, const float *sa_dev, const float *sb_dev, void *C,
+                        ssg_dtype c_dtype, void *stream) {
+    if (!fmt_ok(a_fmt) || !fmt_ok(b_fmt)) return fail(SSG_ERR_ARG, "ssg_gemm_fp8: bad format");
+    if (b_fmt != SSG_E4M3) return fail(SSG_ERR_UNSUPPORTED, "ssg_gemm_fp8: B must be E4M3");
+    if (!dtype_ok(c_dtype)) return fail(SSG_ERR_ARG, "ssg_gemm_fp8: bad c_dtype");
+    if (!extent_ok(M) || !extent_ok(N) || !extent_ok(K))
+        return fail(SSG_ERR_SHAPE, "ssg_gemm_fp8: M=%lld N=%lld K=%lld must be positive multiples of 16",
+                    (long long)M, (long long)N, (long long)K);
+    if (M * K >= kMaxElems || N * K >= kMaxElems || M * N >= kMaxElems)
+        return fail(SSG_ERR_SHAPE, "ssg_gemm_fp8: a matrix has 2^32 or more elements");
+    SSG_REQUIRE_PTR(A); SSG_REQUIRE_PTR(B); SSG_REQUIRE_PTR(C);
+    ssg::GemmArgs g;
+    g.epilogue = ssg::EPI_STORE; g.a_fmt = a_fmt; g.M = M; g.N = N; g.K = K; g.A = A; g.B = B;
+    g.sa = sa_dev; g.sb = sb_dev; g.C = C; g.c_f32 = c_dtype == SSG_F32;
+    ssg::launch_gemm(g, (hipStream_t)stream);
+    return check_launch("ssg_gemm_fp8");
+}
+
+ssg_status ssg_swiglu(const void *U, const void *G, int64_t T, int64_t f, float *h, void *stream) {
+    if (!extent_ok(T) || !extent_ok(f)) return fail(SSG_ERR_SHAPE, "ssg_swiglu: T, f must be positive multiples of 16");
+    if (T * f >= kMaxElems) return fail(SSG_ERR_SHAPE, "ssg_swiglu: 2^32 or more elements");
+    SSG_REQUIRE_PTR(U); SSG_REQUIRE_PTR(G); SSG_REQUIRE_PTR(h);
+    ssg::launch_swiglu(U, G, T * f, h, (hipStream_t)stream);
+    return check_launch("ssg_swiglu");
+}
+
+ssg_status ssg_smooth_swiglu_quantize(const void *U, const void *G, int64_t T, int64_t f, int smooth, uint8_t *h_q,
+                                      uint8_t *h_qT, float *s, float *sinv, float *camax, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (!extent_ok(T) || !extent_ok(f))
+        return fail(SSG_ERR_SHAPE, "ssg_smooth_swiglu_quantize: T, f must be positive multiples of 16");
+    if (T * f >= kMaxElems) return fail(SSG_ERR_SHAPE, "ssg_smooth_swiglu_quantize: 2^32 or more elements");
+    if (smooth != 0 && smooth != 1) return fail(SSG_ERR_ARG, "ssg_smooth_swiglu_quantize: smooth must be 0 or 1");
+    SSG_REQUIRE_PTR(U); SSG_REQUIRE_PTR(G); SSG_REQUIRE_PTR(h_q); SSG_OPTIONAL_PTR(h_qT);
+    SSG_REQUIRE_PTR(s); SSG_REQUIRE_PTR(sinv); SSG_REQUIRE_PTR(camax);
+    // The first 16 bytes of h_q serve as scratch until the cast overwrites them: word 0 = running
+    // tensor maximum for the plain mode, word 1 = sink for the folded-weight range (unused here).
+    uint32_t *hmax = reinterpret_cast<uint32_t *>(h_q);
+    uint32_t *sink = hmax + 1;
+    ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(camax), (size_t)f, 0u, st);
+    ssg::launch_fill_u32(hmax, 4, 0u, st);
+    ssg::launch_col_amax(U, G, ssg::SRC_SWIGLU, T, f, reinterpret_cast<uint32_t *>(camax), st);
+    // camax also stands in for the per-channel range of w3 (its product only feeds the sink)
+    ssg::launch_channel_factors(camax, camax, f, smooth, s, sinv, sink, hmax, st);
+    ssg::CastArgs a;
+    a.src = U; a.src2 = G; a.kind = ssg::SRC_SWIGLU; a.rows = T; a.cols = f; a.fmt = ssg::kE4M3;
+    a.col_scale = s; a.dst = h_q; a.dst_t = h_qT;
+    ssg::launch_cast(a, st);
+    return check_launch("ssg_smooth_swiglu_quantize");
+}
+
+ssg_status ssg_fold_w3(const void *W3, const float *sinv, int64_t d, int64_t f, uint8_t *w3_q, uint8_t *w3_qT,
+                       float *w3_camax, float *scale_dev, float *amax_dev, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (!extent_ok(d) || !extent_ok(f)) return fail(SSG_ERR_SHAPE, "ssg_fold_w3: d, f must be positive multiples of 16");
+    if (d * f >= kMaxElems) return fail(SSG_ERR_SHAPE, "ssg_fold_w3: 2^32 or more elements");
+    SSG_REQUIRE_PTR(W3); SSG_REQUIRE_PTR(sinv); SSG_REQUIRE_PTR(w3_q); SSG_OPTIONAL_PTR(w3_qT);
+    SSG_REQUIRE_PTR(w3_camax); SSG_REQUIRE_SCALAR_PTR(scale_dev); SSG_REQUIRE_SCALAR_PTR(amax_dev);
+    ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(w3_camax), (size_t)f, 0u, st);
+    ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_dev), 1, 0u, st);
+    ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, d, f, reinterpret_cast<uint32_t *>(w3_camax), st);
+    ssg::launch_fold_range(w3_camax, sinv, f, reinterpret_cast<uint32_t *>(amax_dev), st);
+    ssg::CastArgs a;
+    a.src = W3; a.kind = ssg::SRC_BF16; a.rows = d; a.cols = f; a.fmt = ssg::kE4M3;
+    a.col_scale = sinv; a.amax = amax_dev; a.scale_out = scale_dev; a.dst = w3_q; a.dst_t = w3_qT;
+    ssg::launch_cast(a, st);
+    return check_launch("ssg_fold_w3");
+}
+
+size_t ssg_mlp_saved_bytes(const ssg_mlp_desc *desc) {
+    if (check_desc(desc, "ssg_mlp_saved_bytes") != SSG_OK) return 0;
+    return saved_layout(*desc).total;
+}
+size_t ssg_mlp_workspace_bytes(const ssg_mlp_desc *desc) {
+    if (check_desc(desc, "ssg_mlp_workspace_bytes") != SSG_OK) return 0;
+    return work_layout(*desc).total;
+}
+
+ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_mlp_saved_view *out) {
+    ssg_status rc = check_desc(desc, "ssg_mlp_view_saved");
+    if (rc != SSG_OK) return rc;
+    if (!saved || !out) return fail(SSG_ERR_ARG, "ssg_mlp_view_saved: NULL argument");
+    const SavedLayout L = saved_layout(*desc);
+    const uint8_t *b = static_cast<const uint8_t *>(saved);
+    out->scales = reinterpret_cast<const float *>(b + L.scalars);
+    out->s = reinterpret_cast<const float *>(b + L.s);
+    out->sinv = reinterpret_cast<const float *>(b + L.sinv);
+    out->h_camax = reinterpret_cast<const float *>(b + L.h_camax);
+    out->w3_camax = reinterpret_cast<const float *>(b + L.w3_camax);
+    out->x_q = b + L.x_q; out->x_qT = b + L.x_qT;
+    out->w1_q = b + L.w1_q; out->w2_q = b + L.w2_q; out->w1_qT = b + L.w1_qT; out->w2_qT = b + L.w2_qT;
+    out->h_q = b + L.h_q; out->h_qT = b + L.h_qT; out->w3_q = b + L.w3_q; out->w3_qT = b + L.w3_qT;
+    out->U = b + L.U; out->G = b + L.G;
+    return SSG_OK;
+}
+
+ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspace, ssg_mlp_workspace_view *out) {
+    ssg_status rc = check_desc(desc, "ssg_mlp_view_workspace");
+    if (rc != SSG_OK) return rc;
+    if (!workspace || !out) return fail(SSG_ERR_ARG, "ssg_mlp_view_workspace: NULL argument");
+    const WorkLayout L = work_layout(*desc);
+    const uint8_t *b = static_cast<const uint8_t *>(workspace);
+    out->scales = reinterpret_cast<const float *>(b + L.scalars);
+    out->dy_q = b + L.dy_q; out->dy_qT = b + L.dy_qT;
+    out->du_q = b + L.du_q; out->du_qT = b + L.du_qT; out->dg_q = b + L.dg_q; out->dg_qT = b + L.dg_qT;
+    out->dU = b + L.dU; out->dG = b + L.dG;
+    return SSG_OK;
+}
+
+ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, const void *W2, const void *W3,
+                       void *y, void *saved, void *stream) {
+    ssg_status rc = check_desc(desc, "ssg_mlp_fwd");
+    if (rc != SSG_OK) return rc;
+    SSG_REQUIRE_PTR(x); SSG_REQUIRE_PTR(W1); SSG_REQUIRE_PTR(W2); SSG_REQUIRE_PTR(W3);
+    SSG_REQUIRE_PTR(y); SSG_REQUIRE_PTR(saved);
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t T = desc->T, dm = desc->d, f = desc->f;
+    const int pow2 = desc->rnd == SSG_ROUND_POW2;
+    const SavedLayout L = saved_layout(*desc);
+    uint8_t *b = static_cast<uint8_t *>(saved);
+    float *sc = reinterpret_cast<float *>(b + L.scalars);
+    uint32_t *scb = reinterpret_cast<uint32_t *>(sc);
+    float *h_camax = reinterpret_cast<float *>(b + L.h_camax), *w3_camax = reinterpret_cast<float *>(b + L.w3_camax);
+    float *s = reinterpret_cast<float *>(b + L.s), *sinv = reinterpret_cast<float *>(b + L.sinv);
+
+    // zero the scalar block and both per-channel maxima (contiguous) in one fill
+    ssg::launch_fill_u32(scb, (L.s - L.scalars) / 4, 0u, st);
+
+    // a1: per-tensor ranges (Section 2)
+    ssg::launch_amax(x, ssg::SRC_BF16, (size_t)(T * dm), scb + S_AMAX_X, st);
+    ssg::launch_amax(W1, ssg::SRC_BF16, (size_t)(f * dm), scb + S_AMAX_W1, st);
+    ssg::launch_amax(W2, ssg::SRC_BF16, (size_t)(f * dm), scb + S_AMAX_W2, st);
+    ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
+
+    // a2: Q(x), Q(w1), Q(w2), each with the transposed copy the backward contractions read
+    ssg::CastArgs c;
+    c.kind = ssg::SRC_BF16; c.fmt = ssg::kE4M3; c.pow2 = pow2;
+    c.src = x; c.rows = T; c.cols = dm; c.amax = sc + S_AMAX_X; c.scale_out = sc + S_SX;
+    c.dst = b + L.x_q; c.dst_t = b + L.x_qT;
+    ssg::launch_cast(c, st);
+    c.src = W1; c.rows = f; c.cols = dm; c.amax = sc + S_AMAX_W1; c.scale_out = sc + S_SW1;
+    c.dst = b + L.w1_q; c.dst_t = b + L.w1_qT;
+    ssg::launch_cast(c, st);
+    c.src = W2; c.amax = sc + S_AMAX_W2; c.scale_out = sc + S_SW2; c.dst = b + L.w2_q; c.dst_t = b + L.w2_qT;
+    ssg::launch_cast(c, st);
+
+    // a3 + a4 + first half of a5: both inner products of Eq. 2, bf16 U and G, per-channel max |h|
+    ssg::GemmArgs g;
+    g.epilogue = ssg::EPI_SWIGLU; g.a_fmt = ssg::kE4M3; g.M = T; g.N = f; g.K = dm;
+    g.A = b + L.x_q; g.B = b + L.w1_q; g.B2 = b + L.w2_q;
+    g.sa = sc + S_SX; g.sb = sc + S_SW1; g.sb2 = sc + S_SW2;
+    g.C = b + L.U; g.C2 = b + L.G; g.camax_bits = reinterpret_cast<uint32_t *>(h_camax);
+    ssg::launch_gemm(g, st);
+
+    // a5: factors s_i, s_i^-1 and the range of s^-1 * w3
+    ssg::launch_channel_factors(h_camax, w3_camax, f, desc->smooth, s, sinv, scb + S_AMAX_W3S, scb + S_HMAX, st);
+
+    // a6: h^ = cast(s_i * h), recomputing h from the stored bf16 U, G
+    ssg::CastArgs hq;
+    hq.src = b + L.U; hq.src2 = b + L.G; hq.kind = ssg::SRC_SWIGLU; hq.rows = T; hq.cols = f; hq.fmt = ssg::kE4M3;
+    hq.col_scale = s; hq.dst = b + L.h_q; hq.dst_t = b + L.h_qT;
+    ssg::launch_cast(hq, st);
+
+    // a7: w3~ = Q(s^-1 * w3)
+    ssg::CastArgs wq;
+    wq.src = W3; wq.kind = ssg::SRC_BF16; wq.rows = dm; wq.cols = f; wq.fmt = ssg::kE4M3; wq.pow2 = pow2;
+    wq.col_scale = sinv; wq.amax = sc + S_AMAX_W3S; wq.scale_out = sc + S_SW3;
+    wq.dst = b + L.w3_q; wq.dst_t = b + L.w3_qT;
+    ssg::launch_cast(wq, st);
+
+    // a8: last linear layer.  Smooth: only the scale of w3~ is left; plain: s_i = sigma_h for all i
+    ssg::GemmArgs g2;
+    g2.epilogue = ssg::EPI_STORE; g2.a_fmt = ssg::kE4M3; g2.M = T; g2.N = dm; g2.K = f;
+    g2.A = b + L.h_q; g2.B = b + L.w3_q;
+    g2.sa = desc->smooth ? nullptr : s; g2.sb = sc + S_SW3;
+    g2.C = y; g2.c_f32 = desc->y_dtype == SSG_F32;
+    ssg::launch_gemm(g2, st);
+    return check_launch("ssg_mlp_fwd");
+}
+
+ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *saved, void *dx, void *dW1, void *dW2,
+                       void *dW3, void *workspace, void *stream) {
+    ssg_status rc = check_desc(desc, "ssg_mlp_bwd");
+    if (rc != SSG_OK) return rc;
+    SSG_REQUIRE_PTR(dy); SSG_REQUIRE_PTR(saved); SSG_REQUIRE_PTR(dx);
+    SSG_REQUIRE_PTR(dW1); SSG_REQUIRE_PTR(dW2); SSG_REQUIRE_PTR(dW3); SSG_REQUIRE_PTR(workspace);
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t T = desc->T, dm = desc->d, f = desc->f;
+    const int pow2 = desc->rnd == SSG_ROUND_POW2;
+    const SavedLayout L = saved_layout(*desc);
+    const WorkLayout Wl = work_layout(*desc);
+    const uint8_t *sv = static_cast<const uint8_t *>(saved);
+    uint8_t *wk = static_cast<uint8_t *>(workspace);
+    const float *sc = reinterpret_cast<const float *>(sv + L.scalars);
+    const float *s = reinterpret_cast<const float *>(sv + L.s), *sinv = reinterpret_cast<const float *>(sv + L.sinv);
+    float *wsc = reinterpret_cast<float *>(wk + Wl.scalars);
+    uint32_t *wscb = reinterpret_cast<uint32_t *>(wsc);
+    const int dw_f32 = desc->dw_dtype == SSG_F32;
+
+    ssg::launch_fill_u32(wscb, W_COUNT, 0u, st);
+
+    // a9: upstream gradient to E5M2 (Section 6.2), with its transposed copy
+    ssg::launch_amax(dy, ssg::SRC_BF16, (size_t)(T * dm), wscb + W_AMAX_DY, st);
+    ssg::CastArgs c;
+    c.src = dy; c.kind = ssg::SRC_BF16; c.rows = T; c.cols = dm; c.fmt = ssg::kE5M2; c.pow2 = pow2;
+    c.amax = wsc + W_AMAX_DY; c.scale_out = wsc + W_SDY; c.dst = wk + Wl.dy_q; c.dst_t = wk + Wl.dy_qT;
+    ssg::launch_cast(c, st);
+
+    // a10: dH = s_i * dY^ w3~ / (sdy sw3), then through the SwiGLU product
+    ssg::GemmArgs g;
+    g.epilogue = ssg::EPI_SWIGLU_BWD; g.a_fmt = ssg::kE5M2; g.M = T; g.N = f; g.K = dm;
+    g.A = wk + Wl.dy_q; g.B = sv + L.w3_qT; g.sa = wsc + W_SDY; g.sb = sc + S_SW3;
+    // plain block: dH = acc / (sdy sw3), no channel factor
+    g.col_scale = desc->smooth ? s : nullptr;
+    g.U = sv + L.U; g.G = sv + L.G; g.C = wk + Wl.dU; g.C2 = wk + Wl.dG; g.amax_bits = wscb + W_AMAX_DU;
+    ssg::launch_gemm(g, st);
+
+    // a11: two tensors, two E5M2 scales
+    c.kind = ssg::SRC_BF16; c.rows = T; c.cols = f;
+    c.src = wk + Wl.dU; c.amax = wsc + W_AMAX_DU; c.scale_out = wsc + W_SDU; c.dst = wk + Wl.du_q; c.dst_t = wk + Wl.du_qT;
+    ssg::launch_cast(c, st);
+    c.src = wk + Wl.dG; c.amax = wsc + W_AMAX_DG; c.scale_out = wsc + W_SDG; c.dst = wk + Wl.dg_q; c.dst_t = wk + Wl.dg_qT;
+    ssg::launch_cast(c, st);
+
+    // a12: dW3[j,i] = sinv_i * sum_t dY^[t,j] h^[t,i] / sdy   (plain: / (sdy * sigma_h))
+    ssg::GemmArgs g3;
+    g3.epilogue = ssg::EPI_STORE; g3.a_fmt = ssg::kE5M2; g3.M = dm; g3.N = f; g3.K = T;
+    g3.A = wk + Wl.dy_qT; g3.B = sv + L.h_qT; g3.sa = wsc + W_SDY; g3.sb = desc->smooth ? nullptr : s;
+    g3.col_scale = desc->smooth ? sinv : nullptr; g3.C = dW3; g3.c_f32 = dw_f32;
+    ssg::launch_gemm(g3, st);
+
+    // a13: dX = dU^ w1^ / (sdu sw1) + dG^ w2^ / (sdg sw2): two K segments, one accumulator
+    ssg::GemmArgs g4;
+    g4.epilogue = ssg::EPI_STORE; g4.a_fmt = ssg::kE5M2; g4.M = T; g4.N = dm; g4.K = f; g4.K2 = f;
+    g4.A = wk + Wl.du_q; g4.B = sv + L.w1_qT; g4.sa = wsc + W_SDU; g4.sb = sc + S_SW1;
+    g4.A2 = wk + Wl.dg_q; g4.B2 = sv + L.w2_qT; g4.sa2 = wsc + W_SDG; g4.sb2 = sc + S_SW2;
+    g4.C = dx; g4.c_f32 = desc->y_dtype == SSG_F32;
+    ssg::launch_gemm(g4, st);
+
+    // a14: dW1 = dU^T x^ / (sdu sx), dW2 = dG^T x^ / (sdg sx)
+    ssg::GemmArgs g5;
+    g5.epilogue = ssg::EPI_STORE; g5.a_fmt = ssg::kE5M2; g5.M = f; g5.N = dm; g5.K = T;
+    g5.A = wk + Wl.du_qT; g5.B = sv + L.x_qT; g5.sa = wsc + W_SDU; g5.sb = sc + S_SX; g5.C = dW1; g5.c_f32 = dw_f32;
+    ssg::launch_gemm(g5, st);
+    g5.A = wk + Wl.dg_qT; g5.sa = wsc + W_SDG; g5.C = dW2;
+    ssg::launch_gemm(g5, st);
+    return check_launch("ssg_mlp_bwd");
+}
+
+}  // extern "C"

@@ -1,0 +1,97 @@
+// Device-side helpers shared by the gfx950 kernels: bf16 <-> fp32, the
+// saturating FP8 cast, the SwiGLU product and its derivatives, reductions.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ssg {
+
+constexpr int kE4M3 = 0;
+constexpr int kE5M2 = 1;
+
+template <int FMT> struct Fp8Traits;
+template <> struct Fp8Traits<kE4M3> { static constexpr float fmax = 448.0f; };
+template <> struct Fp8Traits<kE5M2> { static constexpr float fmax = 57344.0f; };
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// fp32 -> bf16 bits, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// Per-tensor scale (Section 2; Q of Eq. 2): fl32(fmax / amax), 1 for an empty
+// range, clamped to the largest finite float; optionally rounded down to a
+// power of two by clearing the mantissa.
+__device__ __forceinline__ float scale_from_amax(float amax, float fmax, int pow2) {
+    float s = 1.0f;
+    if (amax > 0.0f) {
+        s = __fdiv_rn(fmax, amax);
+        s = fminf(s, 3.402823466e+38f);
+    }
+    if (pow2) s = __uint_as_float(__float_as_uint(s) & 0xff800000u);
+    return s;
+}
+
+// Two fp32 values -> two FP8 codes in the low 16 bits.  The hardware
+// conversion rounds to nearest even through the subnormal range but turns
+// out-of-range magnitudes into NaN/Inf codes, so the value is clamped to the
+// largest finite magnitude first.  NaN keeps its sign and becomes S.1111111.
+template <int FMT>
+__device__ __forceinline__ uint32_t satcast_pk2(float a, float b) {
+    constexpr float fmax = Fp8Traits<FMT>::fmax;
+    float ca = __builtin_amdgcn_fmed3f(a, -fmax, fmax);
+    float cb = __builtin_amdgcn_fmed3f(b, -fmax, fmax);
+    uint32_t p;
+    if (FMT == kE4M3) p = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(ca, cb, 0, false);
+    else              p = (uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(ca, cb, 0, false);
+    p &= 0xffffu;
+    if (__builtin_expect(a != a, 0)) p = (p & 0xff00u) | 0x7fu | ((__float_as_uint(a) >> 24) & 0x80u);
+    if (__builtin_expect(b != b, 0)) p = (p & 0x00ffu) | ((0x7fu | ((__float_as_uint(b) >> 24) & 0x80u)) << 8);
+    return p;
+}
+
+template <int FMT>
+__device__ __forceinline__ uint32_t satcast_pk4(float a, float b, float c, float d) {
+    return satcast_pk2<FMT>(a, b) | (satcast_pk2<FMT>(c, d) << 16);
+}
+
+// SwiGLU neuron of Section 4.1 in fp32: u * Swish(g), Swish(g) = g * sigma(g).
+// Every operation is a single rounded fp32 operation in a fixed order so that
+// the GEMM epilogue and the stand-alone pass produce identical bits.
+__device__ __forceinline__ float sigmoid_f32(float g) {
+    float e = expf(-g);
+    return __fdiv_rn(1.0f, __fadd_rn(1.0f, e));
+}
+__device__ __forceinline__ float swiglu_f32(float u, float g) {
+    float sw = __fmul_rn(g, sigmoid_f32(g));
+    return __fmul_rn(u, sw);
+}
+// d h / d u = g*sigma(g);  d h / d g = u * sigma(g) * (1 + g * (1 - sigma(g)))
+__device__ __forceinline__ void swiglu_grad_f32(float u, float g, float dh, float &du, float &dg) {
+    float sg = sigmoid_f32(g);
+    du = __fmul_rn(dh, __fmul_rn(g, sg));
+    float t = __fadd_rn(1.0f, __fmul_rn(g, __fsub_rn(1.0f, sg)));
+    dg = __fmul_rn(__fmul_rn(dh, u), __fmul_rn(sg, t));
+}
+
+// |x| of a non-NaN float as an unsigned integer orders like the float; NaN -> 0.
+__device__ __forceinline__ uint32_t abs_bits_ignore_nan(float v) {
+    uint32_t u = __float_as_uint(v) & 0x7fffffffu;
+    return u > 0x7f800000u ? 0u : u;
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        uint32_t o = (uint32_t)__shfl_xor((int)v, off, 64);
+        v = v > o ? v : o;
+    }
+    return v;
+}
+
+}  // namespace ssg

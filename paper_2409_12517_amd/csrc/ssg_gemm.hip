@@ -1,0 +1,309 @@
+// FP8 MFMA GEMM for gfx950 with the block's fused epilogues.
+//
+//   C[m,n] = sum_k A[m,k] * B[n,k]      A [M,K], B [N,K] FP8 codes, K contiguous
+//
+// (the inner products of Eq. 2, the last linear layer of the display after it,
+// and their gradient contractions).  fp32 accumulation on the matrix cores with
+// v_mfma_f32_32x32x64_f8f6f4, the only FP8 form that reaches the full rate on
+// this chip; its per-operand format selectors take E4M3 or E5M2.
+//
+// Workgroup: 512 threads = 8 waves as 2 (M) x 4 (N); tile 256 x 256 x 128; each
+// wave owns 128 x 64 outputs = 4 x 2 MFMA blocks (128 accumulator registers).
+// Tiles are streamed global -> LDS with 16-byte direct-to-LDS loads (no
+// staging registers), two LDS stages of 64 KB, one barrier per K step.  A row
+// of a tile is 128 bytes; the eight 16-byte chunks of a row are stored XOR-
+// permuted by the row index so that the 32 lanes that read the same logical
+// chunk of 32 different rows spread over all banks.
+//
+// Epilogues:
+//   STORE       C = acc / (sa*sb) [* col_scale[n]], bf16 or fp32; optional second
+//               K segment with its own scales (input gradient: two products summed).
+//   SWIGLU      B tile = 128 rows of W1 and the same 128 rows of W2, so a wave
+//               holds u and g of the same (t,i): stores bf16 U, G and folds
+//               max_t |u * Swish(g)| into the per-channel maxima (Section 4.4).
+//   SWIGLU_BWD  acc -> dH (times the channel factor s_i), reads bf16 U, G, stores
+//               bf16 dU, dG and folds their amax.
+#include "ssg_device.h"
+#include "ssg_internal.h"
+
+namespace ssg {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef __attribute__((address_space(1))) const void *global_void_ptr;
+
+constexpr int BM = 256, BN = 256, BK = 128;
+constexpr int kThreads = 512;
+constexpr int kTileBytes = BM * BK;               // one operand tile, 32 KB
+constexpr int kStageBytes = 2 * kTileBytes;       // A + B
+constexpr int kStages = 2;
+
+__device__ uint4 g_zero_chunk = {0u, 0u, 0u, 0u}; // source of the zero fill of a ragged K tail
+
+struct GemmParams {
+    const uint8_t *A, *B, *A2, *B2;
+    int64_t M, N, K, K2;
+    const float *sa, *sb, *sa2, *sb2, *col_scale;
+    void *C, *C2;
+    const uint16_t *U, *G;
+    uint32_t *camax_bits, *amax_bits;
+    int c_f32;
+    int tiles_m, tiles_n;
+};
+
+__device__ __forceinline__ int swz(int row) { return row & 7; }
+
+template <int AFMT>
+__device__ __forceinline__ v16f mfma(const v8i &a, const v8i &b, const v16f &c) {
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, AFMT, 0, 0, 0, 0, 0);
+}
+
+__device__ __forceinline__ float inv_scale_product(const float *sa, const float *sb) {
+    float p = 1.0f;
+    if (sa) p = *sa;
+    if (sb) p = __fmul_rn(p, *sb);
+    return __fdiv_rn(1.0f, p);
+}
+
+template <int EPI, int AFMT>
+__global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[kStages * kStageBytes];
+
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, l = tid & 63;
+    const int wm = w >> 2, wn = w & 3;
+
+    const int tile_m = blockIdx.x % p.tiles_m;
+    const int tile_n = blockIdx.x / p.tiles_m;
+    const int64_t m0 = (int64_t)tile_m * BM;
+    // SWIGLU: a tile covers 128 channels (128 rows of W1 + the same 128 rows of W2)
+    const int64_t n0 = (int64_t)tile_n * (EPI == EPI_SWIGLU ? BN / 2 : BN);
+
+    // ---- global -> LDS slots of this lane: 4 chunks of A and 4 of B per stage
+    const int lrow = l >> 3;                   // row inside the 8-row group one instruction fills
+    const int lpos = l & 7;                    // 16-byte position inside the 128-byte LDS row
+    uint32_t a_off[4], b_off[4];               // byte offsets of the row starts (without k)
+    const uint8_t *b_src = p.B;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = (w * 4 + j) * 8 + lrow;
+        int64_t gm = m0 + row;
+        gm = gm < p.M ? gm : p.M - 1;
+        a_off[j] = (uint32_t)(gm * p.K);
+        int64_t gn;
+        if (EPI == EPI_SWIGLU) gn = n0 + (row & 127);
+        else gn = n0 + row;
+        gn = gn < p.N ? gn : p.N - 1;
+        b_off[j] = (uint32_t)(gn * p.K);
+    }
+    if (EPI == EPI_SWIGLU && w >= 4) b_src = p.B2;      // waves 4..7 fill tile rows 128..255
+    const int chunk = lpos ^ swz(lrow);        // logical chunk this lane fetches (rows of a group are 8-aligned)
+    const uint32_t lds_a = (uint32_t)(w * 4) * 1024u;   // + j*1024 + stage offset
+    const uint32_t lds_b = kTileBytes + lds_a;
+
+    // ---- LDS -> register fragment offsets (same pattern for A and B)
+    uint32_t frag_off[2][2];
+#pragma unroll
+    for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            frag_off[kh][e] = (uint32_t)((l & 31) * BK + (((kh * 4 + (l >> 5) * 2 + e) ^ swz(l & 31)) << 4));
+    const uint32_t a_frag_base = (uint32_t)(wm * 128) * BK;
+    uint32_t b_frag_base[2];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+        b_frag_base[nb] = kTileBytes + (uint32_t)(EPI == EPI_SWIGLU ? nb * 128 + wn * 32 : wn * 64 + nb * 32) * BK;
+
+    v16f acc[4][2];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mb][nb][i] = 0.0f;
+
+    const int n_seg = (EPI == EPI_STORE && p.A2) ? 2 : 1;
+    for (int seg = 0; seg < n_seg; ++seg) {
+        const uint8_t *Aseg = seg ? p.A2 : p.A;
+        const uint8_t *Bseg = seg ? p.B2 : b_src;
+        const int64_t Kseg = seg ? p.K2 : p.K;
+        if (seg) {
+            // both products share one accumulator: rescale the first by alpha1 / alpha2
+            const float r = __fdiv_rn(inv_scale_product(p.sa, p.sb), inv_scale_product(p.sa2, p.sb2));
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[mb][nb][i] *= r;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {      // row starts for the second pair (row pitch K2)
+                const int row = (w * 4 + j) * 8 + lrow;
+                int64_t gm = m0 + row; gm = gm < p.M ? gm : p.M - 1;
+                int64_t gn = n0 + row; gn = gn < p.N ? gn : p.N - 1;
+                a_off[j] = (uint32_t)(gm * Kseg);
+                b_off[j] = (uint32_t)(gn * Kseg);
+            }
+            __syncthreads();                   // everyone is done reading the last stage of segment 0
+        }
+        const int nk = (int)((Kseg + BK - 1) / BK);
+
+        auto issue = [&](int kt, int stage) {
+            const int64_t k0 = (int64_t)kt * BK + chunk * 16;
+            const bool k_ok = k0 < Kseg;       // K is a multiple of 16: a chunk is all in or all out
+            const uint32_t sbase = (uint32_t)stage * kStageBytes;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint8_t *ga = k_ok ? Aseg + a_off[j] + k0 : reinterpret_cast<const uint8_t *>(&g_zero_chunk);
+                const uint8_t *gb = k_ok ? Bseg + b_off[j] + k0 : reinterpret_cast<const uint8_t *>(&g_zero_chunk);
+                __builtin_amdgcn_global_load_lds((global_void_ptr)ga, (lds_void_ptr)(smem + sbase + lds_a + j * 1024),
+                                                 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((global_void_ptr)gb, (lds_void_ptr)(smem + sbase + lds_b + j * 1024),
+                                                 16, 0, 0);
+            }
+        };
+
+        issue(0, 0);
+        for (int kt = 0; kt < nk; ++kt) {
+            const int stage = kt & 1;
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (kt + 1 < nk) issue(kt + 1, stage ^ 1);
+            const uint8_t *sA = smem + stage * kStageBytes + a_frag_base;
+            const uint8_t *sB = smem + stage * kStageBytes;
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh) {
+                v8i a[4], b[2];
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) {
+                    const uint4 lo = *reinterpret_cast<const uint4 *>(sA + mb * 32 * BK + frag_off[kh][0]);
+                    const uint4 hi = *reinterpret_cast<const uint4 *>(sA + mb * 32 * BK + frag_off[kh][1]);
+                    a[mb] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+                }
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) {
+                    const uint4 lo = *reinterpret_cast<const uint4 *>(sB + b_frag_base[nb] + frag_off[kh][0]);
+                    const uint4 hi = *reinterpret_cast<const uint4 *>(sB + b_frag_base[nb] + frag_off[kh][1]);
+                    b[nb] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+                }
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma<AFMT>(a[mb], b[nb], acc[mb][nb]);
+            }
+        }
+    }
+
+    // ---- epilogue.  Block (mb, nb), register i, lane l holds
+    //      row = wm*128 + mb*32 + (i/4)*8 + (l/32)*4 + i%4,  column = colbase(nb) + l%32.
+    const int lcol = l & 31;
+    const int lrow4 = (l >> 5) * 4;
+
+    if (EPI == EPI_STORE) {
+        const float alpha = inv_scale_product(n_seg == 2 ? p.sa2 : p.sa, n_seg == 2 ? p.sb2 : p.sb);
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            const int64_t col = n0 + wn * 64 + nb * 32 + lcol;
+            if (col >= p.N) continue;
+            const float f = p.col_scale ? __fmul_rn(alpha, p.col_scale[col]) : alpha;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int64_t row = m0 + wm * 128 + mb * 32 + (i >> 2) * 8 + lrow4 + (i & 3);
+                    if (row >= p.M) continue;
+                    const float v = __fmul_rn(acc[mb][nb][i], f);
+                    if (p.c_f32) reinterpret_cast<float *>(p.C)[row * p.N + col] = v;
+                    else reinterpret_cast<uint16_t *>(p.C)[row * p.N + col] = (uint16_t)f32_to_bf16_bits(v);
+                }
+        }
+    } else if (EPI == EPI_SWIGLU) {
+        const float alpha_u = inv_scale_product(p.sa, p.sb);
+        const float alpha_g = inv_scale_product(p.sa, p.sb2);
+        const int64_t col = n0 + wn * 32 + lcol;
+        uint32_t hmax = 0;
+        if (col < p.N) {
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int64_t row = m0 + wm * 128 + mb * 32 + (i >> 2) * 8 + lrow4 + (i & 3);
+                    if (row >= p.M) continue;
+                    const uint32_t ub = f32_to_bf16_bits(__fmul_rn(acc[mb][0][i], alpha_u));
+                    const uint32_t gb = f32_to_bf16_bits(__fmul_rn(acc[mb][1][i], alpha_g));
+                    reinterpret_cast<uint16_t *>(p.C)[row * p.N + col] = (uint16_t)ub;
+                    reinterpret_cast<uint16_t *>(p.C2)[row * p.N + col] = (uint16_t)gb;
+                    const uint32_t hb = abs_bits_ignore_nan(swiglu_f32(bf16_bits_to_f32(ub), bf16_bits_to_f32(gb)));
+                    hmax = hmax > hb ? hmax : hb;
+                }
+        }
+        const uint32_t other = (uint32_t)__shfl_xor((int)hmax, 32, 64);
+        hmax = hmax > other ? hmax : other;
+        if (l < 32 && col < p.N && hmax) atomicMax(&p.camax_bits[col], hmax);
+    } else {   // EPI_SWIGLU_BWD
+        const float alpha = inv_scale_product(p.sa, p.sb);
+        uint32_t du_max = 0, dg_max = 0;
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            const int64_t col = n0 + wn * 64 + nb * 32 + lcol;
+            if (col >= p.N) continue;
+            const float f = p.col_scale ? __fmul_rn(alpha, p.col_scale[col]) : alpha;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int64_t row = m0 + wm * 128 + mb * 32 + (i >> 2) * 8 + lrow4 + (i & 3);
+                    if (row >= p.M) continue;
+                    const float dh = __fmul_rn(acc[mb][nb][i], f);
+                    const float u = bf16_bits_to_f32(p.U[row * p.N + col]);
+                    const float g = bf16_bits_to_f32(p.G[row * p.N + col]);
+                    float du, dg;
+                    swiglu_grad_f32(u, g, dh, du, dg);
+                    const uint32_t dub = f32_to_bf16_bits(du), dgb = f32_to_bf16_bits(dg);
+                    reinterpret_cast<uint16_t *>(p.C)[row * p.N + col] = (uint16_t)dub;
+                    reinterpret_cast<uint16_t *>(p.C2)[row * p.N + col] = (uint16_t)dgb;
+                    const uint32_t am = abs_bits_ignore_nan(bf16_bits_to_f32(dub));
+                    const uint32_t bm = abs_bits_ignore_nan(bf16_bits_to_f32(dgb));
+                    du_max = du_max > am ? du_max : am;
+                    dg_max = dg_max > bm ? dg_max : bm;
+                }
+        }
+        du_max = wave_max_u32(du_max);
+        dg_max = wave_max_u32(dg_max);
+        if (l == 0) {
+            if (du_max) atomicMax(&p.amax_bits[0], du_max);
+            if (dg_max) atomicMax(&p.amax_bits[1], dg_max);
+        }
+    }
+}
+
+template <int EPI>
+static void launch_epi(const GemmParams &p, int a_fmt, unsigned blocks, hipStream_t st) {
+    if (a_fmt == kE4M3)
+        hipLaunchKernelGGL((gemm_kernel<EPI, kE4M3>), dim3(blocks), dim3(kThreads), 0, st, p);
+    else
+        hipLaunchKernelGGL((gemm_kernel<EPI, kE5M2>), dim3(blocks), dim3(kThreads), 0, st, p);
+}
+
+void launch_gemm(const GemmArgs &a, hipStream_t st) {
+    GemmParams p;
+    p.A = a.A; p.B = a.B; p.A2 = a.A2; p.B2 = a.B2;
+    p.M = a.M; p.N = a.N; p.K = a.K; p.K2 = a.K2;
+    p.sa = a.sa; p.sb = a.sb; p.sa2 = a.sa2; p.sb2 = a.sb2; p.col_scale = a.col_scale;
+    p.C = a.C; p.C2 = a.C2;
+    p.U = (const uint16_t *)a.U; p.G = (const uint16_t *)a.G;
+    p.camax_bits = a.camax_bits; p.amax_bits = a.amax_bits;
+    p.c_f32 = a.c_f32;
+    p.tiles_m = (int)((a.M + BM - 1) / BM);
+    const int n_per_tile = a.epilogue == EPI_SWIGLU ? BN / 2 : BN;
+    p.tiles_n = (int)((a.N + n_per_tile - 1) / n_per_tile);
+    const unsigned blocks = (unsigned)p.tiles_m * (unsigned)p.tiles_n;
+    switch (a.epilogue) {
+        case EPI_STORE: launch_epi<EPI_STORE>(p, a.a_fmt, blocks, st); break;
+        case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(p, a.a_fmt, blocks, st); break;
+        default: launch_epi<EPI_SWIGLU_BWD>(p, a.a_fmt, blocks, st); break;
+    }
+}
+
+}  // namespace ssg

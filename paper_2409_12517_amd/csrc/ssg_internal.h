@@ -1,0 +1,79 @@
+// Internal launch interface between the C-ABI layer and the kernels.
+// Everything takes raw device pointers and a hipStream_t; nothing allocates.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ssg {
+
+enum SrcKind { SRC_BF16 = 0, SRC_F32 = 1, SRC_SWIGLU = 2 };
+
+// ---- elementwise / reduction passes (ssg_quant.hip) -------------------------
+void launch_fill_u32(uint32_t *p, size_t n, uint32_t value, hipStream_t st);
+
+// amax_bits: running maximum of |x| as float bits (must be zeroed by the caller).
+void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, hipStream_t st);
+
+struct CastArgs {
+    const void *src = nullptr;       // bf16 / f32 [rows, cols]; U for SRC_SWIGLU
+    const void *src2 = nullptr;      // G for SRC_SWIGLU
+    SrcKind kind = SRC_BF16;
+    int64_t rows = 0, cols = 0;
+    int fmt = 0;                     // kE4M3 / kE5M2
+    const float *col_scale = nullptr;   // optional per-column factor applied first (one fp32 multiply)
+    const float *amax = nullptr;     // per-tensor: scale = scale_from_amax(*amax) ...
+    const float *scale_in = nullptr; // ... or a given scale; both null = no per-tensor factor
+    int pow2 = 0;
+    float *scale_out = nullptr;      // where the per-tensor scale is recorded (may be null)
+    uint8_t *dst = nullptr;          // [rows, cols]
+    uint8_t *dst_t = nullptr;        // [cols, rows] or null
+};
+void launch_cast(const CastArgs &a, hipStream_t st);
+
+// camax_bits[c] = max_r |v[r,c]| as float bits (zeroed by the caller).
+void launch_col_amax(const void *src, const void *src2, SrcKind kind, int64_t rows, int64_t cols,
+                     uint32_t *camax_bits, hipStream_t st);
+
+// Per-channel factors from the per-channel maxima (Section 4.4) and the range
+// of s^-1 * w3 for the folded weight.  smooth = 0: one factor for all channels.
+//   hmax_bits: scratch for the plain mode (zeroed by the caller)
+void launch_channel_factors(const float *h_camax, const float *w3_camax, int64_t f, int smooth,
+                            float *s, float *sinv, uint32_t *amax_w3s_bits, uint32_t *hmax_bits,
+                            hipStream_t st);
+
+// amax_bits = max_i fl32(w3_camax[i] * sinv[i]) as float bits (zeroed by the caller).
+void launch_fold_range(const float *w3_camax, const float *sinv, int64_t f, uint32_t *amax_bits, hipStream_t st);
+
+void launch_swiglu(const void *U, const void *G, int64_t n, float *h, hipStream_t st);
+
+// ---- FP8 MFMA GEMM (ssg_gemm.hip) --------------------------------------------
+enum Epilogue {
+    EPI_STORE = 0,        // C = acc * alpha [* col_scale[n]]
+    EPI_SWIGLU = 1,       // dual B: U, G bf16 stores + per-channel max of |h|
+    EPI_SWIGLU_BWD = 2    // acc -> dH; loads U, G; stores dU, dG bf16 + their amax
+};
+
+struct GemmArgs {
+    int epilogue = EPI_STORE;
+    int a_fmt = 0;                      // kE4M3 / kE5M2 (B is always E4M3)
+    int64_t M = 0, N = 0, K = 0;
+    const uint8_t *A = nullptr;         // [M, K]
+    const uint8_t *B = nullptr;         // [N, K]
+    // second K segment (EPI_STORE only): acc = acc1 * (alpha1/alpha2) + sum A2*B2
+    const uint8_t *A2 = nullptr;        // [M, K2]
+    const uint8_t *B2 = nullptr;        // [N, K2]   (EPI_SWIGLU: the second weight matrix, same K)
+    int64_t K2 = 0;
+    // dequantization: alpha = 1 / (sa * sb); null pointer = 1
+    const float *sa = nullptr, *sb = nullptr, *sa2 = nullptr, *sb2 = nullptr;
+    const float *col_scale = nullptr;   // optional [N] factor (EPI_STORE, EPI_SWIGLU_BWD)
+    void *C = nullptr;                  // EPI_STORE: [M,N];  EPI_SWIGLU: U;  EPI_SWIGLU_BWD: dU
+    void *C2 = nullptr;                 // EPI_SWIGLU: G;  EPI_SWIGLU_BWD: dG
+    int c_f32 = 0;                      // EPI_STORE: 1 = fp32 output, 0 = bf16
+    const void *U = nullptr, *G = nullptr;      // EPI_SWIGLU_BWD inputs (bf16 [M,N])
+    uint32_t *camax_bits = nullptr;     // EPI_SWIGLU: [N] running max |h| (float bits)
+    uint32_t *amax_bits = nullptr;      // EPI_SWIGLU_BWD: [2] running max |dU|, |dG| (float bits)
+};
+void launch_gemm(const GemmArgs &a, hipStream_t st);
+
+}  // namespace ssg

@@ -1,0 +1,356 @@
+// HBM-bound passes of the FP8 Smooth-SwiGLU block for gfx950:
+//   amax (Section 2: per-tensor range), the scale + saturating cast Q of Eq. 2
+//   with an optional transposed copy, per-channel maxima and factors of
+//   Section 4.4, and the SwiGLU product of Section 4.1 for tests.
+// All loads and stores are 16-byte (8-byte for row-major code stores) vectors
+// along the contiguous index; reductions use one atomic max per workgroup or
+// per column on the float's bit pattern (|x| orders like an unsigned integer).
+#include "ssg_device.h"
+#include "ssg_internal.h"
+
+namespace ssg {
+
+// ------------------------------------------------------------------ fill
+__global__ void __launch_bounds__(256) fill_u32_kernel(uint32_t *p, size_t n, uint32_t v) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+void launch_fill_u32(uint32_t *p, size_t n, uint32_t value, hipStream_t st) {
+    if (n == 0) return;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, value);
+}
+
+// ------------------------------------------------------------------ loaders
+// Each loader returns 8 consecutive elements of one row as fp32.
+struct LoadBf16 {
+    const uint16_t *p;
+    __device__ __forceinline__ void load8(size_t off, float (&v)[8]) const {
+        uint4 q = *reinterpret_cast<const uint4 *>(p + off);
+        uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+struct LoadF32 {
+    const float *p;
+    __device__ __forceinline__ void load8(size_t off, float (&v)[8]) const {
+        float4 a = *reinterpret_cast<const float4 *>(p + off);
+        float4 b = *reinterpret_cast<const float4 *>(p + off + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+};
+struct LoadSwiglu {          // h = u * Swish(g) from stored bf16 U, G
+    const uint16_t *u, *g;
+    __device__ __forceinline__ void load8(size_t off, float (&v)[8]) const {
+        float uu[8], gg[8];
+        LoadBf16{u}.load8(off, uu);
+        LoadBf16{g}.load8(off, gg);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = swiglu_f32(uu[i], gg[i]);
+    }
+};
+
+// ------------------------------------------------------------------ amax
+template <class Loader>
+__global__ void __launch_bounds__(256) amax_kernel(Loader ld, size_t n8, uint32_t *amax_bits) {
+    uint32_t m = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+        float v[8];
+        ld.load8(i * 8, v);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            uint32_t b = abs_bits_ignore_nan(v[k]);
+            m = m > b ? m : b;
+        }
+    }
+    m = wave_max_u32(m);
+    __shared__ uint32_t part[4];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t r = part[0];
+        for (int w = 1; w < 4; ++w) r = r > part[w] ? r : part[w];
+        if (r) atomicMax(amax_bits, r);
+    }
+}
+
+void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, hipStream_t st) {
+    size_t n8 = n / 8;      // n is a multiple of 256 at every call site (rows, cols multiples of 16)
+    if (n8 == 0) return;
+    size_t want = (n8 + 255) / 256;
+    unsigned blocks = (unsigned)(want < 2048 ? want : 2048);
+    if (kind == SRC_BF16)
+        hipLaunchKernelGGL(amax_kernel<LoadBf16>, dim3(blocks), dim3(256), 0, st,
+                           LoadBf16{(const uint16_t *)src}, n8, amax_bits);
+    else
+        hipLaunchKernelGGL(amax_kernel<LoadF32>, dim3(blocks), dim3(256), 0, st,
+                           LoadF32{(const float *)src}, n8, amax_bits);
+}
+
+// ------------------------------------------------------------------ cast
+// One workgroup converts a 128 x 128 tile.  A thread owns two 4-row x 8-column
+// blocks: it loads 8 elements from each of 4 rows, scales, casts, stores the
+// 8 codes of each row (8 bytes, 16 lanes cover 128 contiguous bytes), and, if
+// the transposed copy is wanted, transposes its 4x4 byte blocks in registers
+// and parks them in LDS as [column][row] so that the copy is written in
+// 16-byte pieces that are contiguous along the source's row index.
+constexpr int kTile = 128;
+constexpr int kTPitchWords = 33;     // LDS pitch of one transposed column, in 32-bit words
+
+__device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d,
+                                                   uint32_t (&o)[4]) {
+    uint32_t ab_lo = __builtin_amdgcn_perm(b, a, 0x05010400u);   // a0 b0 a1 b1
+    uint32_t ab_hi = __builtin_amdgcn_perm(b, a, 0x07030602u);   // a2 b2 a3 b3
+    uint32_t cd_lo = __builtin_amdgcn_perm(d, c, 0x05010400u);
+    uint32_t cd_hi = __builtin_amdgcn_perm(d, c, 0x07030602u);
+    o[0] = __builtin_amdgcn_perm(cd_lo, ab_lo, 0x05040100u);     // a0 b0 c0 d0
+    o[1] = __builtin_amdgcn_perm(cd_lo, ab_lo, 0x07060302u);
+    o[2] = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x05040100u);
+    o[3] = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x07060302u);
+}
+
+template <class Loader, int FMT, bool COLSCALE, bool TRANSPOSED>
+__global__ void __launch_bounds__(256)
+cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col_scale,
+            const float *__restrict__ amax, const float *__restrict__ scale_in, int pow2,
+            float *__restrict__ scale_out, uint8_t *__restrict__ dst, uint8_t *__restrict__ dst_t) {
+    __shared__ uint32_t tile[TRANSPOSED ? kTile * kTPitchWords : 1];
+
+    float sigma = 1.0f;
+    bool tensor_scale = false;
+    if (scale_in) { sigma = *scale_in; tensor_scale = true; }
+    else if (amax) { sigma = scale_from_amax(*amax, Fp8Traits<FMT>::fmax, pow2); tensor_scale = true; }
+    if (scale_out && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *scale_out = sigma;
+
+    const int64_t row0 = (int64_t)blockIdx.y * kTile;
+    const int64_t col0 = (int64_t)blockIdx.x * kTile;
+    const int c8 = threadIdx.x & 15;       // which 8-column chunk
+    const int r4 = threadIdx.x >> 4;       // which 4-row group (0..15) inside a 64-row half
+    const int64_t col = col0 + c8 * 8;
+    const bool col_ok = col < cols;
+
+    float cs[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) cs[i] = 1.0f;
+    if (COLSCALE && col_ok) {
+        float4 a = *reinterpret_cast<const float4 *>(col_scale + col);
+        float4 b = *reinterpret_cast<const float4 *>(col_scale + col + 4);
+        cs[0] = a.x; cs[1] = a.y; cs[2] = a.z; cs[3] = a.w;
+        cs[4] = b.x; cs[5] = b.y; cs[6] = b.z; cs[7] = b.w;
+    }
+
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int lr = half * 64 + r4 * 4;             // local row of the 4-row group
+        uint32_t lo[4] = {0, 0, 0, 0}, hi[4] = {0, 0, 0, 0};
+        if (col_ok && row0 + lr < rows) {              // rows is a multiple of 16: the group is all in or all out
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const size_t off = (size_t)(row0 + lr + r) * (size_t)cols + (size_t)col;
+                float v[8];
+                ld.load8(off, v);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    if (COLSCALE) v[i] = __fmul_rn(v[i], cs[i]);
+                    if (tensor_scale) v[i] = __fmul_rn(v[i], sigma);
+                }
+                lo[r] = satcast_pk4<FMT>(v[0], v[1], v[2], v[3]);
+                hi[r] = satcast_pk4<FMT>(v[4], v[5], v[6], v[7]);
+                *reinterpret_cast<uint2 *>(dst + off) = make_uint2(lo[r], hi[r]);
+            }
+        }
+        if (TRANSPOSED) {
+            uint32_t t[4];
+            transpose4x4_bytes(lo[0], lo[1], lo[2], lo[3], t);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) tile[(c8 * 8 + j) * kTPitchWords + (lr >> 2)] = t[j];
+            transpose4x4_bytes(hi[0], hi[1], hi[2], hi[3], t);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) tile[(c8 * 8 + 4 + j) * kTPitchWords + (lr >> 2)] = t[j];
+        }
+    }
+    if (TRANSPOSED) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int q = threadIdx.x + 256 * j;
+            const int c = q >> 3;                      // local column = row of the transposed copy
+            const int rc = q & 7;                      // 16-row chunk
+            if (col0 + c < cols && row0 + rc * 16 < rows) {
+                const uint32_t *src = &tile[c * kTPitchWords + rc * 4];
+                uint4 o = make_uint4(src[0], src[1], src[2], src[3]);
+                *reinterpret_cast<uint4 *>(dst_t + (size_t)(col0 + c) * (size_t)rows + (size_t)(row0 + rc * 16)) = o;
+            }
+        }
+    }
+}
+
+template <class Loader, int FMT>
+static void launch_cast_l(const Loader &ld, const CastArgs &a, hipStream_t st) {
+    dim3 grid((unsigned)((a.cols + kTile - 1) / kTile), (unsigned)((a.rows + kTile - 1) / kTile));
+    const bool cs = a.col_scale != nullptr, tr = a.dst_t != nullptr;
+#define SSG_CAST(CS, TR)                                                                               \
+    hipLaunchKernelGGL((cast_kernel<Loader, FMT, CS, TR>), grid, dim3(256), 0, st, ld, a.rows, a.cols, \
+                       a.col_scale, a.amax, a.scale_in, a.pow2, a.scale_out, a.dst, a.dst_t)
+    if (cs && tr) SSG_CAST(true, true);
+    else if (cs) SSG_CAST(true, false);
+    else if (tr) SSG_CAST(false, true);
+    else SSG_CAST(false, false);
+#undef SSG_CAST
+}
+
+template <int FMT>
+static void launch_cast_f(const CastArgs &a, hipStream_t st) {
+    switch (a.kind) {
+        case SRC_BF16: launch_cast_l<LoadBf16, FMT>(LoadBf16{(const uint16_t *)a.src}, a, st); break;
+        case SRC_F32: launch_cast_l<LoadF32, FMT>(LoadF32{(const float *)a.src}, a, st); break;
+        case SRC_SWIGLU:
+            launch_cast_l<LoadSwiglu, FMT>(LoadSwiglu{(const uint16_t *)a.src, (const uint16_t *)a.src2}, a, st);
+            break;
+    }
+}
+
+void launch_cast(const CastArgs &a, hipStream_t st) {
+    if (a.rows == 0 || a.cols == 0) return;
+    if (a.fmt == kE4M3) launch_cast_f<kE4M3>(a, st);
+    else launch_cast_f<kE5M2>(a, st);
+}
+
+// ------------------------------------------------------------------ per-column amax
+// Grid (cols/128, rows/512).  A thread keeps 8 running column maxima over its
+// share of the slab's rows; the 16 row groups of a workgroup meet in LDS and
+// one atomic per column goes to memory.
+constexpr int kSlabRows = 512;
+
+template <class Loader>
+__global__ void __launch_bounds__(256)
+col_amax_kernel(Loader ld, int64_t rows, int64_t cols, uint32_t *__restrict__ camax_bits) {
+    __shared__ uint32_t cmax[kTile];
+    if (threadIdx.x < kTile) cmax[threadIdx.x] = 0;
+    __syncthreads();
+    const int c8 = threadIdx.x & 15, rg = threadIdx.x >> 4;
+    const int64_t col = (int64_t)blockIdx.x * kTile + c8 * 8;
+    const int64_t row0 = (int64_t)blockIdx.y * kSlabRows;
+    const int64_t row1 = row0 + kSlabRows < rows ? row0 + kSlabRows : rows;
+    if (col < cols) {
+        uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int64_t r = row0 + rg; r < row1; r += 16) {
+            float v[8];
+            ld.load8((size_t)r * (size_t)cols + (size_t)col, v);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                uint32_t b = abs_bits_ignore_nan(v[i]);
+                m[i] = m[i] > b ? m[i] : b;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (m[i]) atomicMax(&cmax[c8 * 8 + i], m[i]);
+    }
+    __syncthreads();
+    if (threadIdx.x < kTile) {
+        const int64_t c = (int64_t)blockIdx.x * kTile + threadIdx.x;
+        if (c < cols && cmax[threadIdx.x]) atomicMax(&camax_bits[c], cmax[threadIdx.x]);
+    }
+}
+
+void launch_col_amax(const void *src, const void *src2, SrcKind kind, int64_t rows, int64_t cols,
+                     uint32_t *camax_bits, hipStream_t st) {
+    if (rows == 0 || cols == 0) return;
+    dim3 grid((unsigned)((cols + kTile - 1) / kTile), (unsigned)((rows + kSlabRows - 1) / kSlabRows));
+    switch (kind) {
+        case SRC_BF16:
+            hipLaunchKernelGGL(col_amax_kernel<LoadBf16>, grid, dim3(256), 0, st, LoadBf16{(const uint16_t *)src},
+                               rows, cols, camax_bits);
+            break;
+        case SRC_F32:
+            hipLaunchKernelGGL(col_amax_kernel<LoadF32>, grid, dim3(256), 0, st, LoadF32{(const float *)src},
+                               rows, cols, camax_bits);
+            break;
+        case SRC_SWIGLU:
+            hipLaunchKernelGGL(col_amax_kernel<LoadSwiglu>, grid, dim3(256), 0, st,
+                               LoadSwiglu{(const uint16_t *)src, (const uint16_t *)src2}, rows, cols, camax_bits);
+            break;
+    }
+}
+
+// ------------------------------------------------------------------ per-channel factors
+// Smooth-SwiGLU (Section 4.4): s_i = fl32(448 / a_i), sinv_i = fl32(a_i / 448),
+// both 1 for an all-zero channel.  The range of s^-1 * w3 needs no pass over
+// W3: rounding is monotone, so max_j fl32(|w_ji| * sinv_i) = fl32(max_j |w_ji| * sinv_i).
+__global__ void __launch_bounds__(256)
+channel_factors_kernel(const float *__restrict__ h_camax, const float *__restrict__ w3_camax, int64_t f,
+                       int smooth, const uint32_t *__restrict__ hmax_bits, float *__restrict__ s,
+                       float *__restrict__ sinv, uint32_t *__restrict__ amax_w3s_bits) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    uint32_t wbits = 0;
+    if (i < f) {
+        float si, sv;
+        if (smooth) {
+            const float a = h_camax[i];
+            si = scale_from_amax(a, 448.0f, 0);
+            sv = a > 0.0f ? __fdiv_rn(a, 448.0f) : 1.0f;
+        } else {
+            si = scale_from_amax(__uint_as_float(*hmax_bits), 448.0f, 0);
+            sv = 1.0f;
+        }
+        s[i] = si;
+        sinv[i] = sv;
+        wbits = abs_bits_ignore_nan(__fmul_rn(w3_camax[i], sv));
+    }
+    wbits = wave_max_u32(wbits);
+    if ((threadIdx.x & 63) == 0 && wbits) atomicMax(amax_w3s_bits, wbits);
+}
+
+__global__ void __launch_bounds__(256)
+vec_max_kernel(const float *__restrict__ v, int64_t n, uint32_t *__restrict__ out_bits) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    uint32_t b = i < n ? abs_bits_ignore_nan(v[i]) : 0u;
+    b = wave_max_u32(b);
+    if ((threadIdx.x & 63) == 0 && b) atomicMax(out_bits, b);
+}
+
+void launch_channel_factors(const float *h_camax, const float *w3_camax, int64_t f, int smooth, float *s,
+                            float *sinv, uint32_t *amax_w3s_bits, uint32_t *hmax_bits, hipStream_t st) {
+    const unsigned blocks = (unsigned)((f + 255) / 256);
+    if (!smooth)
+        hipLaunchKernelGGL(vec_max_kernel, dim3(blocks), dim3(256), 0, st, h_camax, f, hmax_bits);
+    hipLaunchKernelGGL(channel_factors_kernel, dim3(blocks), dim3(256), 0, st, h_camax, w3_camax, f, smooth,
+                       hmax_bits, s, sinv, amax_w3s_bits);
+}
+
+__global__ void __launch_bounds__(256)
+fold_range_kernel(const float *__restrict__ w3_camax, const float *__restrict__ sinv, int64_t f,
+                  uint32_t *__restrict__ amax_bits) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    uint32_t b = i < f ? abs_bits_ignore_nan(__fmul_rn(w3_camax[i], sinv[i])) : 0u;
+    b = wave_max_u32(b);
+    if ((threadIdx.x & 63) == 0 && b) atomicMax(amax_bits, b);
+}
+void launch_fold_range(const float *w3_camax, const float *sinv, int64_t f, uint32_t *amax_bits, hipStream_t st) {
+    hipLaunchKernelGGL(fold_range_kernel, dim3((unsigned)((f + 255) / 256)), dim3(256), 0, st, w3_camax, sinv, f,
+                       amax_bits);
+}
+
+// ------------------------------------------------------------------ SwiGLU product (tests)
+__global__ void __launch_bounds__(256)
+swiglu_kernel(LoadSwiglu ld, size_t n8, float *__restrict__ h) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n8) return;
+    float v[8];
+    ld.load8(i * 8, v);
+    *reinterpret_cast<float4 *>(h + i * 8) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4 *>(h + i * 8 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+void launch_swiglu(const void *U, const void *G, int64_t n, float *h, hipStream_t st) {
+    const size_t n8 = (size_t)n / 8;
+    if (n8 == 0) return;
+    hipLaunchKernelGGL(swiglu_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, st,
+                       LoadSwiglu{(const uint16_t *)U, (const uint16_t *)G}, n8, h);
+}
+
+}  // namespace ssg

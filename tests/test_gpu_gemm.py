@@ -1,0 +1,77 @@
+"""GPU parity: the FP8 MFMA GEMM against the oracle's fp64 contraction (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fp8, gemm
+
+pytestmark = pytest.mark.gpu
+
+import paper_2409_12517_amd as ssg  # noqa: E402
+import gpu_util as gu  # noqa: E402
+
+FMT = {ssg.SSG_E4M3: fp8.E4M3, ssg.SSG_E5M2: fp8.E5M2}
+
+
+def _codes(rng, fmt, shape, gaussian=True):
+    """Codes with the value distribution of a per-tensor-scaled Gaussian tensor (or uniform over all finite codes)."""
+    f = FMT[fmt]
+    if gaussian:
+        v = rng.standard_normal(shape).astype(np.float32)
+        v = v * np.float32(fp8.max_finite(f) / np.abs(v).max())
+        return fp8.satcast(v, f)
+    c = rng.integers(0, f.max_code + 1, size=shape).astype(np.uint8)
+    return c | (rng.integers(0, 2, size=shape).astype(np.uint8) << 7)
+
+
+def _run(a, a_fmt, b, sa, sb, c_dtype):
+    M, K = a.shape
+    N = b.shape[0]
+    A, B = gu.dev(torch.from_numpy(a)), gu.dev(torch.from_numpy(b))
+    sa_t = None if sa is None else torch.tensor([sa], dtype=torch.float32, device=gu.DEV)
+    sb_t = None if sb is None else torch.tensor([sb], dtype=torch.float32, device=gu.DEV)
+    C = torch.empty(M, N, dtype=torch.float32 if c_dtype == ssg.SSG_F32 else torch.bfloat16, device=gu.DEV)
+    ssg.ssg_gemm_fp8(A, a_fmt, B, ssg.SSG_E4M3, M, N, K, sa_t, sb_t, C, c_dtype)
+    torch.cuda.synchronize()
+    return gu.f32(C)
+
+
+@pytest.mark.parametrize("a_fmt", [ssg.SSG_E4M3, ssg.SSG_E5M2])
+def test_tiny_gemm_against_exact_integer_sum(a_fmt):
+    """Values restricted to a narrow exponent range make every fp32 partial sum exact: the
+    result must equal the integer brute force bit for bit (checks operand layouts and indexing)."""
+    rng = np.random.default_rng(1)
+    M, N, K = 48, 32, 80
+    fa = FMT[a_fmt]
+    ea = rng.integers(fa.bias - 2, fa.bias + 3, size=(M, K))
+    a = ((ea << fa.man_bits) | rng.integers(0, 1 << fa.man_bits, size=(M, K)) | (rng.integers(0, 2, size=(M, K)) << 7)).astype(np.uint8)
+    eb = rng.integers(5, 10, size=(N, K))
+    b = ((eb << 3) | rng.integers(0, 8, size=(N, K)) | (rng.integers(0, 2, size=(N, K)) << 7)).astype(np.uint8)
+    got = _run(a, a_fmt, b, None, None, ssg.SSG_F32)
+    exact = gemm.matmul_nt_exact(a, fa, b, fp8.E4M3)
+    ref = np.array([[float(v) for v in row] for row in exact])
+    assert np.array_equal(got.astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("a_fmt", [ssg.SSG_E4M3, ssg.SSG_E5M2])
+@pytest.mark.parametrize("M,N,K", [(256, 256, 128), (256, 688, 256), (688, 256, 256), (256, 256, 688),
+                                   (16, 16, 16), (272, 528, 400), (1024, 768, 2048)])
+@pytest.mark.parametrize("c_dtype", [ssg.SSG_F32, ssg.SSG_BF16])
+def test_gemm_against_fp64_oracle(a_fmt, M, N, K, c_dtype):
+    rng = np.random.default_rng(M + 3 * N + 7 * K + a_fmt)
+    a, b = _codes(rng, a_fmt, (M, K)), _codes(rng, ssg.SSG_E4M3, (N, K))
+    sa, sb = np.float32(37.5), np.float32(0.8125)
+    got = _run(a, a_fmt, b, sa, sb, c_dtype)
+    ref = gemm.matmul_nt(a, FMT[a_fmt], b, fp8.E4M3) / (float(sa) * float(sb))
+    gu.assert_close_gemm(got, ref, c_dtype == ssg.SSG_BF16, f"gemm {M}x{N}x{K}")
+
+
+def test_gemm_uniform_codes_full_dynamic_range():
+    """Codes uniform over the whole format (11+ binades in one dot product): the matrix core aligns
+    products before adding, so this is the hardest case for the stated tolerance."""
+    rng = np.random.default_rng(3)
+    M, N, K = 256, 256, 512
+    a, b = _codes(rng, ssg.SSG_E5M2, (M, K), gaussian=False), _codes(rng, ssg.SSG_E4M3, (N, K), gaussian=False)
+    got = _run(a, ssg.SSG_E5M2, b, None, None, ssg.SSG_F32)
+    ref = gemm.matmul_nt(a, fp8.E5M2, b, fp8.E4M3)
+    gu.assert_close_gemm(got, ref, False, "uniform codes")

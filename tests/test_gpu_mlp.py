@@ -1,0 +1,181 @@
+"""GPU parity: the whole block, forward and backward, against the oracle (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import fp8, mlp, quant
+
+pytestmark = pytest.mark.gpu
+
+import paper_2409_12517_amd as ssg  # noqa: E402
+import gpu_util as gu  # noqa: E402
+
+
+class Block:
+    """Device buffers of one forward+backward call and typed views into saved/workspace."""
+
+    def __init__(self, inp, smooth=1, y_dtype=None, dw_dtype=None, rnd=None):
+        self.T, self.d = inp["x"].shape
+        self.f = inp["W1"].shape[0]
+        self.desc = ssg.make_desc(self.T, self.d, self.f, smooth=smooth,
+                                  rnd=ssg.SSG_ROUND_EXACT_DIV if rnd is None else rnd,
+                                  y_dtype=ssg.SSG_BF16 if y_dtype is None else y_dtype,
+                                  dw_dtype=ssg.SSG_F32 if dw_dtype is None else dw_dtype)
+        self.x, self.W1, self.W2, self.W3 = (gu.dev(inp[k]) for k in ("x", "W1", "W2", "W3"))
+        self.dY = gu.dev(inp["dY"]) if inp.get("dY") is not None else None
+        ydt = torch.bfloat16 if self.desc.y_dtype == ssg.SSG_BF16 else torch.float32
+        wdt = torch.bfloat16 if self.desc.dw_dtype == ssg.SSG_BF16 else torch.float32
+        self.y = torch.empty(self.T, self.d, dtype=ydt, device=gu.DEV)
+        self.saved = torch.empty(ssg.ssg_mlp_saved_bytes(self.desc), dtype=torch.uint8, device=gu.DEV)
+        self.work = torch.empty(ssg.ssg_mlp_workspace_bytes(self.desc), dtype=torch.uint8, device=gu.DEV)
+        self.dx = torch.empty(self.T, self.d, dtype=ydt, device=gu.DEV)
+        self.dW1 = torch.empty(self.f, self.d, dtype=wdt, device=gu.DEV)
+        self.dW2 = torch.empty(self.f, self.d, dtype=wdt, device=gu.DEV)
+        self.dW3 = torch.empty(self.d, self.f, dtype=wdt, device=gu.DEV)
+
+    def fwd(self):
+        ssg.ssg_mlp_fwd(self.desc, self.x, self.W1, self.W2, self.W3, self.y, self.saved)
+        torch.cuda.synchronize()
+
+    def bwd(self):
+        ssg.ssg_mlp_bwd(self.desc, self.dY, self.saved, self.dx, self.dW1, self.dW2, self.dW3, self.work)
+        torch.cuda.synchronize()
+
+    def sv(self, name, shape, dtype):
+        v = ssg.ssg_mlp_view_saved(self.desc, self.saved)
+        return ssg.view_tensor(self.saved, self.saved.data_ptr(), getattr(v, name), shape, dtype)
+
+    def wv(self, name, shape, dtype):
+        v = ssg.ssg_mlp_view_workspace(self.desc, self.work)
+        return ssg.view_tensor(self.work, self.work.data_ptr(), getattr(v, name), shape, dtype)
+
+
+def _np_inputs(inp):
+    return {k: synth.bf16_to_f32_numpy(v) for k, v in inp.items() if isinstance(v, torch.Tensor) and v.dtype == torch.bfloat16}
+
+
+def check_forward(blk: Block, npi, smooth=1):
+    """Tiered comparison of one forward call with the oracle."""
+    T, d, f = blk.T, blk.d, blk.f
+    ref = mlp.forward(npi["x"], npi["W1"], npi["W2"], npi["W3"], smooth=bool(smooth))
+    sc = gu.f32(blk.sv("scales", (8,), torch.float32))
+    # tier 1: quantized inputs and their scales are bit-exact
+    assert sc[0] == ref.sx and sc[1] == ref.sw1 and sc[2] == ref.sw2
+    x_q = gu.u8(blk.sv("x_q", (T, d), torch.uint8))
+    assert np.array_equal(x_q, ref.x_q) and np.array_equal(gu.u8(blk.sv("x_qT", (d, T), torch.uint8)), ref.x_q.T)
+    for n, r in (("w1_q", ref.w1_q), ("w2_q", ref.w2_q)):
+        assert np.array_equal(gu.u8(blk.sv(n, (f, d), torch.uint8)), r)
+        assert np.array_equal(gu.u8(blk.sv(n + "T", (d, f), torch.uint8)), r.T)
+    # tier 2: U, G (fp32 accumulation vs fp64) within the GEMM bar
+    U = gu.f32(blk.sv("U", (T, f), torch.bfloat16)); G = gu.f32(blk.sv("G", (T, f), torch.bfloat16))
+    gu.assert_close_gemm(U, ref.U, True, "U"); gu.assert_close_gemm(G, ref.G, True, "G")
+    # tier 3: everything downstream of the GPU's own U, G is bit-exact given the GPU's fp32 h
+    h = gu.empty_f32(T, f)
+    ssg.ssg_swiglu(blk.sv("U", (T, f), torch.bfloat16), blk.sv("G", (T, f), torch.bfloat16), T, f, h)
+    torch.cuda.synchronize()
+    h_np = gu.f32(h)
+    from oracle import swiglu
+    h_ref = swiglu.swiglu(U, G)
+    assert np.all(np.abs(h_np - h_ref) <= 4 * 2.0 ** -23 * np.abs(h_ref) + 1e-37)
+    if smooth:
+        a, s_ref, sinv_ref = mlp.channel_scales(h_np)
+        hq_ref = quant.cast_with_scale(h_np, s_ref[None, :], fp8.E4M3)
+        w3q_ref, sw3_ref, amax_w3s = mlp.fold_w3(npi["W3"], sinv_ref)
+    else:
+        a = np.abs(h_np).max(axis=0)
+        hq_ref, sh, _ = quant.quantize_per_tensor(h_np, fp8.E4M3)
+        s_ref, sinv_ref = np.full(f, sh, np.float32), np.ones(f, np.float32)
+        w3q_ref, sw3_ref, amax_w3s = quant.quantize_per_tensor(npi["W3"], fp8.E4M3)
+    assert np.array_equal(gu.f32(blk.sv("h_camax", (f,), torch.float32)), a)
+    assert np.array_equal(gu.f32(blk.sv("s", (f,), torch.float32)), s_ref)
+    assert np.array_equal(gu.f32(blk.sv("sinv", (f,), torch.float32)), sinv_ref)
+    h_q = gu.u8(blk.sv("h_q", (T, f), torch.uint8))
+    assert np.array_equal(h_q, hq_ref) and np.array_equal(gu.u8(blk.sv("h_qT", (f, T), torch.uint8)), hq_ref.T)
+    assert sc[7] == amax_w3s and sc[3] == sw3_ref
+    w3_q = gu.u8(blk.sv("w3_q", (d, f), torch.uint8))
+    assert np.array_equal(w3_q, w3q_ref) and np.array_equal(gu.u8(blk.sv("w3_qT", (f, d), torch.uint8)), w3q_ref.T)
+    # tier 4: the output against the oracle end to end
+    gu.assert_close_gemm(gu.f32(blk.y), ref.Y, blk.desc.y_dtype == ssg.SSG_BF16, "Y")
+    # the factors follow the oracle's up to the bf16 step of the U or G that sets a channel's maximum
+    if smooth:
+        assert np.all(np.abs(s_ref / ref.s - 1) < 2.0 ** -5)
+    return ref, dict(U=U, G=G, h_q=h_q, w3_q=w3_q, x_q=x_q, s=s_ref, sinv=sinv_ref, sw3=sw3_ref, sc=sc)
+
+
+def check_backward(blk: Block, npi, ref_fw, g, smooth=1):
+    T, d, f = blk.T, blk.d, blk.f
+    ref = mlp.backward(ref_fw, npi["dY"])
+    wsc = gu.f32(blk.wv("scales", (8,), torch.float32))
+    dy_q = gu.u8(blk.wv("dy_q", (T, d), torch.uint8))
+    assert wsc[0] == ref.sdy and np.array_equal(dy_q, ref.dy_q)
+    assert np.array_equal(gu.u8(blk.wv("dy_qT", (d, T), torch.uint8)), ref.dy_q.T)
+    dU = gu.f32(blk.wv("dU", (T, f), torch.bfloat16)); dG = gu.f32(blk.wv("dG", (T, f), torch.bfloat16))
+    # dU, dG, and the quantization of the GPU's own dU, dG (bit-exact)
+    gu.assert_close_gemm(dU, ref.dU, True, "dU"); gu.assert_close_gemm(dG, ref.dG, True, "dG")
+    duq_ref, sdu_ref, amax_du = quant.quantize_per_tensor(dU, fp8.E5M2)
+    dgq_ref, sdg_ref, amax_dg = quant.quantize_per_tensor(dG, fp8.E5M2)
+    assert wsc[4] == amax_du and wsc[5] == amax_dg and wsc[1] == sdu_ref and wsc[2] == sdg_ref
+    assert np.array_equal(gu.u8(blk.wv("du_q", (T, f), torch.uint8)), duq_ref)
+    assert np.array_equal(gu.u8(blk.wv("du_qT", (f, T), torch.uint8)), duq_ref.T)
+    assert np.array_equal(gu.u8(blk.wv("dg_q", (T, f), torch.uint8)), dgq_ref)
+    assert np.array_equal(gu.u8(blk.wv("dg_qT", (f, T), torch.uint8)), dgq_ref.T)
+    bf_y = blk.desc.y_dtype == ssg.SSG_BF16
+    bf_w = blk.desc.dw_dtype == ssg.SSG_BF16
+    gu.assert_close_gemm(gu.f32(blk.dx), ref.dX, bf_y, "dX")
+    gu.assert_close_gemm(gu.f32(blk.dW1), ref.dW1, bf_w, "dW1")
+    gu.assert_close_gemm(gu.f32(blk.dW2), ref.dW2, bf_w, "dW2")
+    gu.assert_close_gemm(gu.f32(blk.dW3), ref.dW3, bf_w, "dW3")
+    return ref
+
+
+@pytest.mark.parametrize("smooth", [1, 0])
+def test_tiny_config_forward_backward(smooth):
+    inp = synth.make_config("tiny")
+    npi = _np_inputs(inp)
+    blk = Block(inp, smooth=smooth)
+    blk.fwd()
+    ref_fw, g = check_forward(blk, npi, smooth)
+    blk.bwd()
+    check_backward(blk, npi, ref_fw, g, smooth)
+
+
+@pytest.mark.parametrize("T,d,f,aligned", [(528, 400, 1040, 0), (1024, 512, 1536, 6), (16, 16, 16, 0)])
+def test_ragged_shapes_and_outlier_channels(T, d, f, aligned):
+    inp = synth.make_inputs(T, d, f, seed=T + d + f, aligned_channels=aligned)
+    npi = _np_inputs(inp)
+    blk = Block(inp)
+    blk.fwd()
+    ref_fw, g = check_forward(blk, npi)
+    blk.bwd()
+    check_backward(blk, npi, ref_fw, g)
+
+
+def test_fp32_outputs_bf16_weight_grads_and_pow2_scales():
+    inp = synth.make_inputs(256, 256, 512, seed=21)
+    npi = _np_inputs(inp)
+    blk = Block(inp, y_dtype=ssg.SSG_F32, dw_dtype=ssg.SSG_BF16)
+    blk.fwd(); blk.bwd()
+    ref_fw = mlp.forward(npi["x"], npi["W1"], npi["W2"], npi["W3"], y_dtype="f32")
+    ref_bw = mlp.backward(ref_fw, npi["dY"], dx_dtype="f32", dw_dtype="bf16")
+    gu.assert_close_gemm(gu.f32(blk.y), ref_fw.Y, False, "Y f32")
+    gu.assert_close_gemm(gu.f32(blk.dx), ref_bw.dX, False, "dX f32")
+    gu.assert_close_gemm(gu.f32(blk.dW3), ref_bw.dW3, True, "dW3 bf16")
+    blk2 = Block(inp, rnd=ssg.SSG_ROUND_POW2)
+    blk2.fwd()
+    sc = gu.f32(blk2.sv("scales", (8,), torch.float32))
+    assert sc[0] == quant.scale_from_amax(quant.amax(npi["x"]), fp8.E4M3, pow2=True)
+    assert np.array_equal(gu.u8(blk2.sv("x_q", (256, 256), torch.uint8)),
+                          quant.quantize_per_tensor(npi["x"], fp8.E4M3, pow2=True)[0])
+
+
+def test_two_calls_give_identical_bytes():
+    """Atomic maxima are order independent, so the block is deterministic run to run."""
+    inp = synth.make_inputs(512, 256, 688, seed=31)
+    blk = Block(inp)
+    blk.fwd(); blk.bwd()
+    first = [t.clone() for t in (blk.y, blk.dx, blk.dW1, blk.dW2, blk.dW3, blk.saved)]
+    blk.fwd(); blk.bwd()
+    torch.cuda.synchronize()
+    for a, b in zip(first, (blk.y, blk.dx, blk.dW1, blk.dW2, blk.dW3, blk.saved)):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))

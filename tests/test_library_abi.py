@@ -1,0 +1,71 @@
+"""CPU checks of the boundary: the C-ABI library loads and exports every symbol
+that include/ssg.h declares, and host-side validation rejects bad arguments
+without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ssg.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ssg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    import paper_2409_12517_amd as ssg
+    lib = ctypes.CDLL(ssg.LIB_PATH)
+    names = _declared_symbols()
+    assert "ssg_quantize" in names and "ssg_mlp_fwd" in names and "ssg_mlp_bwd" in names
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in ssg.h but not exported"
+    assert sorted(ssg.EXPORTS) == names
+    assert "gfx950" in ssg.ssg_version()
+
+
+def test_sizes_and_descriptor_validation():
+    import paper_2409_12517_amd as ssg
+    d = ssg.make_desc(256, 256, 688)
+    saved, work = ssg.ssg_mlp_saved_bytes(d), ssg.ssg_mlp_workspace_bytes(d)
+    T, dm, f = 256, 256, 688
+    assert saved >= 2 * T * dm + 4 * f * dm + 4 * T * f + 2 * T * f + 2 * f * dm
+    assert work >= 2 * T * dm + 4 * T * f + 4 * T * f
+    assert saved % 256 == 0 and work % 256 == 0
+    assert ssg.ssg_mlp_saved_bytes(ssg.make_desc(250, 256, 688)) == 0        # T not a multiple of 16
+    assert "multiples of 16" in ssg.ssg_last_error()
+    assert ssg.ssg_mlp_saved_bytes(ssg.make_desc(256, 256, 688, smooth=3)) == 0
+    assert ssg.ssg_mlp_workspace_bytes(ssg.make_desc(1 << 20, 1 << 20, 16)) == 0  # too many elements
+
+
+def test_entry_points_reject_bad_arguments_before_launching():
+    import paper_2409_12517_amd as ssg
+    # stream value is irrelevant: validation fails first and nothing is enqueued
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_quantize(0, ssg.SSG_BF16, 16, 16, ssg.SSG_E4M3, ssg.SSG_SCALE_CURRENT, ssg.SSG_ROUND_EXACT_DIV,
+                         0, 0, 0, 0, stream=0)
+    assert e.value.status == ssg.SSG_ERR_ARG
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_quantize(256, ssg.SSG_BF16, 24, 16, ssg.SSG_E4M3, ssg.SSG_SCALE_GIVEN, ssg.SSG_ROUND_EXACT_DIV,
+                         256, 0, 256, 0, stream=0)
+    assert e.value.status == ssg.SSG_ERR_SHAPE
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_quantize(264, ssg.SSG_BF16, 16, 16, ssg.SSG_E4M3, ssg.SSG_SCALE_GIVEN, ssg.SSG_ROUND_EXACT_DIV,
+                         256, 0, 256, 0, stream=0)                       # misaligned src
+    assert e.value.status == ssg.SSG_ERR_ARG and "aligned" in str(e.value)
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_gemm_fp8(256, ssg.SSG_E4M3, 256, ssg.SSG_E5M2, 16, 16, 16, 0, 0, 256, ssg.SSG_F32, stream=0)
+    assert e.value.status == ssg.SSG_ERR_UNSUPPORTED
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_gemm_fp8(256, ssg.SSG_E4M3, 256, ssg.SSG_E4M3, 16, 20, 16, 0, 0, 256, ssg.SSG_F32, stream=0)
+    assert e.value.status == ssg.SSG_ERR_SHAPE
+    d = ssg.make_desc(256, 256, 688)
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_mlp_fwd(d, 256, 256, 256, 0, 256, 256, stream=0)          # W3 NULL
+    assert e.value.status == ssg.SSG_ERR_ARG and "W3" in str(e.value)
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_mlp_bwd(ssg.make_desc(256, 256, 100), 256, 256, 256, 256, 256, 256, 256, stream=0)
+    assert e.value.status == ssg.SSG_ERR_SHAPE
