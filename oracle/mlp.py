@@ -185,8 +185,14 @@ class Backward:
     dW3: np.ndarray = field(default=None)
 
 
-def backward(fw: Forward, dY, *, dx_dtype: str = "bf16", dw_dtype: str = "f32") -> Backward:
-    """Gradients of sum(Y * dY) with respect to x, W1, W2, W3."""
+def backward(fw: Forward, dY, *, dx_dtype: str = "bf16", dw_dtype: str = "f32",
+             stored_dU_dG=None) -> Backward:
+    """Gradients of sum(Y * dY) with respect to x, W1, W2, W3.
+
+    ``stored_dU_dG`` = (dU, dG), bf16-valued arrays: continue from step 10 with
+    these stored activations' gradients instead of the ones step 9 produced.
+    Tests use it to check the later steps on identical inputs when an earlier
+    step differed from another implementation by a bf16 rounding."""
     bw = Backward()
     if not fw.quantized:
         dY64 = np.asarray(dY, np.float64)
@@ -216,6 +222,8 @@ def backward(fw: Forward, dY, *, dx_dtype: str = "bf16", dw_dtype: str = "f32") 
     # 9. through the SwiGLU product, from the stored bf16 U and G
     dU, dG = swiglu.swiglu_grads(fw.U, fw.G, bw.dH)
     bw.dU, bw.dG = round_bf16(dU), round_bf16(dG)
+    if stored_dU_dG is not None:
+        bw.dU, bw.dG = (np.asarray(v, np.float64) for v in stored_dU_dG)
     # 10. two tensors, two E5M2 scales
     bw.du_q, bw.sdu, _ = quant.quantize_per_tensor(bw.dU, fp8.E5M2)
     bw.dg_q, bw.sdg, _ = quant.quantize_per_tensor(bw.dG, fp8.E5M2)

@@ -64,8 +64,11 @@ __device__ __forceinline__ uint32_t satcast_pk4(float a, float b, float c, float
 // Every operation is a single rounded fp32 operation in a fixed order so that
 // the GEMM epilogue and the stand-alone pass produce identical bits.
 __device__ __forceinline__ float sigmoid_f32(float g) {
-    float e = expf(-g);
-    return __fdiv_rn(1.0f, __fadd_rn(1.0f, e));
+    // sigma(g) = 1/(1+e^-g) = e^g/(1+e^g): evaluate with t = e^-|g| <= 1 so that nothing
+    // overflows for strongly negative g (the large-|g| regime is the one the method is about).
+    const float t = expf(-fabsf(g));
+    const float r = __fdiv_rn(1.0f, __fadd_rn(1.0f, t));
+    return g >= 0.0f ? r : __fmul_rn(t, r);
 }
 __device__ __forceinline__ float swiglu_f32(float u, float g) {
     float sw = __fmul_rn(g, sigmoid_f32(g));

@@ -38,15 +38,19 @@ def _run(a, a_fmt, b, sa, sb, c_dtype):
 
 @pytest.mark.parametrize("a_fmt", [ssg.SSG_E4M3, ssg.SSG_E5M2])
 def test_tiny_gemm_against_exact_integer_sum(a_fmt):
-    """Values restricted to a narrow exponent range make every fp32 partial sum exact: the
-    result must equal the integer brute force bit for bit (checks operand layouts and indexing)."""
+    """Operands confined to one binade (plus sign and zeros): every product has the same few
+    fractional bits, so neither the matrix core's product alignment nor the fp32 sums round, and
+    the result must equal the integer brute force bit for bit (checks operand layouts, indexing
+    and the ragged-tile handling)."""
     rng = np.random.default_rng(1)
     M, N, K = 48, 32, 80
     fa = FMT[a_fmt]
-    ea = rng.integers(fa.bias - 2, fa.bias + 3, size=(M, K))
+    ea = np.full((M, K), fa.bias)
     a = ((ea << fa.man_bits) | rng.integers(0, 1 << fa.man_bits, size=(M, K)) | (rng.integers(0, 2, size=(M, K)) << 7)).astype(np.uint8)
-    eb = rng.integers(5, 10, size=(N, K))
+    eb = np.full((N, K), 7)
     b = ((eb << 3) | rng.integers(0, 8, size=(N, K)) | (rng.integers(0, 2, size=(N, K)) << 7)).astype(np.uint8)
+    a[rng.random((M, K)) < 0.1] = 0
+    b[rng.random((N, K)) < 0.1] = 0x80
     got = _run(a, a_fmt, b, None, None, ssg.SSG_F32)
     exact = gemm.matmul_nt_exact(a, fa, b, fp8.E4M3)
     ref = np.array([[float(v) for v in row] for row in exact])

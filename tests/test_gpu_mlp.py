@@ -5,6 +5,7 @@ import torch
 
 import synth
 from oracle import fp8, mlp, quant
+from oracle import gemm as fp8_gemm
 
 pytestmark = pytest.mark.gpu
 
@@ -95,37 +96,58 @@ def check_forward(blk: Block, npi, smooth=1):
     assert sc[7] == amax_w3s and sc[3] == sw3_ref
     w3_q = gu.u8(blk.sv("w3_q", (d, f), torch.uint8))
     assert np.array_equal(w3_q, w3q_ref) and np.array_equal(gu.u8(blk.sv("w3_qT", (f, d), torch.uint8)), w3q_ref.T)
-    # tier 4: the output against the oracle end to end
-    gu.assert_close_gemm(gu.f32(blk.y), ref.Y, blk.desc.y_dtype == ssg.SSG_BF16, "Y")
-    # the factors follow the oracle's up to the bf16 step of the U or G that sets a channel's maximum
+    # tier 4: the last GEMM on identical inputs -- the oracle continued from the GPU's own (verified) operands
+    y_cont = fp8_gemm.matmul_nt(h_q, fp8.E4M3, w3_q, fp8.E4M3) / (float(sw3_ref) * (1.0 if smooth else float(s_ref[0])))
+    bf_y = blk.desc.y_dtype == ssg.SSG_BF16
+    gu.assert_close_gemm(gu.f32(blk.y), mlp.round_bf16(y_cont) if bf_y else y_cont, bf_y, "Y (continued)")
+    # tier 5: end to end against the oracle.  A bf16 rounding of U or G that differs (fp32 vs fp64
+    # accumulation) can move a channel's maximum, hence its factor and many of its FP8 codes, so the
+    # two outputs differ by FP8 decision noise, not by the GEMM bar; bound it normwise.
+    rel = np.linalg.norm(gu.f32(blk.y) - ref.Y) / np.linalg.norm(ref.Y)
+    assert rel < 1e-2, rel
     if smooth:
         assert np.all(np.abs(s_ref / ref.s - 1) < 2.0 ** -5)
-    return ref, dict(U=U, G=G, h_q=h_q, w3_q=w3_q, x_q=x_q, s=s_ref, sinv=sinv_ref, sw3=sw3_ref, sc=sc)
+    # the oracle's forward state rebuilt from the GPU's stored tensors, for the backward checks
+    fw_gpu = mlp.Forward(quantized=True, smooth=bool(smooth), x_q=x_q, sx=np.float32(sc[0]),
+                         w1_q=gu.u8(blk.sv("w1_q", (f, d), torch.uint8)), sw1=np.float32(sc[1]),
+                         w2_q=gu.u8(blk.sv("w2_q", (f, d), torch.uint8)), sw2=np.float32(sc[2]),
+                         w3_q=w3_q, sw3=np.float32(sw3_ref), h_q=h_q, sh=np.float32(s_ref[0]),
+                         U=U.astype(np.float64), G=G.astype(np.float64), h=h_np, a=a, s=s_ref, sinv=sinv_ref)
+    return ref, fw_gpu
 
 
-def check_backward(blk: Block, npi, ref_fw, g, smooth=1):
+def check_backward(blk: Block, npi, ref_fw, fw_gpu, smooth=1):
     T, d, f = blk.T, blk.d, blk.f
-    ref = mlp.backward(ref_fw, npi["dY"])
-    wsc = gu.f32(blk.wv("scales", (8,), torch.float32))
-    dy_q = gu.u8(blk.wv("dy_q", (T, d), torch.uint8))
-    assert wsc[0] == ref.sdy and np.array_equal(dy_q, ref.dy_q)
-    assert np.array_equal(gu.u8(blk.wv("dy_qT", (d, T), torch.uint8)), ref.dy_q.T)
-    dU = gu.f32(blk.wv("dU", (T, f), torch.bfloat16)); dG = gu.f32(blk.wv("dG", (T, f), torch.bfloat16))
-    # dU, dG, and the quantization of the GPU's own dU, dG (bit-exact)
-    gu.assert_close_gemm(dU, ref.dU, True, "dU"); gu.assert_close_gemm(dG, ref.dG, True, "dG")
-    duq_ref, sdu_ref, amax_du = quant.quantize_per_tensor(dU, fp8.E5M2)
-    dgq_ref, sdg_ref, amax_dg = quant.quantize_per_tensor(dG, fp8.E5M2)
-    assert wsc[4] == amax_du and wsc[5] == amax_dg and wsc[1] == sdu_ref and wsc[2] == sdg_ref
-    assert np.array_equal(gu.u8(blk.wv("du_q", (T, f), torch.uint8)), duq_ref)
-    assert np.array_equal(gu.u8(blk.wv("du_qT", (f, T), torch.uint8)), duq_ref.T)
-    assert np.array_equal(gu.u8(blk.wv("dg_q", (T, f), torch.uint8)), dgq_ref)
-    assert np.array_equal(gu.u8(blk.wv("dg_qT", (f, T), torch.uint8)), dgq_ref.T)
     bf_y = blk.desc.y_dtype == ssg.SSG_BF16
     bf_w = blk.desc.dw_dtype == ssg.SSG_BF16
-    gu.assert_close_gemm(gu.f32(blk.dx), ref.dX, bf_y, "dX")
-    gu.assert_close_gemm(gu.f32(blk.dW1), ref.dW1, bf_w, "dW1")
-    gu.assert_close_gemm(gu.f32(blk.dW2), ref.dW2, bf_w, "dW2")
-    gu.assert_close_gemm(gu.f32(blk.dW3), ref.dW3, bf_w, "dW3")
+    ydt, wdt = ("bf16" if bf_y else "f32"), ("bf16" if bf_w else "f32")
+    # stage 1: upstream gradient, bit-exact
+    cont = mlp.backward(fw_gpu, npi["dY"], dx_dtype=ydt, dw_dtype=wdt)
+    wsc = gu.f32(blk.wv("scales", (8,), torch.float32))
+    dy_q = gu.u8(blk.wv("dy_q", (T, d), torch.uint8))
+    assert wsc[0] == cont.sdy and wsc[3] == quant.amax(npi["dY"]) and np.array_equal(dy_q, cont.dy_q)
+    assert np.array_equal(gu.u8(blk.wv("dy_qT", (d, T), torch.uint8)), cont.dy_q.T)
+    # stage 2: dU, dG on identical inputs (one GEMM plus the SwiGLU derivative)
+    dU = gu.f32(blk.wv("dU", (T, f), torch.bfloat16)); dG = gu.f32(blk.wv("dG", (T, f), torch.bfloat16))
+    gu.assert_close_gemm(dU, cont.dU, True, "dU"); gu.assert_close_gemm(dG, cont.dG, True, "dG")
+    # stage 3: quantization of the GPU's own dU, dG, bit-exact
+    cont2 = mlp.backward(fw_gpu, npi["dY"], dx_dtype=ydt, dw_dtype=wdt, stored_dU_dG=(dU, dG))
+    assert wsc[4] == quant.amax(dU) and wsc[5] == quant.amax(dG) and wsc[1] == cont2.sdu and wsc[2] == cont2.sdg
+    assert np.array_equal(gu.u8(blk.wv("du_q", (T, f), torch.uint8)), cont2.du_q)
+    assert np.array_equal(gu.u8(blk.wv("du_qT", (f, T), torch.uint8)), cont2.du_q.T)
+    assert np.array_equal(gu.u8(blk.wv("dg_q", (T, f), torch.uint8)), cont2.dg_q)
+    assert np.array_equal(gu.u8(blk.wv("dg_qT", (f, T), torch.uint8)), cont2.dg_q.T)
+    # stage 4: the four gradient GEMMs on identical inputs
+    gu.assert_close_gemm(gu.f32(blk.dx), cont2.dX, bf_y, "dX")
+    gu.assert_close_gemm(gu.f32(blk.dW1), cont2.dW1, bf_w, "dW1")
+    gu.assert_close_gemm(gu.f32(blk.dW2), cont2.dW2, bf_w, "dW2")
+    gu.assert_close_gemm(gu.f32(blk.dW3), cont2.dW3, bf_w, "dW3")
+    # stage 5: end to end against the oracle, normwise (FP8 decision noise, see check_forward)
+    ref = mlp.backward(ref_fw, npi["dY"], dx_dtype=ydt, dw_dtype=wdt)
+    for name, got in (("dX", blk.dx), ("dW1", blk.dW1), ("dW2", blk.dW2), ("dW3", blk.dW3)):
+        r = getattr(ref, name)
+        rel = np.linalg.norm(gu.f32(got) - r) / np.linalg.norm(r)
+        assert rel < 2e-2, (name, rel)
     return ref
 
 
@@ -156,11 +178,8 @@ def test_fp32_outputs_bf16_weight_grads_and_pow2_scales():
     npi = _np_inputs(inp)
     blk = Block(inp, y_dtype=ssg.SSG_F32, dw_dtype=ssg.SSG_BF16)
     blk.fwd(); blk.bwd()
-    ref_fw = mlp.forward(npi["x"], npi["W1"], npi["W2"], npi["W3"], y_dtype="f32")
-    ref_bw = mlp.backward(ref_fw, npi["dY"], dx_dtype="f32", dw_dtype="bf16")
-    gu.assert_close_gemm(gu.f32(blk.y), ref_fw.Y, False, "Y f32")
-    gu.assert_close_gemm(gu.f32(blk.dx), ref_bw.dX, False, "dX f32")
-    gu.assert_close_gemm(gu.f32(blk.dW3), ref_bw.dW3, True, "dW3 bf16")
+    ref_fw, fw_gpu = check_forward(blk, npi)
+    check_backward(blk, npi, ref_fw, fw_gpu)
     blk2 = Block(inp, rnd=ssg.SSG_ROUND_POW2)
     blk2.fwd()
     sc = gu.f32(blk2.sv("scales", (8,), torch.float32))

@@ -140,7 +140,7 @@ def test_smooth_swiglu_quantize_bit_exact_given_gpu_h(T, f, spiky, smooth):
     assert np.array_equal(gu.u8(h_q), ref_q)
     assert np.array_equal(gu.u8(h_qT), ref_q.T)
     if smooth:
-        live = a > 0
+        live = a > 1e-30          # below ~1.3e-36 the factor clamps at the largest float and the channel cannot fill
         assert np.all((gu.u8(h_q) & 0x7F).max(axis=0)[live] == 0x7E)      # every live channel fills the format
 
 
