@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Benchmark of the FP8 Smooth-SwiGLU MLP block (forward + backward) on one MI355X.
+
+One "step" is one pass of the whole hot path -- ssg_mlp_fwd followed by
+ssg_mlp_bwd, i.e. every quantization pass (including W1/W2 and the per-call
+re-quantization of the folded W3), the nine FP8 GEMMs and their fused
+epilogues -- over one batch of synthetic bf16 input at the Llama2-7B MLP shape
+(T=4096, d_model=4096, d_ffn=11008).  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+  value       = 18*T*d*f / time per step, in TFLOP/s (only GEMM flops count)
+  roofline    = the dominant GEMM kernel against the dense FP8 MFMA peak, from HIP
+                events recorded around its launches on the launch stream
+  cpu_baseline= the numpy oracle timed on the host cores on a bounded sample
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP8_TFLOPS = 5000.0          # MI355X dense FP8 MFMA peak (published: 5.0 PFLOP/s)
+METRIC = "FP8 Smooth-SwiGLU MLP fwd+bwd TFLOP/s (7B shape), % of FP8 MFMA peak"
+TAG_NAMES = {0: "gemm_kernel<STORE,E4M3>", 1: "gemm_kernel<STORE,E5M2>", 2: "gemm_kernel<SWIGLU,E4M3>",
+             5: "gemm_kernel<SWIGLU_BWD,E5M2>"}
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (see profiles/); None until such a run has been recorded for the current kernel.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def gemm_flops_by_tag(T, d, f):
+    """Algorithmic flops per step and launches per step of each GEMM kernel instantiation."""
+    one = 2.0 * T * d * f
+    return {
+        0: (one, 1),          # y = h^ w3~^T
+        2: (2 * one, 1),      # U and G in one launch
+        5: (one, 1),          # dH
+        1: (5 * one, 4),      # dW3, dX (two products), dW1, dW2
+    }
+
+
+def cpu_baseline(T_sample: int, cfg):
+    """The oracle, as it stands, on the first T_sample tokens of the workload with the full weights."""
+    import numpy as np
+    import synth
+    from oracle import mlp
+    inp = synth.make_inputs(T_sample, cfg.d, cfg.f, cfg.seed, cfg.w_std, backward=True)
+    npi = {k: synth.bf16_to_f32_numpy(v) for k, v in inp.items() if v is not None and k != "aligned"}
+    t0 = time.perf_counter()
+    fw = mlp.forward(npi["x"], npi["W1"], npi["W2"], npi["W3"])
+    mlp.backward(fw, npi["dY"])
+    dt = time.perf_counter() - t0
+    flops = 18.0 * T_sample * cfg.d * cfg.f
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {T_sample} of {cfg.T} tokens, full weights, fwd+bwd, {dt:.1f} s wall",
+            "seconds": dt}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="7b", help="name in synth.CONFIGS (default: the headline shape)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=256)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import synth
+    import paper_2409_12517_amd as ssg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = "cuda:0"
+    cfg = synth.CONFIGS[args.workload]
+    T, d, f = cfg.T, cfg.d, cfg.f
+    inp = synth.make_inputs(T, d, f, cfg.seed, cfg.w_std, backward=True)
+    x, W1, W2, W3, dY = (inp[k].to(dev) for k in ("x", "W1", "W2", "W3", "dY"))
+    desc = ssg.make_desc(T, d, f, smooth=1)
+    saved = torch.empty(ssg.ssg_mlp_saved_bytes(desc), dtype=torch.uint8, device=dev)
+    work = torch.empty(ssg.ssg_mlp_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    y = torch.empty(T, d, dtype=torch.bfloat16, device=dev)
+    dx = torch.empty(T, d, dtype=torch.bfloat16, device=dev)
+    dW1 = torch.empty(f, d, dtype=torch.float32, device=dev)
+    dW2 = torch.empty(f, d, dtype=torch.float32, device=dev)
+    dW3 = torch.empty(d, f, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        ssg.ssg_mlp_fwd(desc, x, W1, W2, W3, y, saved, stream)
+        ssg.ssg_mlp_bwd(desc, dY, saved, dx, dW1, dW2, dW3, work, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # the timed region: exactly K steps, GEMM launches bracketed by HIP events on the launch stream
+    launches_per_step = 7
+    ssg.ssg_profile_enable(launches_per_step * args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_list, tags = ssg.ssg_profile_read(launches_per_step * args.steps)
+    ssg.ssg_profile_enable(0)
+
+    ms_per_step = dt * 1e3 / args.steps
+    flops_step = 18.0 * T * d * f
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    # per-kernel averages; dominant = largest share of the step
+    per_tag = {}
+    for ms, tg in zip(ms_list, tags):
+        per_tag.setdefault(tg, []).append(ms)
+    fl = gemm_flops_by_tag(T, d, f)
+    kernels = {}
+    for tg, v in per_tag.items():
+        flops_per_launch = fl[tg][0] / fl[tg][1]
+        avg = sum(v) / len(v)
+        kernels[TAG_NAMES.get(tg, str(tg))] = {
+            "launches_per_step": fl[tg][1], "avg_ms": avg,
+            "tflops": flops_per_launch / (avg * 1e-3) / 1e12}
+    dom_tag = max(per_tag, key=lambda tg: sum(per_tag[tg]))
+    dom_avg = sum(per_tag[dom_tag]) / len(per_tag[dom_tag])
+    dom_flops = fl[dom_tag][0] / fl[dom_tag][1]
+    achieved = dom_flops / (dom_avg * 1e-3) / 1e12
+    gemm_ms = sum(ms_list) / args.steps
+    roofline = {"bound": "mfma", "kernel": TAG_NAMES.get(dom_tag, str(dom_tag)), "achieved": achieved,
+                "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP8_TFLOPS,
+                "traffic": MEASURED_TRAFFIC_BYTES, "avg_launch_ms": dom_avg,
+                "flops_per_launch": dom_flops, "all_gemm_ms_per_step": gemm_ms,
+                "non_gemm_ms_per_step": ms_per_step - gemm_ms, "kernels": kernels}
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "fp8 (E4M3/E5M2 operands, fp32 accumulate)", "data": "synthetic",
+        "pct_of_fp8_peak": 100.0 * value / PEAK_FP8_TFLOPS,
+        "config": {"workload": f"{cfg.name}: Llama2-7B MLP fwd+bwd, T={T} d_model={d} d_ffn={f}, Smooth-SwiGLU, "
+                               "current scaling, W1/W2 quantized every step",
+                   "T": T, "d_model": d, "d_ffn": f, "seed": cfg.seed},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(min(args.cpu_sample_tokens, T), cfg)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -157,6 +157,20 @@ typedef struct {
 ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_mlp_saved_view *out);
 ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspace, ssg_mlp_workspace_view *out);
 
+/* ---- kernel timing for benchmarks (optional) --------------------------------
+ * The one piece of state the library keeps, off by default.  While enabled,
+ * every GEMM launch is bracketed by two HIP events recorded on the launch's
+ * own stream (events are host objects; no device memory is allocated).
+ *   ssg_profile_enable(n)  n > 0: create n event pairs and start recording (records beyond n are
+ *                          dropped); n = 0: stop and destroy the events.
+ *   ssg_profile_read       waits for the recorded events, writes up to `cap` durations in
+ *                          milliseconds and their tags (host arrays), clears the record list and
+ *                          returns the number written, or a negative ssg_status.
+ *                          tag = 2 * epilogue + a_fmt with epilogue 0 = plain store (y, dx, dW),
+ *                          1 = fused SwiGLU forward (U, G, channel maxima), 2 = fused SwiGLU backward. */
+ssg_status ssg_profile_enable(int max_records);
+int ssg_profile_read(float *ms, int *tags, int cap);
+
 #ifdef __cplusplus
 }
 #endif

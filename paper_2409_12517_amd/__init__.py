@@ -33,6 +33,7 @@ EXPORTS = [
     "ssg_last_error", "ssg_version", "ssg_amax", "ssg_quantize", "ssg_gemm_fp8", "ssg_swiglu",
     "ssg_smooth_swiglu_quantize", "ssg_fold_w3", "ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes",
     "ssg_mlp_fwd", "ssg_mlp_bwd", "ssg_mlp_view_saved", "ssg_mlp_view_workspace",
+    "ssg_profile_enable", "ssg_profile_read",
 ]
 
 
@@ -71,6 +72,8 @@ _lib.ssg_mlp_fwd.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 7
 _lib.ssg_mlp_bwd.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 8
 _lib.ssg_mlp_view_saved.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_saved_view)]
 _lib.ssg_mlp_view_workspace.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_workspace_view)]
+_lib.ssg_profile_enable.argtypes = [c_int]
+_lib.ssg_profile_read.argtypes = [POINTER(c_float), POINTER(c_int), c_int]
 for _n in EXPORTS[2:]:
     if _n not in ("ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes"):
         getattr(_lib, _n).restype = c_int
@@ -172,6 +175,20 @@ def ssg_mlp_view_workspace(desc, workspace) -> ssg_mlp_workspace_view:
     v = ssg_mlp_workspace_view()
     _check(_lib.ssg_mlp_view_workspace(ctypes.byref(desc), _ptr(workspace), ctypes.byref(v)))
     return v
+
+
+def ssg_profile_enable(max_records: int) -> None:
+    _check(_lib.ssg_profile_enable(max_records))
+
+
+def ssg_profile_read(cap: int):
+    """Returns (durations_ms, tags) of the GEMM launches recorded since the last read."""
+    ms = (c_float * cap)()
+    tags = (c_int * cap)()
+    n = _lib.ssg_profile_read(ms, tags, cap)
+    if n < 0:
+        raise SsgError(n, ssg_last_error())
+    return list(ms[:n]), list(tags[:n])
 
 
 def view_tensor(saved, base_ptr: int, field_ptr: int, shape, dtype):

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "../../include/ssg.h"
 #include "ssg_device.h"
@@ -112,9 +113,62 @@ ssg_status check_desc(const ssg_mlp_desc *d, const char *who) {
     return SSG_OK;
 }
 
+// ---- optional kernel timing -----------------------------------------------------
+struct ProfileState {
+    std::vector<hipEvent_t> start, stop;
+    std::vector<int> tag;
+    int used = 0;
+    bool open = false;       // a start event was recorded and waits for its stop
+};
+ProfileState g_prof;
+
 }  // namespace
 
+namespace ssg {
+void profile_before(int tag, hipStream_t st) {
+    g_prof.open = false;
+    if (g_prof.used >= (int)g_prof.start.size()) return;
+    if (hipEventRecord(g_prof.start[g_prof.used], st) != hipSuccess) return;
+    g_prof.tag[g_prof.used] = tag;
+    g_prof.open = true;
+}
+void profile_after(hipStream_t st) {
+    if (!g_prof.open) return;
+    g_prof.open = false;
+    if (hipEventRecord(g_prof.stop[g_prof.used], st) == hipSuccess) ++g_prof.used;
+}
+}  // namespace ssg
+
 extern "C" {
+
+ssg_status ssg_profile_enable(int max_records) {
+    if (max_records < 0 || max_records > (1 << 20)) return fail(SSG_ERR_ARG, "ssg_profile_enable: bad max_records");
+    for (hipEvent_t e : g_prof.start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : g_prof.stop) (void)hipEventDestroy(e);
+    g_prof = ProfileState();
+    for (int i = 0; i < max_records; ++i) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess)
+            return fail(SSG_ERR_HIP, "ssg_profile_enable: hipEventCreate failed");
+        g_prof.start.push_back(a);
+        g_prof.stop.push_back(b);
+    }
+    g_prof.tag.assign((size_t)max_records, 0);
+    return SSG_OK;
+}
+
+int ssg_profile_read(float *ms, int *tags, int cap) {
+    if (!ms || !tags || cap < 0) return fail(SSG_ERR_ARG, "ssg_profile_read: bad argument");
+    int n = g_prof.used < cap ? g_prof.used : cap;
+    for (int i = 0; i < n; ++i) {
+        if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess ||
+            hipEventElapsedTime(&ms[i], g_prof.start[i], g_prof.stop[i]) != hipSuccess)
+            return fail(SSG_ERR_HIP, "ssg_profile_read: event query failed");
+        tags[i] = g_prof.tag[i];
+    }
+    g_prof.used = 0;
+    return n;
+}
 
 const char *ssg_last_error(void) { return g_err; }
 const char *ssg_version(void) { return "ssg 0.1 (gfx950)"; }

@@ -76,4 +76,8 @@ struct GemmArgs {
 };
 void launch_gemm(const GemmArgs &a, hipStream_t st);
 
+// Benchmark hook: called by launch_gemm before and after the kernel launch (no-ops unless enabled).
+void profile_before(int tag, hipStream_t st);
+void profile_after(hipStream_t st);
+
 }  // namespace ssg
