@@ -52,7 +52,22 @@ struct GemmParams {
     int tiles_m, tiles_n;
 };
 
-__device__ __forceinline__ int swz(int row) { return row & 7; }
+// Rows r and r+8 are 1 KB apart and would share banks; pairing rows (r >> 1) spreads 16
+// consecutive rows over sixteen distinct 16-byte bank groups of the 256-byte bank period.
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+
+// Direct-to-LDS loads are issued through inline assembly: the compiler would otherwise wait for
+// ALL outstanding LDS-DMA loads before every ds_read (it cannot tell the two LDS stages apart),
+// which serialises memory latency with the MFMA work.  M0 carries the wave-uniform LDS
+// destination; lane i lands at M0 + 16*i.  The vmcnt waits are placed by hand in the main loop.
+__device__ __forceinline__ void dma16(const uint8_t *g, uint32_t lds_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_addr), "v"(g) : "memory");
+#else
+    (void)g; (void)lds_addr;
+#endif
+}
 
 template <int AFMT>
 __device__ __forceinline__ v16f mfma(const v8i &a, const v8i &b, const v16f &c) {
@@ -71,7 +86,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     __shared__ __attribute__((aligned(1024))) uint8_t smem[kStages * kStageBytes];
 
     const int tid = threadIdx.x;
-    const int w = tid >> 6, l = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;   // wave index is uniform: keep it scalar
     const int wm = w >> 2, wn = w & 3;
 
     const int tile_m = blockIdx.x % p.tiles_m;
@@ -98,7 +113,8 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         b_off[j] = (uint32_t)(gn * p.K);
     }
     if (EPI == EPI_SWIGLU && w >= 4) b_src = p.B2;      // waves 4..7 fill tile rows 128..255
-    const int chunk = lpos ^ swz(lrow);        // logical chunk this lane fetches (rows of a group are 8-aligned)
+    // logical chunk this lane fetches for slot j (the LDS row of slot j is (w*4+j)*8 + lrow)
+    const int chunk_even = lpos ^ swz(lrow), chunk_odd = lpos ^ swz(8 + lrow);
     const uint32_t lds_a = (uint32_t)(w * 4) * 1024u;   // + j*1024 + stage offset
     const uint32_t lds_b = kTileBytes + lds_a;
 
@@ -149,18 +165,17 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         }
         const int nk = (int)((Kseg + BK - 1) / BK);
 
+        const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
         auto issue = [&](int kt, int stage) {
-            const int64_t k0 = (int64_t)kt * BK + chunk * 16;
-            const bool k_ok = k0 < Kseg;       // K is a multiple of 16: a chunk is all in or all out
-            const uint32_t sbase = (uint32_t)stage * kStageBytes;
+            const uint32_t sbase = smem_base + (uint32_t)stage * kStageBytes;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
+                const int64_t k0 = (int64_t)kt * BK + ((j & 1) ? chunk_odd : chunk_even) * 16;
+                const bool k_ok = k0 < Kseg;   // K is a multiple of 16: a chunk is all in or all out
                 const uint8_t *ga = k_ok ? Aseg + a_off[j] + k0 : reinterpret_cast<const uint8_t *>(&g_zero_chunk);
                 const uint8_t *gb = k_ok ? Bseg + b_off[j] + k0 : reinterpret_cast<const uint8_t *>(&g_zero_chunk);
-                __builtin_amdgcn_global_load_lds((global_void_ptr)ga, (lds_void_ptr)(smem + sbase + lds_a + j * 1024),
-                                                 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((global_void_ptr)gb, (lds_void_ptr)(smem + sbase + lds_b + j * 1024),
-                                                 16, 0, 0);
+                dma16(ga, sbase + lds_a + j * 1024);
+                dma16(gb, sbase + lds_b + j * 1024);
             }
         };
 
@@ -196,84 +211,158 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     }
 
     // ---- epilogue.  Block (mb, nb), register i, lane l holds
-    //      row = wm*128 + mb*32 + (i/4)*8 + (l/32)*4 + i%4,  column = colbase(nb) + l%32.
+    //      row = wm*128 + mb*32 + (i/4)*8 + (l/32)*4 + i%4,  column = colbase(nb) + l%32,
+    // i.e. one column and scattered rows per lane.  Each wave re-lays its accumulators out through
+    // a private LDS patch, one 32 x 64 slab (mb) at a time, so that a lane then owns 8 consecutive
+    // columns of one row and every global access is a 16-byte vector on a full 64/128-byte run.
+    __syncthreads();                                   // main-loop LDS is no longer read by anyone
+    constexpr int kPitch = 72;                         // floats; 4 rows apart lands on the other 32 banks
+    float *stg = reinterpret_cast<float *>(smem) + w * (32 * kPitch);
     const int lcol = l & 31;
     const int lrow4 = (l >> 5) * 4;
+    auto stage_slab = [&](int mb) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                stg[((i >> 2) * 8 + lrow4 + (i & 3)) * kPitch + nb * 32 + lcol] = acc[mb][nb][i];
+    };
+    auto load8 = [&](int r, int c, float (&v)[8]) {
+        const float4 a = *reinterpret_cast<const float4 *>(stg + r * kPitch + c);
+        const float4 b = *reinterpret_cast<const float4 *>(stg + r * kPitch + c + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    };
+    auto pack_bf16x8 = [&](const float (&v)[8]) {
+        uint32_t q[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) q[k] = f32_to_bf16_bits(v[2 * k]) | (f32_to_bf16_bits(v[2 * k + 1]) << 16);
+        return make_uint4(q[0], q[1], q[2], q[3]);
+    };
+    auto unpack_bf16x8 = [&](const uint4 q, float (&v)[8]) {
+        const uint32_t w4[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[2 * k] = __uint_as_float(w4[k] << 16);
+            v[2 * k + 1] = __uint_as_float(w4[k] & 0xffff0000u);
+        }
+    };
 
-    if (EPI == EPI_STORE) {
-        const float alpha = inv_scale_product(n_seg == 2 ? p.sa2 : p.sa, n_seg == 2 ? p.sb2 : p.sb);
+    if (EPI == EPI_STORE || EPI == EPI_SWIGLU_BWD) {
+        // lane -> (row r of the slab in 4 passes of 8 rows, 8 columns c8 of the wave's 64)
+        const int c8 = (l & 7) * 8;
+        const int64_t col = n0 + wn * 64 + c8;
+        const bool col_ok = col < p.N;                 // N is a multiple of 16: the 8 columns are all in or all out
+        const float alpha = (EPI == EPI_STORE && n_seg == 2) ? inv_scale_product(p.sa2, p.sb2)
+                                                             : inv_scale_product(p.sa, p.sb);
+        float f[8];
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            const int64_t col = n0 + wn * 64 + nb * 32 + lcol;
-            if (col >= p.N) continue;
-            const float f = p.col_scale ? __fmul_rn(alpha, p.col_scale[col]) : alpha;
+        for (int k = 0; k < 8; ++k) f[k] = alpha;
+        if (p.col_scale && col_ok) {
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int64_t row = m0 + wm * 128 + mb * 32 + (i >> 2) * 8 + lrow4 + (i & 3);
-                    if (row >= p.M) continue;
-                    const float v = __fmul_rn(acc[mb][nb][i], f);
-                    if (p.c_f32) reinterpret_cast<float *>(p.C)[row * p.N + col] = v;
-                    else reinterpret_cast<uint16_t *>(p.C)[row * p.N + col] = (uint16_t)f32_to_bf16_bits(v);
-                }
+            for (int k = 0; k < 8; ++k) f[k] = __fmul_rn(alpha, p.col_scale[col + k]);
         }
-    } else if (EPI == EPI_SWIGLU) {
-        const float alpha_u = inv_scale_product(p.sa, p.sb);
-        const float alpha_g = inv_scale_product(p.sa, p.sb2);
-        const int64_t col = n0 + wn * 32 + lcol;
-        uint32_t hmax = 0;
-        if (col < p.N) {
-#pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int64_t row = m0 + wm * 128 + mb * 32 + (i >> 2) * 8 + lrow4 + (i & 3);
-                    if (row >= p.M) continue;
-                    const uint32_t ub = f32_to_bf16_bits(__fmul_rn(acc[mb][0][i], alpha_u));
-                    const uint32_t gb = f32_to_bf16_bits(__fmul_rn(acc[mb][1][i], alpha_g));
-                    reinterpret_cast<uint16_t *>(p.C)[row * p.N + col] = (uint16_t)ub;
-                    reinterpret_cast<uint16_t *>(p.C2)[row * p.N + col] = (uint16_t)gb;
-                    const uint32_t hb = abs_bits_ignore_nan(swiglu_f32(bf16_bits_to_f32(ub), bf16_bits_to_f32(gb)));
-                    hmax = hmax > hb ? hmax : hb;
-                }
-        }
-        const uint32_t other = (uint32_t)__shfl_xor((int)hmax, 32, 64);
-        hmax = hmax > other ? hmax : other;
-        if (l < 32 && col < p.N && hmax) atomicMax(&p.camax_bits[col], hmax);
-    } else {   // EPI_SWIGLU_BWD
-        const float alpha = inv_scale_product(p.sa, p.sb);
         uint32_t du_max = 0, dg_max = 0;
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            const int64_t col = n0 + wn * 64 + nb * 32 + lcol;
-            if (col >= p.N) continue;
-            const float f = p.col_scale ? __fmul_rn(alpha, p.col_scale[col]) : alpha;
+        for (int mb = 0; mb < 4; ++mb) {
+            stage_slab(mb);
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
+            for (int pass = 0; pass < 4; ++pass) {
+                const int r = pass * 8 + (l >> 3);
+                const int64_t row = m0 + wm * 128 + mb * 32 + r;
+                float v[8];
+                load8(r, c8, v);
+                if (!col_ok || row >= p.M) continue;
+                const size_t at = (size_t)row * (size_t)p.N + (size_t)col;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int64_t row = m0 + wm * 128 + mb * 32 + (i >> 2) * 8 + lrow4 + (i & 3);
-                    if (row >= p.M) continue;
-                    const float dh = __fmul_rn(acc[mb][nb][i], f);
-                    const float u = bf16_bits_to_f32(p.U[row * p.N + col]);
-                    const float g = bf16_bits_to_f32(p.G[row * p.N + col]);
-                    float du, dg;
-                    swiglu_grad_f32(u, g, dh, du, dg);
-                    const uint32_t dub = f32_to_bf16_bits(du), dgb = f32_to_bf16_bits(dg);
-                    reinterpret_cast<uint16_t *>(p.C)[row * p.N + col] = (uint16_t)dub;
-                    reinterpret_cast<uint16_t *>(p.C2)[row * p.N + col] = (uint16_t)dgb;
-                    const uint32_t am = abs_bits_ignore_nan(bf16_bits_to_f32(dub));
-                    const uint32_t bm = abs_bits_ignore_nan(bf16_bits_to_f32(dgb));
-                    du_max = du_max > am ? du_max : am;
-                    dg_max = dg_max > bm ? dg_max : bm;
+                for (int k = 0; k < 8; ++k) v[k] = __fmul_rn(v[k], f[k]);
+                if (EPI == EPI_STORE) {
+                    if (p.c_f32) {
+                        float *out = reinterpret_cast<float *>(p.C) + at;
+                        *reinterpret_cast<float4 *>(out) = make_float4(v[0], v[1], v[2], v[3]);
+                        *reinterpret_cast<float4 *>(out + 4) = make_float4(v[4], v[5], v[6], v[7]);
+                    } else {
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = pack_bf16x8(v);
+                    }
+                } else {
+                    float u[8], g[8], du[8], dg[8];
+                    unpack_bf16x8(*reinterpret_cast<const uint4 *>(p.U + at), u);
+                    unpack_bf16x8(*reinterpret_cast<const uint4 *>(p.G + at), g);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) swiglu_grad_f32(u[k], g[k], v[k], du[k], dg[k]);
+                    const uint4 qu = pack_bf16x8(du), qg = pack_bf16x8(dg);
+                    *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = qu;
+                    *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C2) + at) = qg;
+                    // amax of the stored bf16 values: compare the 15-bit magnitudes (NaN -> 0)
+                    const uint32_t wu[4] = {qu.x, qu.y, qu.z, qu.w}, wg[4] = {qg.x, qg.y, qg.z, qg.w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        uint32_t a0 = wu[k] & 0x7fffu, a1 = (wu[k] >> 16) & 0x7fffu;
+                        uint32_t b0 = wg[k] & 0x7fffu, b1 = (wg[k] >> 16) & 0x7fffu;
+                        a0 = a0 > 0x7f80u ? 0u : a0; a1 = a1 > 0x7f80u ? 0u : a1;
+                        b0 = b0 > 0x7f80u ? 0u : b0; b1 = b1 > 0x7f80u ? 0u : b1;
+                        a0 = a0 > a1 ? a0 : a1; b0 = b0 > b1 ? b0 : b1;
+                        du_max = du_max > a0 ? du_max : a0;
+                        dg_max = dg_max > b0 ? dg_max : b0;
+                    }
                 }
+            }
         }
-        du_max = wave_max_u32(du_max);
-        dg_max = wave_max_u32(dg_max);
-        if (l == 0) {
-            if (du_max) atomicMax(&p.amax_bits[0], du_max);
-            if (dg_max) atomicMax(&p.amax_bits[1], dg_max);
+        if (EPI == EPI_SWIGLU_BWD) {
+            du_max = wave_max_u32(du_max);
+            dg_max = wave_max_u32(dg_max);
+            if (l == 0) {
+                if (du_max) atomicMax(&p.amax_bits[0], du_max << 16);
+                if (dg_max) atomicMax(&p.amax_bits[1], dg_max << 16);
+            }
+        }
+    } else {   // EPI_SWIGLU: slab columns 0..31 are u, 32..63 are g of the same 32 channels
+        const int c8 = (l & 3) * 8;
+        const int64_t col = n0 + wn * 32 + c8;
+        const bool col_ok = col < p.N;
+        const float alpha_u = inv_scale_product(p.sa, p.sb);
+        const float alpha_g = inv_scale_product(p.sa, p.sb2);
+        uint32_t hmax[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            stage_slab(mb);
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+                const int r = pass * 16 + (l >> 2);
+                const int64_t row = m0 + wm * 128 + mb * 32 + r;
+                float u[8], g[8];
+                load8(r, c8, u);
+                load8(r, 32 + c8, g);
+                if (!col_ok || row >= p.M) continue;
+                const size_t at = (size_t)row * (size_t)p.N + (size_t)col;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    u[k] = __fmul_rn(u[k], alpha_u);
+                    g[k] = __fmul_rn(g[k], alpha_g);
+                }
+                const uint4 qu = pack_bf16x8(u), qg = pack_bf16x8(g);
+                *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = qu;
+                *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C2) + at) = qg;
+                unpack_bf16x8(qu, u);                  // h is formed from the stored (rounded) values
+                unpack_bf16x8(qg, g);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const uint32_t hb = abs_bits_ignore_nan(swiglu_f32(u[k], g[k]));
+                    hmax[k] = hmax[k] > hb ? hmax[k] : hb;
+                }
+            }
+        }
+        // lanes with equal (l & 3) hold the same 8 channels: fold over the 16 row lanes
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+#pragma unroll
+            for (int off = 4; off < 64; off <<= 1) {
+                const uint32_t o = (uint32_t)__shfl_xor((int)hmax[k], off, 64);
+                hmax[k] = hmax[k] > o ? hmax[k] : o;
+            }
+        if (l < 4 && col_ok) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (hmax[k]) atomicMax(&p.camax_bits[col + k], hmax[k]);
         }
     }
 }

@@ -58,14 +58,26 @@ struct LoadSwiglu {          // h = u * Swish(g) from stored bf16 U, G
 template <class Loader>
 __global__ void __launch_bounds__(256) amax_kernel(Loader ld, size_t n8, uint32_t *amax_bits) {
     uint32_t m = 0;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
-        float v[8];
-        ld.load8(i * 8, v);
+    const size_t stride = (size_t)gridDim.x * 256;
+    // four independent 16-byte loads in flight per lane and iteration
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += 4 * stride) {
+        float v[4][8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            uint32_t b = abs_bits_ignore_nan(v[k]);
-            m = m > b ? m : b;
+        for (int u = 0; u < 4; ++u) {
+            const size_t j = i + u * stride;
+            if (j < n8) ld.load8(j * 8, v[u]);
+            else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[u][k] = 0.0f;
+            }
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                uint32_t b = abs_bits_ignore_nan(v[u][k]);
+                m = m > b ? m : b;
+            }
     }
     m = wave_max_u32(m);
     __shared__ uint32_t part[4];
@@ -82,7 +94,7 @@ void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, h
     size_t n8 = n / 8;      // n is a multiple of 256 at every call site (rows, cols multiples of 16)
     if (n8 == 0) return;
     size_t want = (n8 + 255) / 256;
-    unsigned blocks = (unsigned)(want < 2048 ? want : 2048);
+    unsigned blocks = (unsigned)(want < 4096 ? want : 4096);
     if (kind == SRC_BF16)
         hipLaunchKernelGGL(amax_kernel<LoadBf16>, dim3(blocks), dim3(256), 0, st,
                            LoadBf16{(const uint16_t *)src}, n8, amax_bits);
