@@ -353,21 +353,20 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     // zero the scalar block and both per-channel maxima (contiguous) in one fill
     ssg::launch_fill_u32(scb, (L.s - L.scalars) / 4, 0u, st);
 
-    // a1: per-tensor ranges (Section 2)
-    ssg::launch_amax(x, ssg::SRC_BF16, (size_t)(T * dm), scb + S_AMAX_X, st);
-    ssg::launch_amax(W1, ssg::SRC_BF16, (size_t)(f * dm), scb + S_AMAX_W1, st);
-    ssg::launch_amax(W2, ssg::SRC_BF16, (size_t)(f * dm), scb + S_AMAX_W2, st);
-    ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
-
-    // a2: Q(x), Q(w1), Q(w2), each with the transposed copy the backward contractions read
+    // a1 + a2: per-tensor range (Section 2), then Q (Eq. 2) with the transposed copy the backward
+    // contractions read.  Range and cast of one tensor run back to back so that the second read of
+    // the tensor can still be served from the memory-side cache.
     ssg::CastArgs c;
     c.kind = ssg::SRC_BF16; c.fmt = ssg::kE4M3; c.pow2 = pow2;
+    ssg::launch_amax(x, ssg::SRC_BF16, (size_t)(T * dm), scb + S_AMAX_X, st);
     c.src = x; c.rows = T; c.cols = dm; c.amax = sc + S_AMAX_X; c.scale_out = sc + S_SX;
     c.dst = b + L.x_q; c.dst_t = b + L.x_qT;
     ssg::launch_cast(c, st);
+    ssg::launch_amax(W1, ssg::SRC_BF16, (size_t)(f * dm), scb + S_AMAX_W1, st);
     c.src = W1; c.rows = f; c.cols = dm; c.amax = sc + S_AMAX_W1; c.scale_out = sc + S_SW1;
     c.dst = b + L.w1_q; c.dst_t = b + L.w1_qT;
     ssg::launch_cast(c, st);
+    ssg::launch_amax(W2, ssg::SRC_BF16, (size_t)(f * dm), scb + S_AMAX_W2, st);
     c.src = W2; c.amax = sc + S_AMAX_W2; c.scale_out = sc + S_SW2; c.dst = b + L.w2_q; c.dst_t = b + L.w2_qT;
     ssg::launch_cast(c, st);
 
@@ -379,7 +378,8 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     g.C = b + L.U; g.C2 = b + L.G; g.camax_bits = reinterpret_cast<uint32_t *>(h_camax);
     ssg::launch_gemm(g, st);
 
-    // a5: factors s_i, s_i^-1 and the range of s^-1 * w3
+    // a5: factors s_i, s_i^-1 and the range of s^-1 * w3 (from the per-channel range of w3)
+    ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
     ssg::launch_channel_factors(h_camax, w3_camax, f, desc->smooth, s, sinv, scb + S_AMAX_W3S, scb + S_HMAX, st);
 
     // a6: h^ = cast(s_i * h), recomputing h from the stored bf16 U, G

@@ -89,8 +89,28 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;   // wave index is uniform: keep it scalar
     const int wm = w >> 2, wn = w & 3;
 
-    const int tile_m = blockIdx.x % p.tiles_m;
-    const int tile_n = blockIdx.x / p.tiles_m;
+    // Workgroup -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with
+    // its own L2, so give every XCD a contiguous range of a tile order in which any 32 consecutive
+    // tiles (one per CU of the XCD) form a 4 x 8 patch: 12 operand tiles fetched for 32 computed.
+    int tile_m, tile_n;
+    {
+        const int total = p.tiles_m * p.tiles_n;
+        const int per_xcd = (total + 7) / 8;
+        int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+        if ((total & 7) != 0) {
+            // ranges are uneven: fall back to the identity when the remapped id would leave the grid
+            const int full = total & ~7;
+            t = (int)blockIdx.x < full ? (int)(blockIdx.x & 7) * (full >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+        }
+        constexpr int kGroupM = 4;
+        const int group_tiles = kGroupM * p.tiles_n;
+        const int gidx = t / group_tiles;
+        const int first_m = gidx * kGroupM;
+        const int gsize = (p.tiles_m - first_m) < kGroupM ? (p.tiles_m - first_m) : kGroupM;
+        const int in_group = t - gidx * group_tiles;
+        tile_m = first_m + in_group % gsize;
+        tile_n = in_group / gsize;
+    }
     const int64_t m0 = (int64_t)tile_m * BM;
     // SWIGLU: a tile covers 128 channels (128 rows of W1 + the same 128 rows of W2)
     const int64_t n0 = (int64_t)tile_n * (EPI == EPI_SWIGLU ? BN / 2 : BN);
@@ -308,11 +328,17 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
             }
         }
         if (EPI == EPI_SWIGLU_BWD) {
+            // one atomic pair per workgroup: same-address atomics serialise in L2
             du_max = wave_max_u32(du_max);
             dg_max = wave_max_u32(dg_max);
-            if (l == 0) {
-                if (du_max) atomicMax(&p.amax_bits[0], du_max << 16);
-                if (dg_max) atomicMax(&p.amax_bits[1], dg_max << 16);
+            uint32_t *red = reinterpret_cast<uint32_t *>(smem + 8 * 32 * kPitch * 4);   // past the staging patches
+            if (l == 0) { red[2 * w] = du_max; red[2 * w + 1] = dg_max; }
+            __syncthreads();
+            if (tid < 2) {
+                uint32_t m = 0;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) m = m > red[2 * k + tid] ? m : red[2 * k + tid];
+                if (m) atomicMax(&p.amax_bits[tid], m << 16);
             }
         }
     } else {   // EPI_SWIGLU: slab columns 0..31 are u, 32..63 are g of the same 32 channels

@@ -59,11 +59,11 @@ template <class Loader>
 __global__ void __launch_bounds__(256) amax_kernel(Loader ld, size_t n8, uint32_t *amax_bits) {
     uint32_t m = 0;
     const size_t stride = (size_t)gridDim.x * 256;
-    // four independent 16-byte loads in flight per lane and iteration
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += 4 * stride) {
-        float v[4][8];
+    // eight independent 16-byte loads in flight per lane and iteration
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += 8 * stride) {
+        float v[8][8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 8; ++u) {
             const size_t j = i + u * stride;
             if (j < n8) ld.load8(j * 8, v[u]);
             else {
@@ -72,7 +72,7 @@ __global__ void __launch_bounds__(256) amax_kernel(Loader ld, size_t n8, uint32_
             }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 8; ++u)
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 uint32_t b = abs_bits_ignore_nan(v[u][k]);
@@ -94,7 +94,8 @@ void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, h
     size_t n8 = n / 8;      // n is a multiple of 256 at every call site (rows, cols multiples of 16)
     if (n8 == 0) return;
     size_t want = (n8 + 255) / 256;
-    unsigned blocks = (unsigned)(want < 4096 ? want : 4096);
+    // few workgroups: every one ends with an atomic on the same word, and those serialise
+    unsigned blocks = (unsigned)(want < 512 ? want : 512);
     if (kind == SRC_BF16)
         hipLaunchKernelGGL(amax_kernel<LoadBf16>, dim3(blocks), dim3(256), 0, st,
                            LoadBf16{(const uint16_t *)src}, n8, amax_bits);
