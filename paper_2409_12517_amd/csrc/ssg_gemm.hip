@@ -33,11 +33,15 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef __attribute__((address_space(1))) const void *global_void_ptr;
 
-constexpr int BM = 256, BN = 256, BK = 128;
+constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kThreads = 512;
-constexpr int kTileBytes = BM * BK;               // one operand tile, 32 KB
-constexpr int kStageBytes = 2 * kTileBytes;       // A + B
-constexpr int kStages = 2;
+constexpr int kTileBytes = BM * BK;               // one operand tile of one K step, 16 KB
+constexpr int kStageBytes = 2 * kTileBytes;       // A + B, 32 KB
+constexpr int kStages = 5;                        // ring of K steps in LDS: all 160 KB
+constexpr int kDepth = kStages - 1;               // K steps in flight ahead of the one being read
+#ifndef SSG_GEMM_EXPERIMENT
+#define SSG_GEMM_EXPERIMENT 0   /* timing experiments only: 1 = no DMA in loop, 2 = no LDS reads, 4 = no barriers */
+#endif
 
 __device__ uint4 g_zero_chunk = {0u, 0u, 0u, 0u}; // source of the zero fill of a ragged K tail
 
@@ -52,9 +56,10 @@ struct GemmParams {
     int tiles_m, tiles_n;
 };
 
-// Rows r and r+8 are 1 KB apart and would share banks; pairing rows (r >> 1) spreads 16
-// consecutive rows over sixteen distinct 16-byte bank groups of the 256-byte bank period.
-__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+// An LDS row holds the 64 bytes (four 16-byte chunks) of one matrix row for one K step.  Four rows
+// fill the 256-byte bank period, so rows r, r+4, r+8, r+12 would collide when 16 lanes read the
+// same chunk of 16 consecutive rows; XOR-ing the chunk index with (r >> 2) & 3 spreads them.
+__device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 
 // Direct-to-LDS loads are issued through inline assembly: the compiler would otherwise wait for
 // ALL outstanding LDS-DMA loads before every ds_read (it cannot tell the two LDS stages apart),
@@ -81,7 +86,7 @@ __device__ __forceinline__ float inv_scale_product(const float *sa, const float 
     return __fdiv_rn(1.0f, p);
 }
 
-template <int EPI, int AFMT>
+template <int EPI, int AFMT, bool TWO_SEG>
 __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     __shared__ __attribute__((aligned(1024))) uint8_t smem[kStages * kStageBytes];
 
@@ -115,14 +120,16 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     // SWIGLU: a tile covers 128 channels (128 rows of W1 + the same 128 rows of W2)
     const int64_t n0 = (int64_t)tile_n * (EPI == EPI_SWIGLU ? BN / 2 : BN);
 
-    // ---- global -> LDS slots of this lane: 4 chunks of A and 4 of B per stage
-    const int lrow = l >> 3;                   // row inside the 8-row group one instruction fills
-    const int lpos = l & 7;                    // 16-byte position inside the 128-byte LDS row
-    uint32_t a_off[4], b_off[4];               // byte offsets of the row starts (without k)
+    // ---- global -> LDS slots of this lane.  One DMA instruction fills 1 KB = 16 rows x 64 B; a
+    // stage is 32 instructions, 2 for A and 2 for B per wave.  Lane l lands at row (l >> 2),
+    // position (l & 3) of its 16-row group and fetches the logical chunk that the swizzle puts there.
+    const int lrow = l >> 2;
+    const int chunk = (l & 3) ^ swz(lrow);     // group bases are multiples of 16 rows: swz depends on lrow only
+    uint32_t a_off[2], b_off[2];               // byte offsets of the row starts (without k)
     const uint8_t *b_src = p.B;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = (w * 4 + j) * 8 + lrow;
+    for (int j = 0; j < 2; ++j) {
+        const int row = (w * 2 + j) * 16 + lrow;
         int64_t gm = m0 + row;
         gm = gm < p.M ? gm : p.M - 1;
         a_off[j] = (uint32_t)(gm * p.K);
@@ -133,18 +140,15 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         b_off[j] = (uint32_t)(gn * p.K);
     }
     if (EPI == EPI_SWIGLU && w >= 4) b_src = p.B2;      // waves 4..7 fill tile rows 128..255
-    // logical chunk this lane fetches for slot j (the LDS row of slot j is (w*4+j)*8 + lrow)
-    const int chunk_even = lpos ^ swz(lrow), chunk_odd = lpos ^ swz(8 + lrow);
-    const uint32_t lds_a = (uint32_t)(w * 4) * 1024u;   // + j*1024 + stage offset
+    const uint32_t lds_a = (uint32_t)(w * 2) * 1024u;   // + j*1024 + stage offset
     const uint32_t lds_b = kTileBytes + lds_a;
 
-    // ---- LDS -> register fragment offsets (same pattern for A and B)
-    uint32_t frag_off[2][2];
+    // ---- LDS -> register fragment offsets (same pattern for A and B): lane l holds row l%32 and
+    // the 32 K bytes of half l/32, i.e. logical chunks 2*(l/32) and 2*(l/32)+1
+    uint32_t frag_off[2];
 #pragma unroll
-    for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-        for (int e = 0; e < 2; ++e)
-            frag_off[kh][e] = (uint32_t)((l & 31) * BK + (((kh * 4 + (l >> 5) * 2 + e) ^ swz(l & 31)) << 4));
+    for (int e = 0; e < 2; ++e)
+        frag_off[e] = (uint32_t)((l & 31) * BK + ((((l >> 5) * 2 + e) ^ swz(l & 31)) << 4));
     const uint32_t a_frag_base = (uint32_t)(wm * 128) * BK;
     uint32_t b_frag_base[2];
 #pragma unroll
@@ -159,13 +163,52 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[mb][nb][i] = 0.0f;
 
-    const int n_seg = (EPI == EPI_STORE && p.A2) ? 2 : 1;
-    for (int seg = 0; seg < n_seg; ++seg) {
-        const uint8_t *Aseg = seg ? p.A2 : p.A;
-        const uint8_t *Bseg = seg ? p.B2 : b_src;
-        const int64_t Kseg = seg ? p.K2 : p.K;
-        if (seg) {
-            // both products share one accumulator: rescale the first by alpha1 / alpha2
+    // One K loop over both products when there are two (input gradient): steps 0..nk1-1 come from
+    // (A, B), steps nk1.. from (A2, B2); the accumulators are rescaled by alpha1/alpha2 where the
+    // second product starts, so a single dequantization by alpha2 at the end serves both.
+    constexpr int n_seg = TWO_SEG ? 2 : 1;
+    const int nk1 = (int)((p.K + BK - 1) / BK);
+    const int nk = nk1 + (TWO_SEG ? (int)((p.K2 + BK - 1) / BK) : 0);
+    {
+        const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
+        const uint8_t *a_ptr[2], *b_ptr[2];    // this lane's chunk in K step 0 of the first product
+        const uint8_t *a2_ptr[2] = {nullptr, nullptr}, *b2_ptr[2] = {nullptr, nullptr};
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            a_ptr[j] = p.A + a_off[j] + chunk * 16;
+            b_ptr[j] = b_src + b_off[j] + chunk * 16;
+            if (TWO_SEG) {                     // row pitch of the second pair is K2
+                const int row = (w * 2 + j) * 16 + lrow;
+                int64_t gm = m0 + row; gm = gm < p.M ? gm : p.M - 1;
+                int64_t gn = n0 + row; gn = gn < p.N ? gn : p.N - 1;
+                a2_ptr[j] = p.A2 + gm * p.K2 + chunk * 16;
+                b2_ptr[j] = p.B2 + gn * p.K2 + chunk * 16;
+            }
+        }
+        // K step kt -> ring slot `stage`.  Steps past the end of K fetch only zeros (every chunk is
+        // out of range), which keeps the number of outstanding DMA instructions uniform.
+        auto issue = [&](int kt, int stage) {
+            const uint32_t sbase = smem_base + (uint32_t)stage * kStageBytes;
+            const bool second = TWO_SEG && kt >= nk1;
+            const int64_t kbase = (int64_t)(second ? kt - nk1 : kt) * BK;
+            const int64_t Kseg = second ? p.K2 : p.K;
+            const uint8_t *pa0 = second ? a2_ptr[0] : a_ptr[0], *pa1 = second ? a2_ptr[1] : a_ptr[1];
+            const uint8_t *pb0 = second ? b2_ptr[0] : b_ptr[0], *pb1 = second ? b2_ptr[1] : b_ptr[1];
+            if (kbase + BK <= Kseg) {          // whole step in range (uniform branch): no per-lane select
+                dma16(pa0 + kbase, sbase + lds_a);
+                dma16(pb0 + kbase, sbase + lds_b);
+                dma16(pa1 + kbase, sbase + lds_a + 1024);
+                dma16(pb1 + kbase, sbase + lds_b + 1024);
+            } else {
+                const bool k_ok = kbase + chunk * 16 < Kseg;   // K is a multiple of 16: a chunk is all in or all out
+                const uint8_t *zero = reinterpret_cast<const uint8_t *>(&g_zero_chunk);
+                dma16(k_ok ? pa0 + kbase : zero, sbase + lds_a);
+                dma16(k_ok ? pb0 + kbase : zero, sbase + lds_b);
+                dma16(k_ok ? pa1 + kbase : zero, sbase + lds_a + 1024);
+                dma16(k_ok ? pb1 + kbase : zero, sbase + lds_b + 1024);
+            }
+        };
+        auto rescale_for_second_product = [&]() {
             const float r = __fdiv_rn(inv_scale_product(p.sa, p.sb), inv_scale_product(p.sa2, p.sb2));
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb)
@@ -173,61 +216,89 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                 for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) acc[mb][nb][i] *= r;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {      // row starts for the second pair (row pitch K2)
-                const int row = (w * 4 + j) * 8 + lrow;
-                int64_t gm = m0 + row; gm = gm < p.M ? gm : p.M - 1;
-                int64_t gn = n0 + row; gn = gn < p.N ? gn : p.N - 1;
-                a_off[j] = (uint32_t)(gm * Kseg);
-                b_off[j] = (uint32_t)(gn * Kseg);
-            }
-            __syncthreads();                   // everyone is done reading the last stage of segment 0
-        }
-        const int nk = (int)((Kseg + BK - 1) / BK);
-
-        const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
-        auto issue = [&](int kt, int stage) {
-            const uint32_t sbase = smem_base + (uint32_t)stage * kStageBytes;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int64_t k0 = (int64_t)kt * BK + ((j & 1) ? chunk_odd : chunk_even) * 16;
-                const bool k_ok = k0 < Kseg;   // K is a multiple of 16: a chunk is all in or all out
-                const uint8_t *ga = k_ok ? Aseg + a_off[j] + k0 : reinterpret_cast<const uint8_t *>(&g_zero_chunk);
-                const uint8_t *gb = k_ok ? Bseg + b_off[j] + k0 : reinterpret_cast<const uint8_t *>(&g_zero_chunk);
-                dma16(ga, sbase + lds_a + j * 1024);
-                dma16(gb, sbase + lds_b + j * 1024);
-            }
         };
 
-        issue(0, 0);
-        for (int kt = 0; kt < nk; ++kt) {
-            const int stage = kt & 1;
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (kt + 1 < nk) issue(kt + 1, stage ^ 1);
+        // Schedule.  The ring holds kDepth K steps in flight ahead of the one being read, which is
+        // what hides the memory latency (a 32 KB step per ~1024 MFMA cycles needs >100 KB in flight
+        // at ~2 us).  On top of that the two waves that share a SIMD (w and w+4) run one slot out
+        // of phase: while one feeds the matrix core from registers (8 MFMAs, ~512 cycles) the other
+        // pulls its next fragments out of LDS.  Slots are separated by workgroup barriers; group 0
+        // (waves 0-3) loads step kt in slot 2kt and computes it in slot 2kt+1, group 1 (waves 4-7)
+        // one slot later.  The DMA for step kt+kDepth goes into the ring slot of step kt-1, which
+        // group 1 read last in slot 2kt-1; each group issues its share in its own load slot (2kt / 2kt+1)
+        // so that a wave never has memory instructions queued ahead of its MFMAs.  Before the
+        // barrier that ends slot 2kt+1 every wave waits until all but its newest 4*(kDepth-1) DMA
+        // instructions have landed, i.e. until step kt+1 is complete.
+        v8i fa[4], fb[2];
+        auto load_frags = [&](int stage) {
             const uint8_t *sA = smem + stage * kStageBytes + a_frag_base;
             const uint8_t *sB = smem + stage * kStageBytes;
 #pragma unroll
-            for (int kh = 0; kh < 2; ++kh) {
-                v8i a[4], b[2];
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb) {
-                    const uint4 lo = *reinterpret_cast<const uint4 *>(sA + mb * 32 * BK + frag_off[kh][0]);
-                    const uint4 hi = *reinterpret_cast<const uint4 *>(sA + mb * 32 * BK + frag_off[kh][1]);
-                    a[mb] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-                }
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb) {
-                    const uint4 lo = *reinterpret_cast<const uint4 *>(sB + b_frag_base[nb] + frag_off[kh][0]);
-                    const uint4 hi = *reinterpret_cast<const uint4 *>(sB + b_frag_base[nb] + frag_off[kh][1]);
-                    b[nb] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-                }
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                    for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma<AFMT>(a[mb], b[nb], acc[mb][nb]);
+            for (int mb = 0; mb < 4; ++mb) {
+                const uint4 lo = *reinterpret_cast<const uint4 *>(sA + mb * 32 * BK + frag_off[0]);
+                const uint4 hi = *reinterpret_cast<const uint4 *>(sA + mb * 32 * BK + frag_off[1]);
+                fa[mb] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
             }
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const uint4 lo = *reinterpret_cast<const uint4 *>(sB + b_frag_base[nb] + frag_off[0]);
+                const uint4 hi = *reinterpret_cast<const uint4 *>(sB + b_frag_base[nb] + frag_off[1]);
+                fb[nb] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            }
+        };
+        auto compute = [&]() {
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma<AFMT>(fa[mb], fb[nb], acc[mb][nb]);
+        };
+        auto slot_end = [&]() {   // every wave executes the same number of these
+            __builtin_amdgcn_sched_barrier(0);
+            if (!(SSG_GEMM_EXPERIMENT & 4)) __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        static_assert(kDepth == 4, "the vmcnt immediates below assume 4 steps in flight, 4 DMA instructions per wave and step");
+
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) issue(d, d);
+        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");     // step 0 has landed
+        slot_end();
+        int rd = 0, wr = kDepth;               // ring slots of step kt and of step kt + kDepth
+        if (wm == 0) {
+            for (int kt = 0; kt < nk; ++kt) {
+                if (!(SSG_GEMM_EXPERIMENT & 1)) issue(kt + kDepth, wr);
+                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frags(rd);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                slot_end();
+                if (TWO_SEG && kt == nk1) rescale_for_second_product();
+                compute();
+                asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+                slot_end();
+                rd = rd + 1 == kStages ? 0 : rd + 1;
+                wr = wr + 1 == kStages ? 0 : wr + 1;
+            }
+            slot_end();
+        } else {
+            for (int kt = 0; kt < nk; ++kt) {
+                if (kt > 0) {                  // step kt-1
+                    if (TWO_SEG && kt - 1 == nk1) rescale_for_second_product();
+                    compute();
+                }
+                slot_end();
+                if (!(SSG_GEMM_EXPERIMENT & 1)) issue(kt + kDepth, wr);
+                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frags(rd);
+                asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
+                slot_end();
+                rd = rd + 1 == kStages ? 0 : rd + 1;
+                wr = wr + 1 == kStages ? 0 : wr + 1;
+            }
+            if (TWO_SEG && nk - 1 == nk1) rescale_for_second_product();
+            compute();
+            slot_end();
         }
+        // drain the zero-filled steps still in flight before LDS is reused (next segment / epilogue)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
     }
 
     // ---- epilogue.  Block (mb, nb), register i, lane l holds
@@ -395,10 +466,17 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
 
 template <int EPI>
 static void launch_epi(const GemmParams &p, int a_fmt, unsigned blocks, hipStream_t st) {
+    if (EPI == EPI_STORE && p.A2) {        // two K segments: only the E5M2 x E4M3 input-gradient product uses it
+        if (a_fmt == kE4M3)
+            hipLaunchKernelGGL((gemm_kernel<EPI_STORE, kE4M3, true>), dim3(blocks), dim3(kThreads), 0, st, p);
+        else
+            hipLaunchKernelGGL((gemm_kernel<EPI_STORE, kE5M2, true>), dim3(blocks), dim3(kThreads), 0, st, p);
+        return;
+    }
     if (a_fmt == kE4M3)
-        hipLaunchKernelGGL((gemm_kernel<EPI, kE4M3>), dim3(blocks), dim3(kThreads), 0, st, p);
+        hipLaunchKernelGGL((gemm_kernel<EPI, kE4M3, false>), dim3(blocks), dim3(kThreads), 0, st, p);
     else
-        hipLaunchKernelGGL((gemm_kernel<EPI, kE5M2>), dim3(blocks), dim3(kThreads), 0, st, p);
+        hipLaunchKernelGGL((gemm_kernel<EPI, kE5M2, false>), dim3(blocks), dim3(kThreads), 0, st, p);
 }
 
 void launch_gemm(const GemmArgs &a, hipStream_t st) {
