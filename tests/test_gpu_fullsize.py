@@ -1,0 +1,183 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot run a whole 7B-shape block inside a test, so these tests check (i) what is cheap
+in full (per-tensor quantization of x and dY, scales), (ii) sampled outputs that the oracle computes
+one by one as full-K fp64 dot products over the device's own stored FP8 operands, and (iii)
+properties that hold at any size (every live channel fills the format, factors follow the maxima).
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import fp8, gemm, mlp, quant, swiglu
+
+pytestmark = pytest.mark.gpu
+
+import paper_2409_12517_amd as ssg  # noqa: E402
+import gpu_util as gu  # noqa: E402
+from test_gpu_mlp import Block  # noqa: E402
+
+
+def sampled_gemm_check(Aq, a_fmt, Bq, C, scale, n, rng, what, bf16_out, col_factor=None, A2=None, B2=None, scale2=None):
+    """C[m, j] for n random (m, j): fp64 dot of the stored codes, times `scale` (and a per-column factor)."""
+    M, N = C.shape
+    mi = torch.from_numpy(rng.integers(0, M, n)); ni = torch.from_numpy(rng.integers(0, N, n))
+    a = gu.u8(Aq[mi.to(Aq.device)]); b = gu.u8(Bq[ni.to(Bq.device)])
+    ref = (fp8.decode(a, a_fmt) * fp8.decode(b, fp8.E4M3)).sum(axis=1) * scale
+    if A2 is not None:
+        a2 = gu.u8(A2[mi.to(A2.device)]); b2 = gu.u8(B2[ni.to(B2.device)])
+        ref = ref + (fp8.decode(a2, a_fmt) * fp8.decode(b2, fp8.E4M3)).sum(axis=1) * scale2
+    if col_factor is not None:
+        ref = ref * col_factor[ni.numpy()].astype(np.float64)
+    got = gu.f32(C[mi.to(C.device), ni.to(C.device)]).astype(np.float64)
+    tol = 2e-3 * np.abs(ref).max() + (gu.bf16_ulp(ref) if bf16_out else 0.0)
+    assert np.all(np.abs(got - ref) <= tol), f"{what}: max err {np.abs(got - ref).max():.3g} vs {2e-3 * np.abs(ref).max():.3g}"
+    return mi, ni, ref
+
+
+def run_and_check(name, backward=True, n_samples=192):
+    cfg = synth.CONFIGS[name]
+    inp = synth.make_inputs(cfg.T, cfg.d, cfg.f, cfg.seed, cfg.w_std, backward=backward,
+                            aligned_channels=cfg.aligned_channels)
+    T, d, f = cfg.T, cfg.d, cfg.f
+    blk = Block(inp)
+    blk.fwd()
+    rng = np.random.default_rng(cfg.seed)
+    sc = gu.f32(blk.sv("scales", (8,), torch.float32))
+    # (i) full per-tensor quantization of x
+    xq_ref, sx_ref, _ = quant.quantize_per_tensor(synth.bf16_to_f32_numpy(inp["x"]), fp8.E4M3)
+    x_q = blk.sv("x_q", (T, d), torch.uint8)
+    assert sc[0] == sx_ref and np.array_equal(gu.u8(x_q), xq_ref)
+    assert torch.equal(blk.sv("x_qT", (d, T), torch.uint8), x_q.t())
+    # weights: scale in full (amax is cheap), codes on sampled rows
+    for k, nm, slot in (("W1", "w1_q", 1), ("W2", "w2_q", 2)):
+        w = inp[k]
+        s_ref = quant.scale_from_amax(np.float32(w.abs().max().float().item()), fp8.E4M3)
+        assert sc[slot] == s_ref
+        rows = torch.from_numpy(rng.integers(0, f, 64))
+        ref = quant.cast_with_scale(synth.bf16_to_f32_numpy(w[rows]), s_ref, fp8.E4M3)
+        wq = blk.sv(nm, (f, d), torch.uint8)
+        assert np.array_equal(gu.u8(wq[rows.to(gu.DEV)]), ref)
+        assert torch.equal(blk.sv(nm + "T", (d, f), torch.uint8), wq.t())
+    w1_q, w2_q = blk.sv("w1_q", (f, d), torch.uint8), blk.sv("w2_q", (f, d), torch.uint8)
+    U, G = blk.sv("U", (T, f), torch.bfloat16), blk.sv("G", (T, f), torch.bfloat16)
+    # (ii) sampled U, G
+    sampled_gemm_check(x_q, fp8.E4M3, w1_q, U, 1.0 / (float(sc[0]) * float(sc[1])), n_samples, rng, "U", True)
+    sampled_gemm_check(x_q, fp8.E4M3, w2_q, G, 1.0 / (float(sc[0]) * float(sc[2])), n_samples, rng, "G", True)
+    # (iii) channel maxima, factors and codes from the device's own fp32 h
+    h = gu.empty_f32(T, f)
+    ssg.ssg_swiglu(U, G, T, f, h)
+    torch.cuda.synchronize()
+    camax = blk.sv("h_camax", (f,), torch.float32)
+    assert torch.equal(camax, h.abs().amax(dim=0))
+    a = gu.f32(camax)
+    s_ref = quant.scale_from_amax(a, fp8.E4M3)
+    sinv_ref = np.where(a > 0, a / np.float32(448), np.float32(1)).astype(np.float32)
+    s = gu.f32(blk.sv("s", (f,), torch.float32))
+    assert np.array_equal(s, s_ref) and np.array_equal(gu.f32(blk.sv("sinv", (f,), torch.float32)), sinv_ref)
+    h_q = blk.sv("h_q", (T, f), torch.uint8)
+    assert bool(((h_q & 0x7F).amax(dim=0) == 0x7E).all())            # every channel fills the format
+    assert torch.equal(blk.sv("h_qT", (f, T), torch.uint8), h_q.t())
+    cols = torch.from_numpy(rng.integers(0, f, 48))
+    hq_ref = quant.cast_with_scale(gu.f32(h[:, cols.to(gu.DEV)]), s_ref[cols.numpy()][None, :], fp8.E4M3)
+    assert np.array_equal(gu.u8(h_q[:, cols.to(gu.DEV)]), hq_ref)
+    # sampled h against the oracle's fp64 product
+    ti = torch.from_numpy(rng.integers(0, T, 4096)).to(gu.DEV); ci = torch.from_numpy(rng.integers(0, f, 4096)).to(gu.DEV)
+    h_ref = swiglu.swiglu(gu.f32(U[ti, ci]), gu.f32(G[ti, ci]))
+    assert np.all(np.abs(gu.f32(h[ti, ci]) - h_ref) <= 4 * 2.0 ** -23 * np.abs(h_ref) + 1e-37)
+    del h
+    # folded w3: sampled columns, full range
+    w3_q = blk.sv("w3_q", (d, f), torch.uint8)
+    w3 = synth.bf16_to_f32_numpy(inp["W3"])
+    amax_w3s = np.abs(w3).max(axis=0) * sinv_ref
+    assert sc[7] == amax_w3s.astype(np.float32).max()
+    sw3_ref = quant.scale_from_amax(np.float32(sc[7]), fp8.E4M3)
+    assert sc[3] == sw3_ref
+    w3s = (w3[:, cols.numpy()] * sinv_ref[cols.numpy()][None, :]).astype(np.float32)
+    assert np.array_equal(gu.u8(w3_q[:, cols.to(gu.DEV)]), quant.cast_with_scale(w3s, sw3_ref, fp8.E4M3))
+    assert torch.equal(blk.sv("w3_qT", (f, d), torch.uint8), w3_q.t())
+    del w3
+    # sampled y
+    sampled_gemm_check(h_q, fp8.E4M3, w3_q, blk.y, 1.0 / float(sc[3]), n_samples, rng, "Y", True)
+    if not backward:
+        return blk, inp
+    blk.bwd()
+    wsc = gu.f32(blk.wv("scales", (8,), torch.float32))
+    dyq_ref, sdy_ref, _ = quant.quantize_per_tensor(synth.bf16_to_f32_numpy(inp["dY"]), fp8.E5M2)
+    dy_q = blk.wv("dy_q", (T, d), torch.uint8)
+    assert wsc[0] == sdy_ref and np.array_equal(gu.u8(dy_q), dyq_ref)
+    dy_qT = blk.wv("dy_qT", (d, T), torch.uint8)
+    assert torch.equal(dy_qT, dy_q.t())
+    # sampled dH -> dU, dG through the oracle's SwiGLU derivative
+    w3_qT = blk.sv("w3_qT", (f, d), torch.uint8)
+    dU, dG = blk.wv("dU", (T, f), torch.bfloat16), blk.wv("dG", (T, f), torch.bfloat16)
+    mi = torch.from_numpy(rng.integers(0, T, n_samples)); ni = torch.from_numpy(rng.integers(0, f, n_samples))
+    acc = (fp8.decode(gu.u8(dy_q[mi.to(gu.DEV)]), fp8.E5M2) * fp8.decode(gu.u8(w3_qT[ni.to(gu.DEV)]), fp8.E4M3)).sum(axis=1)
+    dH = acc / (float(wsc[0]) * float(sc[3])) * s[ni.numpy()].astype(np.float64)
+    du_ref, dg_ref = swiglu.swiglu_grads(gu.f32(U[mi.to(gu.DEV), ni.to(gu.DEV)]), gu.f32(G[mi.to(gu.DEV), ni.to(gu.DEV)]), dH)
+    for got_t, ref, nm in ((dU, du_ref, "dU"), (dG, dg_ref, "dG")):
+        got = gu.f32(got_t[mi.to(gu.DEV), ni.to(gu.DEV)]).astype(np.float64)
+        tol = 2e-3 * np.abs(ref).max() + gu.bf16_ulp(ref)
+        assert np.all(np.abs(got - ref) <= tol), nm
+    # quantization of the device's dU, dG: scales in full, codes on sampled rows
+    for nm, slot_s, slot_a, src in (("du_q", 1, 4, dU), ("dg_q", 2, 5, dG)):
+        am = np.float32(src.abs().max().float().item())
+        assert wsc[slot_a] == am and wsc[slot_s] == quant.scale_from_amax(am, fp8.E5M2)
+        rows = torch.from_numpy(rng.integers(0, T, 32)).to(gu.DEV)
+        q = blk.wv(nm, (T, f), torch.uint8)
+        assert np.array_equal(gu.u8(q[rows]), quant.cast_with_scale(gu.f32(src[rows]), np.float32(wsc[slot_s]), fp8.E5M2))
+        assert torch.equal(blk.wv(nm + "T", (f, T), torch.uint8), q.t())
+    du_q, dg_q = blk.wv("du_q", (T, f), torch.uint8), blk.wv("dg_q", (T, f), torch.uint8)
+    sampled_gemm_check(du_q, fp8.E5M2, blk.sv("w1_qT", (d, f), torch.uint8), blk.dx,
+                       1.0 / (float(wsc[1]) * float(sc[1])), n_samples, rng, "dX", True,
+                       A2=dg_q, B2=blk.sv("w2_qT", (d, f), torch.uint8), scale2=1.0 / (float(wsc[2]) * float(sc[2])))
+    x_qT = blk.sv("x_qT", (d, T), torch.uint8)
+    sampled_gemm_check(blk.wv("du_qT", (f, T), torch.uint8), fp8.E5M2, x_qT, blk.dW1,
+                       1.0 / (float(wsc[1]) * float(sc[0])), n_samples, rng, "dW1", False)
+    sampled_gemm_check(blk.wv("dg_qT", (f, T), torch.uint8), fp8.E5M2, x_qT, blk.dW2,
+                       1.0 / (float(wsc[2]) * float(sc[0])), n_samples, rng, "dW2", False)
+    sampled_gemm_check(dy_qT, fp8.E5M2, blk.sv("h_qT", (f, T), torch.uint8), blk.dW3,
+                       1.0 / float(wsc[0]), n_samples, rng, "dW3", False, col_factor=sinv_ref)
+    return blk, inp
+
+
+def test_llama7b_shape_forward_backward():
+    run_and_check("7b", backward=True)
+
+
+def test_large_shape_forward_backward():
+    blk, _ = run_and_check("large", backward=True, n_samples=96)
+    del blk
+    torch.cuda.empty_cache()
+
+
+def test_outlier_stress_shape_saturation_report():
+    """Aligned, large-norm channels (Section 4.3): under a stale per-tensor scale the spikes overflow
+    E4M3 (Section 3); a current per-tensor scale avoids overflow but flushes ordinary channels to
+    zero; the per-channel factors of Section 4.4 do neither."""
+    blk, inp = run_and_check("7b_stress", backward=False, n_samples=96)
+    cfg = synth.CONFIGS["7b_stress"]
+    T, d, f = cfg.T, cfg.d, cfg.f
+    chans = inp["aligned"].numpy()
+    h = gu.empty_f32(T, f)
+    ssg.ssg_swiglu(blk.sv("U", (T, f), torch.bfloat16), blk.sv("G", (T, f), torch.bfloat16), T, f, h)
+    torch.cuda.synchronize()
+    a = gu.f32(blk.sv("h_camax", (f,), torch.float32))
+    calm = np.setdiff1d(np.arange(f), chans)
+    assert a[chans].min() > 50 * np.median(a[calm])                 # the spikes are there
+    # stale scale: what a per-tensor scale from the calm channels (earlier iterations) would be
+    stale = quant.scale_from_amax(np.float32(a[calm].max()), fp8.E4M3)
+    sub = h[:, torch.from_numpy(chans).to(gu.DEV)]
+    sat_stale = quant.count_saturated(gu.f32(sub), stale, fp8.E4M3)
+    sat_smooth = quant.count_saturated(gu.f32(sub), gu.f32(blk.sv("s", (f,), torch.float32))[chans][None, :], fp8.E4M3)
+    assert sat_stale > 0 and sat_smooth == 0
+    # flush-to-zero: Smooth-SwiGLU codes vs a current per-tensor scale, counted on the device
+    h_q = blk.sv("h_q", (T, f), torch.uint8)
+    flushed_smooth = int((((h_q & 0x7F) == 0) & (h != 0)).sum().item())
+    cur = float(quant.scale_from_amax(np.float32(a.max()), fp8.E4M3))
+    half_min_sub = 2.0 ** -10
+    flushed_current = int(((h.abs() * cur <= half_min_sub) & (h != 0)).sum().item())
+    print(f"\nstress: saturated(stale per-tensor) {sat_stale}, saturated(smooth) {sat_smooth}; "
+          f"flushed to zero: current per-tensor {flushed_current}, smooth {flushed_smooth} of {T * f}")
+    assert flushed_current > 10 * max(flushed_smooth, 1)
