@@ -27,12 +27,17 @@ if ROOT not in sys.path:
 
 PEAK_FP8_TFLOPS = 5000.0          # MI355X dense FP8 MFMA peak (published: 5.0 PFLOP/s)
 METRIC = "FP8 Smooth-SwiGLU MLP fwd+bwd TFLOP/s (7B shape), % of FP8 MFMA peak"
-TAG_NAMES = {0: "gemm_kernel<STORE,E4M3>", 1: "gemm_kernel<STORE,E5M2>", 2: "gemm_kernel<SWIGLU,E4M3>",
-             5: "gemm_kernel<SWIGLU_BWD,E5M2>"}
+# tag of ssg_profile_read -> kernel symbol as rocprofv3 prints it (template args: epilogue, A format, two products)
+TAG_NAMES = {0: "gemm_kernel<0, 0, false>", 1: "gemm_kernel<0, 1, false>", 2: "gemm_kernel<1, 0, false>",
+             5: "gemm_kernel<2, 1, false>", 9: "gemm_kernel<0, 1, true>"}
+TAG_ROLES = {0: "y = h^ w3~^T", 1: "dW3, dW1, dW2", 2: "U, G + SwiGLU + channel maxima", 5: "dH + SwiGLU backward",
+             9: "dX (two products)"}
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command (see profiles/); None until such a run has been recorded for the current kernel.
-MEASURED_TRAFFIC_BYTES = None
+# L2<->memory bytes per launch of the dominant kernel (gemm_kernel<0, 1, false>: dW3, dW1, dW2) from two
+# rocprofv3 --pmc runs of this command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
+# reads for a 1 GiB copy (factors 2.000 and 1.000); see profiles/bench_7b_hbm_traffic.txt.  Algorithmic
+# bytes of that launch: 61.9 MB of FP8 operands read + 180.4 MB of fp32 written.
+MEASURED_TRAFFIC_BYTES = {"gemm_kernel<0, 1, false>": 321.3e6 + 180.8e6}
 
 
 def gemm_flops_by_tag(T, d, f):
@@ -42,7 +47,8 @@ def gemm_flops_by_tag(T, d, f):
         0: (one, 1),          # y = h^ w3~^T
         2: (2 * one, 1),      # U and G in one launch
         5: (one, 1),          # dH
-        1: (5 * one, 4),      # dW3, dX (two products), dW1, dW2
+        1: (3 * one, 3),      # dW3, dW1, dW2
+        9: (2 * one, 1),      # dX: two products in one launch
     }
 
 
@@ -75,7 +81,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="7b", help="name in synth.CONFIGS (default: the headline shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=256)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=512)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="first run three 1 GiB device-to-device copies (a kernel of known traffic, used to "
+                         "calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -108,6 +117,14 @@ def main() -> int:
         ssg.ssg_mlp_fwd(desc, x, W1, W2, W3, y, saved, stream)
         ssg.ssg_mlp_bwd(desc, dY, saved, dx, dW1, dW2, dW3, work, stream)
 
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -138,7 +155,7 @@ def main() -> int:
         flops_per_launch = fl[tg][0] / fl[tg][1]
         avg = sum(v) / len(v)
         kernels[TAG_NAMES.get(tg, str(tg))] = {
-            "launches_per_step": fl[tg][1], "avg_ms": avg,
+            "role": TAG_ROLES.get(tg, ""), "launches_per_step": fl[tg][1], "avg_ms": avg,
             "tflops": flops_per_launch / (avg * 1e-3) / 1e12}
     dom_tag = max(per_tag, key=lambda tg: sum(per_tag[tg]))
     dom_avg = sum(per_tag[dom_tag]) / len(per_tag[dom_tag])
@@ -147,7 +164,7 @@ def main() -> int:
     gemm_ms = sum(ms_list) / args.steps
     roofline = {"bound": "mfma", "kernel": TAG_NAMES.get(dom_tag, str(dom_tag)), "achieved": achieved,
                 "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP8_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES, "avg_launch_ms": dom_avg,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(TAG_NAMES.get(dom_tag, "")), "avg_launch_ms": dom_avg,
                 "flops_per_launch": dom_flops, "all_gemm_ms_per_step": gemm_ms,
                 "non_gemm_ms_per_step": ms_per_step - gemm_ms, "kernels": kernels}
 

@@ -167,7 +167,8 @@ ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspac
  *                          milliseconds and their tags (host arrays), clears the record list and
  *                          returns the number written, or a negative ssg_status.
  *                          tag = 2 * epilogue + a_fmt with epilogue 0 = plain store (y, dx, dW),
- *                          1 = fused SwiGLU forward (U, G, channel maxima), 2 = fused SwiGLU backward. */
+ *                          1 = fused SwiGLU forward (U, G, channel maxima), 2 = fused SwiGLU backward;
+ *                          +8 for the two-product form of the plain store (dx). */
 ssg_status ssg_profile_enable(int max_records);
 int ssg_profile_read(float *ms, int *tags, int cap);
 

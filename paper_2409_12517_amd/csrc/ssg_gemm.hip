@@ -492,7 +492,7 @@ void launch_gemm(const GemmArgs &a, hipStream_t st) {
     const int n_per_tile = a.epilogue == EPI_SWIGLU ? BN / 2 : BN;
     p.tiles_n = (int)((a.N + n_per_tile - 1) / n_per_tile);
     const unsigned blocks = (unsigned)p.tiles_m * (unsigned)p.tiles_n;
-    profile_before(2 * a.epilogue + a.a_fmt, st);
+    profile_before(2 * a.epilogue + a.a_fmt + (a.epilogue == EPI_STORE && a.A2 ? 8 : 0), st);
     switch (a.epilogue) {
         case EPI_STORE: launch_epi<EPI_STORE>(p, a.a_fmt, blocks, st); break;
         case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(p, a.a_fmt, blocks, st); break;
