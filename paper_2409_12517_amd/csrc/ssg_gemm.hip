@@ -33,17 +33,23 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef __attribute__((address_space(1))) const void *global_void_ptr;
 
+#ifndef SSG_GEMM_EXPERIMENT
+#define SSG_GEMM_EXPERIMENT 0   /* timing experiments only: 1 = no DMA in loop, 2 = no LDS reads, 4 = no barriers, 8 = timeline */
+#endif
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kThreads = 512;
 constexpr int kTileBytes = BM * BK;               // one operand tile of one K step, 16 KB
 constexpr int kStageBytes = 2 * kTileBytes;       // A + B, 32 KB
 constexpr int kStages = 5;                        // ring of K steps in LDS: all 160 KB
 constexpr int kDepth = kStages - 1;               // K steps in flight ahead of the one being read
-#ifndef SSG_GEMM_EXPERIMENT
-#define SSG_GEMM_EXPERIMENT 0   /* timing experiments only: 1 = no DMA in loop, 2 = no LDS reads, 4 = no barriers */
-#endif
 
 __device__ uint4 g_zero_chunk = {0u, 0u, 0u, 0u}; // source of the zero fill of a ragged K tail
+#if SSG_GEMM_EXPERIMENT & 8
+__device__ unsigned long long g_dbg[8192];
+#define SSG_STAMP(code) do { if (dbg_on && dbg_n < 2000) { g_dbg[dbg_base + dbg_n++] = (__builtin_readcyclecounter() << 4) | (code); } } while (0)
+#else
+#define SSG_STAMP(code) do { } while (0)
+#endif
 
 struct GemmParams {
     const uint8_t *A, *B, *A2, *B2;
@@ -225,8 +231,9 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         // pulls its next fragments out of LDS.  Slots are separated by workgroup barriers; group 0
         // (waves 0-3) loads step kt in slot 2kt and computes it in slot 2kt+1, group 1 (waves 4-7)
         // one slot later.  The DMA for step kt+kDepth goes into the ring slot of step kt-1, which
-        // group 1 read last in slot 2kt-1; each group issues its share in its own load slot (2kt / 2kt+1)
-        // so that a wave never has memory instructions queued ahead of its MFMAs.  Before the
+        // group 1 read last in slot 2kt-1; each group issues its share in its own load slot (2kt / 2kt+1),
+        // after its LDS reads, so that a wave never has memory instructions queued ahead of its MFMAs
+        // (the vector-memory path takes ~20 cycles per 1 KB instruction when all waves push at once).  Before the
         // barrier that ends slot 2kt+1 every wave waits until all but its newest 4*(kDepth-1) DMA
         // instructions have landed, i.e. until step kt+1 is complete.
         v8i fa[4], fb[2];
@@ -263,16 +270,27 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         for (int d = 0; d < kDepth; ++d) issue(d, d);
         asm volatile("s_waitcnt vmcnt(12)" ::: "memory");     // step 0 has landed
         slot_end();
+#if SSG_GEMM_EXPERIMENT & 8
+        const bool dbg_on = blockIdx.x == 0 && l == 0 && (w == 0 || w == 4);
+        const int dbg_base = (w >> 2) * 4096; int dbg_n = 0;
+#endif
         int rd = 0, wr = kDepth;               // ring slots of step kt and of step kt + kDepth
         if (wm == 0) {
             for (int kt = 0; kt < nk; ++kt) {
+                SSG_STAMP(1);
+                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frags(rd);        // LDS reads first: their latency overlaps the DMA issue
+                __builtin_amdgcn_sched_barrier(0);
+                SSG_STAMP(2);
                 if (!(SSG_GEMM_EXPERIMENT & 1)) issue(kt + kDepth, wr);
-                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frags(rd);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                SSG_STAMP(3);
                 slot_end();
+                SSG_STAMP(4);
                 if (TWO_SEG && kt == nk1) rescale_for_second_product();
                 compute();
+                SSG_STAMP(5);
                 asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+                SSG_STAMP(6);
                 slot_end();
                 rd = rd + 1 == kStages ? 0 : rd + 1;
                 wr = wr + 1 == kStages ? 0 : wr + 1;
@@ -280,14 +298,22 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
             slot_end();
         } else {
             for (int kt = 0; kt < nk; ++kt) {
+                SSG_STAMP(4);
                 if (kt > 0) {                  // step kt-1
                     if (TWO_SEG && kt - 1 == nk1) rescale_for_second_product();
                     compute();
                 }
+                SSG_STAMP(5);
                 slot_end();
-                if (!(SSG_GEMM_EXPERIMENT & 1)) issue(kt + kDepth, wr);
+                SSG_STAMP(1);
                 if (!(SSG_GEMM_EXPERIMENT & 2)) load_frags(rd);
-                asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+                SSG_STAMP(2);
+                if (!(SSG_GEMM_EXPERIMENT & 1)) issue(kt + kDepth, wr);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                SSG_STAMP(3);
+                asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+                SSG_STAMP(6);
                 slot_end();
                 rd = rd + 1 == kStages ? 0 : rd + 1;
                 wr = wr + 1 == kStages ? 0 : wr + 1;
@@ -478,6 +504,12 @@ static void launch_epi(const GemmParams &p, int a_fmt, unsigned blocks, hipStrea
     else
         hipLaunchKernelGGL((gemm_kernel<EPI, kE5M2, false>), dim3(blocks), dim3(kThreads), 0, st, p);
 }
+
+#if SSG_GEMM_EXPERIMENT & 8
+extern "C" int ssg_debug_timeline(unsigned long long *host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg), sizeof(unsigned long long) * n);
+}
+#endif
 
 void launch_gemm(const GemmArgs &a, hipStream_t st) {
     GemmParams p;
