@@ -39,7 +39,7 @@ EXPORTS = [
 
 class ssg_mlp_desc(Structure):
     _fields_ = [("T", c_int64), ("d", c_int64), ("f", c_int64), ("smooth", c_int32), ("rnd", c_int32),
-                ("y_dtype", c_int32), ("dw_dtype", c_int32), ("reserved", c_int32 * 4)]
+                ("y_dtype", c_int32), ("dw_dtype", c_int32), ("weights_cached", c_int32), ("reserved", c_int32 * 3)]
 
 
 class ssg_mlp_saved_view(Structure):
@@ -115,8 +115,8 @@ def _stream(stream):
 
 
 def make_desc(T: int, d: int, f: int, smooth: int = 1, rnd: int = SSG_ROUND_EXACT_DIV,
-              y_dtype: int = SSG_BF16, dw_dtype: int = SSG_F32) -> ssg_mlp_desc:
-    return ssg_mlp_desc(T, d, f, smooth, rnd, y_dtype, dw_dtype, (c_int32 * 4)(0, 0, 0, 0))
+              y_dtype: int = SSG_BF16, dw_dtype: int = SSG_F32, weights_cached: int = 0) -> ssg_mlp_desc:
+    return ssg_mlp_desc(T, d, f, smooth, rnd, y_dtype, dw_dtype, weights_cached, (c_int32 * 3)(0, 0, 0))
 
 
 def ssg_amax(src, src_dtype, n, amax_dev, stream=None):

@@ -108,7 +108,8 @@ ssg_status check_desc(const ssg_mlp_desc *d, const char *who) {
     if (d->smooth != 0 && d->smooth != 1) return fail(SSG_ERR_ARG, "%s: smooth must be 0 or 1", who);
     if (d->rnd != SSG_ROUND_EXACT_DIV && d->rnd != SSG_ROUND_POW2) return fail(SSG_ERR_ARG, "%s: bad rnd", who);
     if (!dtype_ok(d->y_dtype) || !dtype_ok(d->dw_dtype)) return fail(SSG_ERR_ARG, "%s: bad output dtype", who);
-    for (int i = 0; i < 4; ++i)
+    if (d->weights_cached != 0 && d->weights_cached != 1) return fail(SSG_ERR_ARG, "%s: weights_cached must be 0 or 1", who);
+    for (int i = 0; i < 3; ++i)
         if (d->reserved[i] != 0) return fail(SSG_ERR_ARG, "%s: reserved fields must be 0", who);
     return SSG_OK;
 }
@@ -350,8 +351,13 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     float *h_camax = reinterpret_cast<float *>(b + L.h_camax), *w3_camax = reinterpret_cast<float *>(b + L.w3_camax);
     float *s = reinterpret_cast<float *>(b + L.s), *sinv = reinterpret_cast<float *>(b + L.sinv);
 
-    // zero the scalar block and both per-channel maxima (contiguous) in one fill
-    ssg::launch_fill_u32(scb, (L.s - L.scalars) / 4, 0u, st);
+    const bool cached = desc->weights_cached != 0;
+    // zero the running maxima of this call; with cached weights the slots that belong to W1, W2 and
+    // W3 (their scales, ranges and W3's per-channel maxima) are left as the earlier call wrote them
+    const uint32_t per_call = (1u << S_AMAX_X) | (1u << S_AMAX_W3S) | (1u << S_HMAX);
+    const uint32_t per_weight = (1u << S_AMAX_W1) | (1u << S_AMAX_W2);
+    ssg::launch_reset(scb, cached ? per_call : (per_call | per_weight), reinterpret_cast<uint32_t *>(h_camax), (size_t)f,
+                      reinterpret_cast<uint32_t *>(w3_camax), cached ? 0 : (size_t)f, st);
 
     // a1 + a2: per-tensor range (Section 2), then Q (Eq. 2) with the transposed copy the backward
     // contractions read.  Range and cast of one tensor run back to back so that the second read of
@@ -362,13 +368,17 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     c.src = x; c.rows = T; c.cols = dm; c.amax = sc + S_AMAX_X; c.scale_out = sc + S_SX;
     c.dst = b + L.x_q; c.dst_t = b + L.x_qT;
     ssg::launch_cast(c, st);
-    ssg::launch_amax(W1, ssg::SRC_BF16, (size_t)(f * dm), scb + S_AMAX_W1, st);
-    c.src = W1; c.rows = f; c.cols = dm; c.amax = sc + S_AMAX_W1; c.scale_out = sc + S_SW1;
-    c.dst = b + L.w1_q; c.dst_t = b + L.w1_qT;
-    ssg::launch_cast(c, st);
-    ssg::launch_amax(W2, ssg::SRC_BF16, (size_t)(f * dm), scb + S_AMAX_W2, st);
-    c.src = W2; c.amax = sc + S_AMAX_W2; c.scale_out = sc + S_SW2; c.dst = b + L.w2_q; c.dst_t = b + L.w2_qT;
-    ssg::launch_cast(c, st);
+    if (!cached) {
+        ssg::launch_amax(W1, ssg::SRC_BF16, (size_t)(f * dm), scb + S_AMAX_W1, st);
+        c.src = W1; c.rows = f; c.cols = dm; c.amax = sc + S_AMAX_W1; c.scale_out = sc + S_SW1;
+        c.dst = b + L.w1_q; c.dst_t = b + L.w1_qT;
+        ssg::launch_cast(c, st);
+        ssg::launch_amax(W2, ssg::SRC_BF16, (size_t)(f * dm), scb + S_AMAX_W2, st);
+        c.src = W2; c.amax = sc + S_AMAX_W2; c.scale_out = sc + S_SW2; c.dst = b + L.w2_q; c.dst_t = b + L.w2_qT;
+        ssg::launch_cast(c, st);
+        // per-channel range of w3, needed for the range of s^-1 * w3 (constant between weight updates)
+        ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
+    }
 
     // a3 + a4 + first half of a5: both inner products of Eq. 2, bf16 U and G, per-channel max |h|
     ssg::GemmArgs g;
@@ -379,7 +389,6 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     ssg::launch_gemm(g, st);
 
     // a5: factors s_i, s_i^-1 and the range of s^-1 * w3 (from the per-channel range of w3)
-    ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
     ssg::launch_channel_factors(h_camax, w3_camax, f, desc->smooth, s, sinv, scb + S_AMAX_W3S, scb + S_HMAX, st);
 
     // a6: h^ = cast(s_i * h), recomputing h from the stored bf16 U, G

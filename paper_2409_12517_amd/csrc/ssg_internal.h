@@ -11,6 +11,8 @@ enum SrcKind { SRC_BF16 = 0, SRC_F32 = 1, SRC_SWIGLU = 2 };
 
 // ---- elementwise / reduction passes (ssg_quant.hip) -------------------------
 void launch_fill_u32(uint32_t *p, size_t n, uint32_t value, hipStream_t st);
+// zero scalar slots selected by mask (bit i -> scalars[i], i < 32) and two vectors (either may be empty)
+void launch_reset(uint32_t *scalars, uint32_t mask, uint32_t *v1, size_t n1, uint32_t *v2, size_t n2, hipStream_t st);
 
 // amax_bits: running maximum of |x| as float bits (must be zeroed by the caller).
 void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, hipStream_t st);

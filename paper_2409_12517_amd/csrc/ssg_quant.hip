@@ -20,6 +20,20 @@ void launch_fill_u32(uint32_t *p, size_t n, uint32_t value, hipStream_t st) {
     hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, value);
 }
 
+// Zero selected scalar slots (bit i of mask -> slot i) and up to two vectors in one launch.
+__global__ void __launch_bounds__(256)
+reset_kernel(uint32_t *scalars, uint32_t mask, uint32_t *v1, size_t n1, uint32_t *v2, size_t n2) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < 32 && ((mask >> i) & 1u)) scalars[i] = 0u;
+    if (i < n1) v1[i] = 0u;
+    if (i < n2) v2[i] = 0u;
+}
+void launch_reset(uint32_t *scalars, uint32_t mask, uint32_t *v1, size_t n1, uint32_t *v2, size_t n2, hipStream_t st) {
+    size_t n = n1 > n2 ? n1 : n2;
+    if (n < 32) n = 32;
+    hipLaunchKernelGGL(reset_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, scalars, mask, v1, n1, v2, n2);
+}
+
 // ------------------------------------------------------------------ loaders
 // Each loader returns 8 consecutive elements of one row as fp32.
 struct LoadBf16 {

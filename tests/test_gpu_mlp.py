@@ -198,3 +198,20 @@ def test_two_calls_give_identical_bytes():
     torch.cuda.synchronize()
     for a, b in zip(first, (blk.y, blk.dx, blk.dW1, blk.dW2, blk.dW3, blk.saved)):
         assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+def test_cached_weights_give_the_same_bytes():
+    """weights_cached = 1 reuses Q(w1), Q(w2), their scales and W3's per-channel ranges from an earlier
+    call on the same `saved` buffer; every output must equal a call that re-quantizes the weights."""
+    inp = synth.make_inputs(512, 256, 688, seed=41)
+    other = synth.make_inputs(512, 256, 688, seed=42)
+    blk = Block(inp)
+    blk.fwd()                                            # fills the weight part of `saved`
+    blk.x, blk.dY = gu.dev(other["x"]), gu.dev(other["dY"])   # a new micro-batch, same weights
+    blk.desc.weights_cached = 1
+    blk.fwd(); blk.bwd()
+    ref = Block(dict(inp, x=other["x"], dY=other["dY"]))
+    ref.fwd(); ref.bwd()
+    for a, b in ((blk.y, ref.y), (blk.dx, ref.dx), (blk.dW1, ref.dW1), (blk.dW2, ref.dW2), (blk.dW3, ref.dW3),
+                 (blk.saved, ref.saved)):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
