@@ -80,6 +80,16 @@ __device__ __forceinline__ void dma16(const uint8_t *g, uint32_t lds_addr) {
 #endif
 }
 
+// Same with a wave-uniform 64-bit base in SGPRs and a 32-bit per-lane byte offset: no VALU work per issue.
+__device__ __forceinline__ void dma16_s(const uint8_t *base_uniform, uint32_t lane_off, uint32_t lds_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base_uniform) : "memory");
+#else
+    (void)base_uniform; (void)lane_off; (void)lds_addr;
+#endif
+}
+
 template <int AFMT>
 __device__ __forceinline__ v16f mfma(const v8i &a, const v8i &b, const v16f &c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, AFMT, 0, 0, 0, 0, 0);
@@ -193,19 +203,32 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         }
         // K step kt -> ring slot `stage`.  Steps past the end of K fetch only zeros (every chunk is
         // out of range), which keeps the number of outstanding DMA instructions uniform.
+        // fast path operands: uniform base pointer (SGPRs) + this lane's 32-bit offset per DMA slot
+        uint32_t a_lane[2], b_lane[2], a2_lane[2] = {0, 0}, b2_lane[2] = {0, 0};
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            a_lane[j] = a_off[j] + chunk * 16;
+            b_lane[j] = b_off[j] + chunk * 16;
+            if (TWO_SEG) {
+                a2_lane[j] = (uint32_t)(a2_ptr[j] - p.A2);
+                b2_lane[j] = (uint32_t)(b2_ptr[j] - p.B2);
+            }
+        }
         auto issue = [&](int kt, int stage) {
             const uint32_t sbase = smem_base + (uint32_t)stage * kStageBytes;
             const bool second = TWO_SEG && kt >= nk1;
             const int64_t kbase = (int64_t)(second ? kt - nk1 : kt) * BK;
             const int64_t Kseg = second ? p.K2 : p.K;
-            const uint8_t *pa0 = second ? a2_ptr[0] : a_ptr[0], *pa1 = second ? a2_ptr[1] : a_ptr[1];
-            const uint8_t *pb0 = second ? b2_ptr[0] : b_ptr[0], *pb1 = second ? b2_ptr[1] : b_ptr[1];
-            if (kbase + BK <= Kseg) {          // whole step in range (uniform branch): no per-lane select
-                dma16(pa0 + kbase, sbase + lds_a);
-                dma16(pb0 + kbase, sbase + lds_b);
-                dma16(pa1 + kbase, sbase + lds_a + 1024);
-                dma16(pb1 + kbase, sbase + lds_b + 1024);
+            if (kbase + BK <= Kseg) {          // whole step in range (uniform branch): scalar base + lane offset
+                const uint8_t *ua = (second ? p.A2 : p.A) + kbase;
+                const uint8_t *ub = (second ? p.B2 : b_src) + kbase;
+                dma16_s(ua, second ? a2_lane[0] : a_lane[0], sbase + lds_a);
+                dma16_s(ub, second ? b2_lane[0] : b_lane[0], sbase + lds_b);
+                dma16_s(ua, second ? a2_lane[1] : a_lane[1], sbase + lds_a + 1024);
+                dma16_s(ub, second ? b2_lane[1] : b_lane[1], sbase + lds_b + 1024);
             } else {
+                const uint8_t *pa0 = second ? a2_ptr[0] : a_ptr[0], *pa1 = second ? a2_ptr[1] : a_ptr[1];
+                const uint8_t *pb0 = second ? b2_ptr[0] : b_ptr[0], *pb1 = second ? b2_ptr[1] : b_ptr[1];
                 const bool k_ok = kbase + chunk * 16 < Kseg;   // K is a multiple of 16: a chunk is all in or all out
                 const uint8_t *zero = reinterpret_cast<const uint8_t *>(&g_zero_chunk);
                 dma16(k_ok ? pa0 + kbase : zero, sbase + lds_a);
@@ -241,7 +264,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
             const uint8_t *sA = smem + stage * kStageBytes + a_frag_base;
             const uint8_t *sB = smem + stage * kStageBytes;
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb) {
+            for (int mb = 0; mb < ((SSG_GEMM_EXPERIMENT & 16) ? 2 : 4); ++mb) {
                 const uint4 lo = *reinterpret_cast<const uint4 *>(sA + mb * 32 * BK + frag_off[0]);
                 const uint4 hi = *reinterpret_cast<const uint4 *>(sA + mb * 32 * BK + frag_off[1]);
                 fa[mb] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
@@ -258,6 +281,20 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
             for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma<AFMT>(fa[mb], fb[nb], acc[mb][nb]);
+        };
+        // A load slot has two jobs that use different pipes: 12 LDS reads (LDS pipe) and 4 DMA
+        // instructions (vector-memory pipe, ~20 cycles per 1 KB instruction when contended).  Half of
+        // the waves do them in one order and half in the other, so both pipes are busy at once.
+        auto load_slot = [&](int kt, int rd_slot, int wr_slot) {
+            if (wn & 1) {
+                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frags(rd_slot);
+                __builtin_amdgcn_sched_barrier(0);
+                if (!(SSG_GEMM_EXPERIMENT & 1)) issue(kt + kDepth, wr_slot);
+            } else {
+                if (!(SSG_GEMM_EXPERIMENT & 1)) issue(kt + kDepth, wr_slot);
+                __builtin_amdgcn_sched_barrier(0);
+                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frags(rd_slot);
+            }
         };
         auto slot_end = [&]() {   // every wave executes the same number of these
             __builtin_amdgcn_sched_barrier(0);
@@ -278,10 +315,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         if (wm == 0) {
             for (int kt = 0; kt < nk; ++kt) {
                 SSG_STAMP(1);
-                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frags(rd);        // LDS reads first: their latency overlaps the DMA issue
-                __builtin_amdgcn_sched_barrier(0);
-                SSG_STAMP(2);
-                if (!(SSG_GEMM_EXPERIMENT & 1)) issue(kt + kDepth, wr);
+                load_slot(kt, rd, wr);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 SSG_STAMP(3);
                 slot_end();
@@ -306,10 +340,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                 SSG_STAMP(5);
                 slot_end();
                 SSG_STAMP(1);
-                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frags(rd);
-                __builtin_amdgcn_sched_barrier(0);
-                SSG_STAMP(2);
-                if (!(SSG_GEMM_EXPERIMENT & 1)) issue(kt + kDepth, wr);
+                load_slot(kt, rd, wr);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 SSG_STAMP(3);
                 asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
