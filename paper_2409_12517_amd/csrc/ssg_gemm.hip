@@ -36,12 +36,10 @@ typedef __attribute__((address_space(1))) const void *global_void_ptr;
 #ifndef SSG_GEMM_EXPERIMENT
 #define SSG_GEMM_EXPERIMENT 0   /* timing experiments only: 1 = no DMA in loop, 2 = no LDS reads, 4 = no barriers, 8 = timeline */
 #endif
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BM = 256, BN = 256, BK = 128;
 constexpr int kThreads = 512;
-constexpr int kTileBytes = BM * BK;               // one operand tile of one K step, 16 KB
-constexpr int kStageBytes = 2 * kTileBytes;       // A + B, 32 KB
-constexpr int kStages = 5;                        // ring of K steps in LDS: all 160 KB
-constexpr int kDepth = kStages - 1;               // K steps in flight ahead of the one being read
+constexpr int kUnitBytes = BM * BK;               // one operand tile of one K step: 256 rows x 128 B = 32 KB
+constexpr int kUnits = 5;                         // ring of operand tiles in LDS: all 160 KB
 
 __device__ uint4 g_zero_chunk = {0u, 0u, 0u, 0u}; // source of the zero fill of a ragged K tail
 #if SSG_GEMM_EXPERIMENT & 8
@@ -62,10 +60,11 @@ struct GemmParams {
     int tiles_m, tiles_n;
 };
 
-// An LDS row holds the 64 bytes (four 16-byte chunks) of one matrix row for one K step.  Four rows
-// fill the 256-byte bank period, so rows r, r+4, r+8, r+12 would collide when 16 lanes read the
-// same chunk of 16 consecutive rows; XOR-ing the chunk index with (r >> 2) & 3 spreads them.
-__device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
+// An LDS row holds the 128 bytes (eight 16-byte chunks, one full cache line) of one matrix row for one
+// K step.  Two rows fill the 256-byte bank period, so rows r, r+2, r+4, ... would collide when 16
+// lanes read the same chunk of 16 consecutive rows; XOR-ing the chunk index with (r >> 1) & 7
+// spreads 16 consecutive rows over the sixteen 16-byte bank groups.
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
 // Direct-to-LDS loads are issued through inline assembly: the compiler would otherwise wait for
 // ALL outstanding LDS-DMA loads before every ds_read (it cannot tell the two LDS stages apart),
@@ -104,7 +103,7 @@ __device__ __forceinline__ float inv_scale_product(const float *sa, const float 
 
 template <int EPI, int AFMT, bool TWO_SEG>
 __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
-    __shared__ __attribute__((aligned(1024))) uint8_t smem[kStages * kStageBytes];
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[kUnits * kUnitBytes];
 
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;   // wave index is uniform: keep it scalar
@@ -136,40 +135,43 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     // SWIGLU: a tile covers 128 channels (128 rows of W1 + the same 128 rows of W2)
     const int64_t n0 = (int64_t)tile_n * (EPI == EPI_SWIGLU ? BN / 2 : BN);
 
-    // ---- global -> LDS slots of this lane.  One DMA instruction fills 1 KB = 16 rows x 64 B; a
-    // stage is 32 instructions, 2 for A and 2 for B per wave.  Lane l lands at row (l >> 2),
-    // position (l & 3) of its 16-row group and fetches the logical chunk that the swizzle puts there.
-    const int lrow = l >> 2;
-    const int chunk = (l & 3) ^ swz(lrow);     // group bases are multiples of 16 rows: swz depends on lrow only
-    uint32_t a_off[2], b_off[2];               // byte offsets of the row starts (without k)
+    // ---- global -> LDS slots of this lane.  One DMA instruction fills 1 KB = 8 rows x 128 B (eight
+    // full cache lines); an operand tile ("unit") is 32 instructions, 4 per wave.  Lane l lands at
+    // row (l >> 3), position (l & 7) of its 8-row group and fetches the logical chunk that the
+    // swizzle puts there: group j of wave w starts at row (4w+j)*8, so swz(row) = (4*(j&1) + (l>>4)) & 7.
+    const int lrow = l >> 3;
+    const int chunk_even = (l & 7) ^ swz(lrow), chunk_odd = (l & 7) ^ swz(8 + lrow);
+    uint32_t a_lane[4], b_lane[4];             // byte offset of this lane's chunk in K step 0, per DMA slot
     const uint8_t *b_src = p.B;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int row = (w * 2 + j) * 16 + lrow;
+    for (int j = 0; j < 4; ++j) {
+        const int row = (w * 4 + j) * 8 + lrow;
+        const int ck = ((j & 1) ? chunk_odd : chunk_even) * 16;
         int64_t gm = m0 + row;
         gm = gm < p.M ? gm : p.M - 1;
-        a_off[j] = (uint32_t)(gm * p.K);
+        a_lane[j] = (uint32_t)(gm * p.K) + ck;
         int64_t gn;
         if (EPI == EPI_SWIGLU) gn = n0 + (row & 127);
         else gn = n0 + row;
         gn = gn < p.N ? gn : p.N - 1;
-        b_off[j] = (uint32_t)(gn * p.K);
+        b_lane[j] = (uint32_t)(gn * p.K) + ck;
     }
     if (EPI == EPI_SWIGLU && w >= 4) b_src = p.B2;      // waves 4..7 fill tile rows 128..255
-    const uint32_t lds_a = (uint32_t)(w * 2) * 1024u;   // + j*1024 + stage offset
-    const uint32_t lds_b = kTileBytes + lds_a;
+    const uint32_t lds_w = (uint32_t)(w * 4) * 1024u;   // + j*1024 + unit offset
 
-    // ---- LDS -> register fragment offsets (same pattern for A and B): lane l holds row l%32 and
-    // the 32 K bytes of half l/32, i.e. logical chunks 2*(l/32) and 2*(l/32)+1
-    uint32_t frag_off[2];
+    // ---- LDS -> register fragment offsets (same pattern for A and B): for K half kh lane l holds
+    // row l%32 and logical chunks kh*4 + 2*(l/32) and the next one
+    uint32_t frag_off[2][2];
 #pragma unroll
-    for (int e = 0; e < 2; ++e)
-        frag_off[e] = (uint32_t)((l & 31) * BK + ((((l >> 5) * 2 + e) ^ swz(l & 31)) << 4));
+    for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            frag_off[kh][e] = (uint32_t)((l & 31) * BK + (((kh * 4 + (l >> 5) * 2 + e) ^ swz(l & 31)) << 4));
     const uint32_t a_frag_base = (uint32_t)(wm * 128) * BK;
     uint32_t b_frag_base[2];
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
-        b_frag_base[nb] = kTileBytes + (uint32_t)(EPI == EPI_SWIGLU ? nb * 128 + wn * 32 : wn * 64 + nb * 32) * BK;
+        b_frag_base[nb] = (uint32_t)(EPI == EPI_SWIGLU ? nb * 128 + wn * 32 : wn * 64 + nb * 32) * BK;
 
     v16f acc[4][2];
 #pragma unroll
@@ -187,54 +189,47 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     const int nk = nk1 + (TWO_SEG ? (int)((p.K2 + BK - 1) / BK) : 0);
     {
         const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
-        const uint8_t *a_ptr[2], *b_ptr[2];    // this lane's chunk in K step 0 of the first product
-        const uint8_t *a2_ptr[2] = {nullptr, nullptr}, *b2_ptr[2] = {nullptr, nullptr};
+        uint32_t a2_lane[4] = {0, 0, 0, 0}, b2_lane[4] = {0, 0, 0, 0};
+        if (TWO_SEG) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            a_ptr[j] = p.A + a_off[j] + chunk * 16;
-            b_ptr[j] = b_src + b_off[j] + chunk * 16;
-            if (TWO_SEG) {                     // row pitch of the second pair is K2
-                const int row = (w * 2 + j) * 16 + lrow;
+            for (int j = 0; j < 4; ++j) {          // row pitch of the second pair is K2
+                const int row = (w * 4 + j) * 8 + lrow;
+                const int ck = ((j & 1) ? chunk_odd : chunk_even) * 16;
                 int64_t gm = m0 + row; gm = gm < p.M ? gm : p.M - 1;
                 int64_t gn = n0 + row; gn = gn < p.N ? gn : p.N - 1;
-                a2_ptr[j] = p.A2 + gm * p.K2 + chunk * 16;
-                b2_ptr[j] = p.B2 + gn * p.K2 + chunk * 16;
+                a2_lane[j] = (uint32_t)(gm * p.K2) + ck;
+                b2_lane[j] = (uint32_t)(gn * p.K2) + ck;
             }
         }
-        // K step kt -> ring slot `stage`.  Steps past the end of K fetch only zeros (every chunk is
-        // out of range), which keeps the number of outstanding DMA instructions uniform.
-        // fast path operands: uniform base pointer (SGPRs) + this lane's 32-bit offset per DMA slot
-        uint32_t a_lane[2], b_lane[2], a2_lane[2] = {0, 0}, b2_lane[2] = {0, 0};
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            a_lane[j] = a_off[j] + chunk * 16;
-            b_lane[j] = b_off[j] + chunk * 16;
-            if (TWO_SEG) {
-                a2_lane[j] = (uint32_t)(a2_ptr[j] - p.A2);
-                b2_lane[j] = (uint32_t)(b2_ptr[j] - p.B2);
-            }
-        }
-        auto issue = [&](int kt, int stage) {
-            const uint32_t sbase = smem_base + (uint32_t)stage * kStageBytes;
-            const bool second = TWO_SEG && kt >= nk1;
-            const int64_t kbase = (int64_t)(second ? kt - nk1 : kt) * BK;
+        // The LDS ring holds 5 operand tiles ("units") of 32 KB: unit u is the A tile (u even) or B tile
+        // (u odd) of K step u/2 and lives in ring slot u % 5.  While step k is being read (2 units)
+        // three more are in flight.  Unit u = DMA of 256 rows x 128 B: 4 instructions per wave, the
+        // source is a wave-uniform base (SGPRs) plus this lane's 32-bit offset.  In the last,
+        // partial K step the chunks past K come from a 16-byte zero word instead.
+        auto issue_unit = [&](int u) {
+            const int k = u >> 1;
+            if (k >= nk) return;                   // nothing left to fetch (the waits below account for it)
+            const uint32_t dst = smem_base + (uint32_t)(u % kUnits) * kUnitBytes + lds_w;
+            const bool second = TWO_SEG && k >= nk1;
+            const int64_t kbase = (int64_t)(second ? k - nk1 : k) * BK;
             const int64_t Kseg = second ? p.K2 : p.K;
-            if (kbase + BK <= Kseg) {          // whole step in range (uniform branch): scalar base + lane offset
-                const uint8_t *ua = (second ? p.A2 : p.A) + kbase;
-                const uint8_t *ub = (second ? p.B2 : b_src) + kbase;
-                dma16_s(ua, second ? a2_lane[0] : a_lane[0], sbase + lds_a);
-                dma16_s(ub, second ? b2_lane[0] : b_lane[0], sbase + lds_b);
-                dma16_s(ua, second ? a2_lane[1] : a_lane[1], sbase + lds_a + 1024);
-                dma16_s(ub, second ? b2_lane[1] : b_lane[1], sbase + lds_b + 1024);
+            const bool is_b = (u & 1) != 0;
+            const uint8_t *base = is_b ? (second ? p.B2 : b_src) : (second ? p.A2 : p.A);
+            if (kbase + BK <= Kseg) {              // whole step in range (uniform branch)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t off = is_b ? (second ? b2_lane[j] : b_lane[j]) : (second ? a2_lane[j] : a_lane[j]);
+                    dma16_s(base + kbase, off, dst + j * 1024);
+                }
             } else {
-                const uint8_t *pa0 = second ? a2_ptr[0] : a_ptr[0], *pa1 = second ? a2_ptr[1] : a_ptr[1];
-                const uint8_t *pb0 = second ? b2_ptr[0] : b_ptr[0], *pb1 = second ? b2_ptr[1] : b_ptr[1];
-                const bool k_ok = kbase + chunk * 16 < Kseg;   // K is a multiple of 16: a chunk is all in or all out
                 const uint8_t *zero = reinterpret_cast<const uint8_t *>(&g_zero_chunk);
-                dma16(k_ok ? pa0 + kbase : zero, sbase + lds_a);
-                dma16(k_ok ? pb0 + kbase : zero, sbase + lds_b);
-                dma16(k_ok ? pa1 + kbase : zero, sbase + lds_a + 1024);
-                dma16(k_ok ? pb1 + kbase : zero, sbase + lds_b + 1024);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t off = is_b ? (second ? b2_lane[j] : b_lane[j]) : (second ? a2_lane[j] : a_lane[j]);
+                    const int ck = ((j & 1) ? chunk_odd : chunk_even) * 16;
+                    const bool k_ok = kbase + ck < Kseg;       // K is a multiple of 16: a chunk is all in or all out
+                    dma16(k_ok ? base + kbase + off : zero, dst + j * 1024);
+                }
             }
         };
         auto rescale_for_second_product = [&]() {
@@ -247,32 +242,29 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                     for (int i = 0; i < 16; ++i) acc[mb][nb][i] *= r;
         };
 
-        // Schedule.  The ring holds kDepth K steps in flight ahead of the one being read, which is
-        // what hides the memory latency (a 32 KB step per ~1024 MFMA cycles needs >100 KB in flight
-        // at ~2 us).  On top of that the two waves that share a SIMD (w and w+4) run one slot out
-        // of phase: while one feeds the matrix core from registers (8 MFMAs, ~512 cycles) the other
-        // pulls its next fragments out of LDS.  Slots are separated by workgroup barriers; group 0
-        // (waves 0-3) loads step kt in slot 2kt and computes it in slot 2kt+1, group 1 (waves 4-7)
-        // one slot later.  The DMA for step kt+kDepth goes into the ring slot of step kt-1, which
-        // group 1 read last in slot 2kt-1; each group issues its share in its own load slot (2kt / 2kt+1),
-        // after its LDS reads, so that a wave never has memory instructions queued ahead of its MFMAs
-        // (the vector-memory path takes ~20 cycles per 1 KB instruction when all waves push at once).  Before the
-        // barrier that ends slot 2kt+1 every wave waits until all but its newest 4*(kDepth-1) DMA
-        // instructions have landed, i.e. until step kt+1 is complete.
+        // Schedule.  The two waves that share a SIMD (w and w+4) run one slot out of phase: while
+        // one feeds the matrix core from registers (8 MFMAs on one 64-wide K half, ~512 cycles) the
+        // other pulls its next fragments out of LDS and issues DMA.  Slots are separated by
+        // workgroup barriers.  Group 0 (waves 0-3) runs K step k in slots 4k..4k+3 as load(kh0)
+        // compute(kh0) load(kh1) compute(kh1); group 1 (waves 4-7) does the same one slot later.
+        // Units 2k+3 and 2k+4 reuse the ring slots of step k-1, which group 1 read last in slot
+        // 4k-1; each wave issues its share of them in its own load(kh0) slot of step k (4k / 4k+1).
+        // Before the barrier that ends slot 4k+3 every wave waits until all but its newest 4 DMA
+        // instructions have landed, i.e. until units 2k+2 and 2k+3 (step k+1) are complete.
         v8i fa[4], fb[2];
-        auto load_frags = [&](int stage) {
-            const uint8_t *sA = smem + stage * kStageBytes + a_frag_base;
-            const uint8_t *sB = smem + stage * kStageBytes;
+        auto load_frags = [&](int k, int kh) {
+            const uint8_t *sA = smem + ((2 * k) % kUnits) * kUnitBytes + a_frag_base;
+            const uint8_t *sB = smem + ((2 * k + 1) % kUnits) * kUnitBytes;
 #pragma unroll
-            for (int mb = 0; mb < ((SSG_GEMM_EXPERIMENT & 16) ? 2 : 4); ++mb) {
-                const uint4 lo = *reinterpret_cast<const uint4 *>(sA + mb * 32 * BK + frag_off[0]);
-                const uint4 hi = *reinterpret_cast<const uint4 *>(sA + mb * 32 * BK + frag_off[1]);
+            for (int mb = 0; mb < 4; ++mb) {
+                const uint4 lo = *reinterpret_cast<const uint4 *>(sA + mb * 32 * BK + frag_off[kh][0]);
+                const uint4 hi = *reinterpret_cast<const uint4 *>(sA + mb * 32 * BK + frag_off[kh][1]);
                 fa[mb] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
             }
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) {
-                const uint4 lo = *reinterpret_cast<const uint4 *>(sB + b_frag_base[nb] + frag_off[0]);
-                const uint4 hi = *reinterpret_cast<const uint4 *>(sB + b_frag_base[nb] + frag_off[1]);
+                const uint4 lo = *reinterpret_cast<const uint4 *>(sB + b_frag_base[nb] + frag_off[kh][0]);
+                const uint4 hi = *reinterpret_cast<const uint4 *>(sB + b_frag_base[nb] + frag_off[kh][1]);
                 fb[nb] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
             }
         };
@@ -282,78 +274,68 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma<AFMT>(fa[mb], fb[nb], acc[mb][nb]);
         };
-        // A load slot has two jobs that use different pipes: 12 LDS reads (LDS pipe) and 4 DMA
-        // instructions (vector-memory pipe, ~20 cycles per 1 KB instruction when contended).  Half of
-        // the waves do them in one order and half in the other, so both pipes are busy at once.
-        auto load_slot = [&](int kt, int rd_slot, int wr_slot) {
+        // A first-half load slot has two jobs on different pipes: 12 LDS reads and 8 DMA instructions.
+        // Half of the waves do them in one order and half in the other, so both pipes are busy at once.
+        auto load_and_issue = [&](int k) {
             if (wn & 1) {
-                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frags(rd_slot);
+                load_frags(k, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                if (!(SSG_GEMM_EXPERIMENT & 1)) issue(kt + kDepth, wr_slot);
+                if (k >= 1) { issue_unit(2 * k + 3); issue_unit(2 * k + 4); }
             } else {
-                if (!(SSG_GEMM_EXPERIMENT & 1)) issue(kt + kDepth, wr_slot);
+                if (k >= 1) { issue_unit(2 * k + 3); issue_unit(2 * k + 4); }
                 __builtin_amdgcn_sched_barrier(0);
-                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frags(rd_slot);
+                load_frags(k, 0);
             }
         };
-        auto slot_end = [&]() {   // every wave executes the same number of these
+        auto wait_next_step = [&](int k) {         // units 2k+2, 2k+3 landed; unit 2k+4 may still be in flight
+            if (2 * k + 4 < 2 * nk) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        };
+        auto slot_end = [&]() {                    // every wave executes the same number of these
             __builtin_amdgcn_sched_barrier(0);
-            if (!(SSG_GEMM_EXPERIMENT & 4)) __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
         };
-        static_assert(kDepth == 4, "the vmcnt immediates below assume 4 steps in flight, 4 DMA instructions per wave and step");
 
 #pragma unroll
-        for (int d = 0; d < kDepth; ++d) issue(d, d);
-        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");     // step 0 has landed
+        for (int u = 0; u < kUnits; ++u) issue_unit(u);
+        if (nk >= 3) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");       // units 0 and 1 have landed
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         slot_end();
-#if SSG_GEMM_EXPERIMENT & 8
-        const bool dbg_on = blockIdx.x == 0 && l == 0 && (w == 0 || w == 4);
-        const int dbg_base = (w >> 2) * 4096; int dbg_n = 0;
-#endif
-        int rd = 0, wr = kDepth;               // ring slots of step kt and of step kt + kDepth
         if (wm == 0) {
-            for (int kt = 0; kt < nk; ++kt) {
-                SSG_STAMP(1);
-                load_slot(kt, rd, wr);
+            for (int k = 0; k < nk; ++k) {
+                load_and_issue(k);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                SSG_STAMP(3);
                 slot_end();
-                SSG_STAMP(4);
-                if (TWO_SEG && kt == nk1) rescale_for_second_product();
+                if (TWO_SEG && k == nk1) rescale_for_second_product();
                 compute();
-                SSG_STAMP(5);
-                asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-                SSG_STAMP(6);
                 slot_end();
-                rd = rd + 1 == kStages ? 0 : rd + 1;
-                wr = wr + 1 == kStages ? 0 : wr + 1;
+                load_frags(k, 1);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                slot_end();
+                compute();
+                wait_next_step(k);
+                slot_end();
             }
             slot_end();
         } else {
-            for (int kt = 0; kt < nk; ++kt) {
-                SSG_STAMP(4);
-                if (kt > 0) {                  // step kt-1
-                    if (TWO_SEG && kt - 1 == nk1) rescale_for_second_product();
-                    compute();
-                }
-                SSG_STAMP(5);
+            for (int k = 0; k < nk; ++k) {
+                if (k > 0) compute();              // second half of step k-1
                 slot_end();
-                SSG_STAMP(1);
-                load_slot(kt, rd, wr);
+                load_and_issue(k);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                SSG_STAMP(3);
-                asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-                SSG_STAMP(6);
                 slot_end();
-                rd = rd + 1 == kStages ? 0 : rd + 1;
-                wr = wr + 1 == kStages ? 0 : wr + 1;
+                if (TWO_SEG && k == nk1) rescale_for_second_product();
+                compute();
+                slot_end();
+                load_frags(k, 1);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                wait_next_step(k);
+                slot_end();
             }
-            if (TWO_SEG && nk - 1 == nk1) rescale_for_second_product();
             compute();
             slot_end();
         }
-        // drain the zero-filled steps still in flight before LDS is reused (next segment / epilogue)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
