@@ -34,7 +34,7 @@ typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef __attribute__((address_space(1))) const void *global_void_ptr;
 
 #ifndef SSG_GEMM_EXPERIMENT
-#define SSG_GEMM_EXPERIMENT 0   /* timing experiments only: 1 = no DMA in loop, 2 = no LDS reads, 4 = no barriers, 8 = timeline */
+#define SSG_GEMM_EXPERIMENT 0   /* timing experiments only (results are wrong): 1 = no DMA after the prologue, 2 = no LDS reads */
 #endif
 constexpr int BM = 256, BN = 256, BK = 128;
 constexpr int kThreads = 512;
@@ -42,12 +42,6 @@ constexpr int kUnitBytes = BM * BK;               // one operand tile of one K s
 constexpr int kUnits = 5;                         // ring of operand tiles in LDS: all 160 KB
 
 __device__ uint4 g_zero_chunk = {0u, 0u, 0u, 0u}; // source of the zero fill of a ragged K tail
-#if SSG_GEMM_EXPERIMENT & 8
-__device__ unsigned long long g_dbg[8192];
-#define SSG_STAMP(code) do { if (dbg_on && dbg_n < 2000) { g_dbg[dbg_base + dbg_n++] = (__builtin_readcyclecounter() << 4) | (code); } } while (0)
-#else
-#define SSG_STAMP(code) do { } while (0)
-#endif
 
 struct GemmParams {
     const uint8_t *A, *B, *A2, *B2;
@@ -209,6 +203,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         auto issue_unit = [&](int u) {
             const int k = u >> 1;
             if (k >= nk) return;                   // nothing left to fetch (the waits below account for it)
+            if ((SSG_GEMM_EXPERIMENT & 1) && u >= kUnits) return;
             const uint32_t dst = smem_base + (uint32_t)(u % kUnits) * kUnitBytes + lds_w;
             const bool second = TWO_SEG && k >= nk1;
             const int64_t kbase = (int64_t)(second ? k - nk1 : k) * BK;
@@ -253,6 +248,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         // instructions have landed, i.e. until units 2k+2 and 2k+3 (step k+1) are complete.
         v8i fa[4], fb[2];
         auto load_frags = [&](int k, int kh) {
+            if (SSG_GEMM_EXPERIMENT & 2) return;
             const uint8_t *sA = smem + ((2 * k) % kUnits) * kUnitBytes + a_frag_base;
             const uint8_t *sB = smem + ((2 * k + 1) % kUnits) * kUnitBytes;
 #pragma unroll
@@ -517,12 +513,6 @@ static void launch_epi(const GemmParams &p, int a_fmt, unsigned blocks, hipStrea
     else
         hipLaunchKernelGGL((gemm_kernel<EPI, kE5M2, false>), dim3(blocks), dim3(kThreads), 0, st, p);
 }
-
-#if SSG_GEMM_EXPERIMENT & 8
-extern "C" int ssg_debug_timeline(unsigned long long *host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg), sizeof(unsigned long long) * n);
-}
-#endif
 
 void launch_gemm(const GemmArgs &a, hipStream_t st) {
     GemmParams p;
