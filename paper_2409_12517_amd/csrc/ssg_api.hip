@@ -59,7 +59,7 @@ bool fmt_ok(int f) { return f == SSG_E4M3 || f == SSG_E5M2; }
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct SavedLayout {
-    size_t scalars, s, sinv, h_camax, w3_camax, x_q, x_qT, w1_q, w2_q, w1_qT, w2_qT, U, G, h_q, h_qT, w3_q, w3_qT, total;
+    size_t scalars, partials, s, sinv, h_camax, w3_camax, x_q, x_qT, w1_q, w2_q, w1_qT, w2_qT, U, G, h_q, h_qT, w3_q, w3_qT, total;
 };
 // scalar slots of `saved` (floats; amax slots are accumulated as bit patterns)
 enum { S_SX = 0, S_SW1, S_SW2, S_SW3, S_AMAX_X, S_AMAX_W1, S_AMAX_W2, S_AMAX_W3S, S_HMAX, S_COUNT = 64 };
@@ -70,7 +70,8 @@ SavedLayout saved_layout(const ssg_mlp_desc &d) {
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
     L.scalars = take(S_COUNT * 4);
-    // h_camax and w3_camax are zeroed together with the scalars: keep them adjacent
+    // slotted running maxima of x, W1, W2, then h_camax: zeroed by one contiguous clear
+    L.partials = take(3 * ssg::kAmaxSlotWords * 4);
     L.h_camax = take(f * 4); L.w3_camax = take(f * 4);
     L.s = take(f * 4); L.sinv = take(f * 4);
     L.x_q = take(T * dm); L.x_qT = take(T * dm);
@@ -82,7 +83,7 @@ SavedLayout saved_layout(const ssg_mlp_desc &d) {
     return L;
 }
 
-struct WorkLayout { size_t scalars, dy_q, dy_qT, dU, dG, du_q, du_qT, dg_q, dg_qT, total; };
+struct WorkLayout { size_t scalars, partials, dy_q, dy_qT, dU, dG, du_q, du_qT, dg_q, dg_qT, total; };
 enum { W_SDY = 0, W_SDU, W_SDG, W_AMAX_DY, W_AMAX_DU, W_AMAX_DG, W_COUNT = 64 };
 
 WorkLayout work_layout(const ssg_mlp_desc &d) {
@@ -91,6 +92,7 @@ WorkLayout work_layout(const ssg_mlp_desc &d) {
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
     L.scalars = take(W_COUNT * 4);
+    L.partials = take(3 * ssg::kAmaxSlotWords * 4);     // slotted running maxima of dY, dU, dG (adjacent to the scalars)
     L.dy_q = take(T * dm); L.dy_qT = take(T * dm);
     L.dU = take(T * f * 2); L.dG = take(T * f * 2);
     L.du_q = take(T * f); L.du_qT = take(T * f); L.dg_q = take(T * f); L.dg_qT = take(T * f);
@@ -181,7 +183,7 @@ ssg_status ssg_amax(const void *src, ssg_dtype src_dtype, size_t n, float *amax_
     if (n % 16) return fail(SSG_ERR_SHAPE, "ssg_amax: n=%zu must be a multiple of 16", n);
     if (n) SSG_REQUIRE_PTR(src);
     ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_dev), 1, 0u, st);
-    ssg::launch_amax(src, src_kind(src_dtype), n, reinterpret_cast<uint32_t *>(amax_dev), st);
+    ssg::launch_amax(src, src_kind(src_dtype), n, reinterpret_cast<uint32_t *>(amax_dev), 1, st);
     return check_launch("ssg_amax");
 }
 
@@ -210,7 +212,7 @@ ssg_status ssg_quantize(const void *src, ssg_dtype src_dtype, int64_t rows, int6
     a.dst = dst; a.dst_t = dst_t; a.pow2 = rnd == SSG_ROUND_POW2;
     if (mode == SSG_SCALE_CURRENT) {
         ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_dev), 1, 0u, st);
-        ssg::launch_amax(src, a.kind, (size_t)(rows * cols), reinterpret_cast<uint32_t *>(amax_dev), st);
+        ssg::launch_amax(src, a.kind, (size_t)(rows * cols), reinterpret_cast<uint32_t *>(amax_dev), 1, st);
         a.amax = amax_dev;
         a.scale_out = scale_dev;
         if (empty) ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(scale_dev), 1, 0x3f800000u, st);
@@ -218,7 +220,7 @@ ssg_status ssg_quantize(const void *src, ssg_dtype src_dtype, int64_t rows, int6
         a.scale_in = scale_dev;
         if (amax_dev && !empty) {
             ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_dev), 1, 0u, st);
-            ssg::launch_amax(src, a.kind, (size_t)(rows * cols), reinterpret_cast<uint32_t *>(amax_dev), st);
+            ssg::launch_amax(src, a.kind, (size_t)(rows * cols), reinterpret_cast<uint32_t *>(amax_dev), 1, st);
         }
     }
     ssg::launch_cast(a, st);
@@ -354,9 +356,10 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     const bool cached = desc->weights_cached != 0;
     // zero the running maxima of this call; with cached weights the slots that belong to W1, W2 and
     // W3 (their scales, ranges and W3's per-channel maxima) are left as the earlier call wrote them
-    const uint32_t per_call = (1u << S_AMAX_X) | (1u << S_AMAX_W3S) | (1u << S_HMAX);
-    const uint32_t per_weight = (1u << S_AMAX_W1) | (1u << S_AMAX_W2);
-    ssg::launch_reset(scb, cached ? per_call : (per_call | per_weight), reinterpret_cast<uint32_t *>(h_camax), (size_t)f,
+    const uint32_t per_call = (1u << S_AMAX_W3S) | (1u << S_HMAX);
+    uint32_t *part = reinterpret_cast<uint32_t *>(b + L.partials);
+    uint32_t *part_x = part, *part_w1 = part + ssg::kAmaxSlotWords, *part_w2 = part + 2 * ssg::kAmaxSlotWords;
+    ssg::launch_reset(scb, per_call, part, (size_t)((L.h_camax - L.partials) / 4) + (size_t)f,
                       reinterpret_cast<uint32_t *>(w3_camax), cached ? 0 : (size_t)f, st);
 
     // a1 + a2: per-tensor range (Section 2), then Q (Eq. 2) with the transposed copy the backward
@@ -364,17 +367,18 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     // the tensor can still be served from the memory-side cache.
     ssg::CastArgs c;
     c.kind = ssg::SRC_BF16; c.fmt = ssg::kE4M3; c.pow2 = pow2;
-    ssg::launch_amax(x, ssg::SRC_BF16, (size_t)(T * dm), scb + S_AMAX_X, st);
-    c.src = x; c.rows = T; c.cols = dm; c.amax = sc + S_AMAX_X; c.scale_out = sc + S_SX;
+    c.amax_slots = ssg::kAmaxSlots;
+    ssg::launch_amax(x, ssg::SRC_BF16, (size_t)(T * dm), part_x, ssg::kAmaxSlots, st);
+    c.src = x; c.rows = T; c.cols = dm; c.amax = reinterpret_cast<float *>(part_x); c.amax_out = sc + S_AMAX_X; c.scale_out = sc + S_SX;
     c.dst = b + L.x_q; c.dst_t = b + L.x_qT;
     ssg::launch_cast(c, st);
     if (!cached) {
-        ssg::launch_amax(W1, ssg::SRC_BF16, (size_t)(f * dm), scb + S_AMAX_W1, st);
-        c.src = W1; c.rows = f; c.cols = dm; c.amax = sc + S_AMAX_W1; c.scale_out = sc + S_SW1;
+        ssg::launch_amax(W1, ssg::SRC_BF16, (size_t)(f * dm), part_w1, ssg::kAmaxSlots, st);
+        c.src = W1; c.rows = f; c.cols = dm; c.amax = reinterpret_cast<float *>(part_w1); c.amax_out = sc + S_AMAX_W1; c.scale_out = sc + S_SW1;
         c.dst = b + L.w1_q; c.dst_t = b + L.w1_qT;
         ssg::launch_cast(c, st);
-        ssg::launch_amax(W2, ssg::SRC_BF16, (size_t)(f * dm), scb + S_AMAX_W2, st);
-        c.src = W2; c.amax = sc + S_AMAX_W2; c.scale_out = sc + S_SW2; c.dst = b + L.w2_q; c.dst_t = b + L.w2_qT;
+        ssg::launch_amax(W2, ssg::SRC_BF16, (size_t)(f * dm), part_w2, ssg::kAmaxSlots, st);
+        c.src = W2; c.amax = reinterpret_cast<float *>(part_w2); c.amax_out = sc + S_AMAX_W2; c.scale_out = sc + S_SW2; c.dst = b + L.w2_q; c.dst_t = b + L.w2_qT;
         ssg::launch_cast(c, st);
         // per-channel range of w3, needed for the range of s^-1 * w3 (constant between weight updates)
         ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
@@ -433,13 +437,15 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     uint32_t *wscb = reinterpret_cast<uint32_t *>(wsc);
     const int dw_f32 = desc->dw_dtype == SSG_F32;
 
-    ssg::launch_fill_u32(wscb, W_COUNT, 0u, st);
+    uint32_t *wpart = reinterpret_cast<uint32_t *>(wk + Wl.partials);
+    uint32_t *part_dy = wpart, *part_du = wpart + ssg::kAmaxSlotWords, *part_dg = wpart + 2 * ssg::kAmaxSlotWords;
+    ssg::launch_fill_u32(wscb, (Wl.partials - Wl.scalars) / 4 + 3 * ssg::kAmaxSlotWords, 0u, st);
 
     // a9: upstream gradient to E5M2 (Section 6.2), with its transposed copy
-    ssg::launch_amax(dy, ssg::SRC_BF16, (size_t)(T * dm), wscb + W_AMAX_DY, st);
+    ssg::launch_amax(dy, ssg::SRC_BF16, (size_t)(T * dm), part_dy, ssg::kAmaxSlots, st);
     ssg::CastArgs c;
     c.src = dy; c.kind = ssg::SRC_BF16; c.rows = T; c.cols = dm; c.fmt = ssg::kE5M2; c.pow2 = pow2;
-    c.amax = wsc + W_AMAX_DY; c.scale_out = wsc + W_SDY; c.dst = wk + Wl.dy_q; c.dst_t = wk + Wl.dy_qT;
+    c.amax = reinterpret_cast<float *>(part_dy); c.amax_slots = ssg::kAmaxSlots; c.amax_out = wsc + W_AMAX_DY; c.scale_out = wsc + W_SDY; c.dst = wk + Wl.dy_q; c.dst_t = wk + Wl.dy_qT;
     ssg::launch_cast(c, st);
 
     // a10: dH = s_i * dY^ w3~ / (sdy sw3), then through the SwiGLU product
@@ -448,14 +454,14 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     g.A = wk + Wl.dy_q; g.B = sv + L.w3_qT; g.sa = wsc + W_SDY; g.sb = sc + S_SW3;
     // plain block: dH = acc / (sdy sw3), no channel factor
     g.col_scale = desc->smooth ? s : nullptr;
-    g.U = sv + L.U; g.G = sv + L.G; g.C = wk + Wl.dU; g.C2 = wk + Wl.dG; g.amax_bits = wscb + W_AMAX_DU;
+    g.U = sv + L.U; g.G = sv + L.G; g.C = wk + Wl.dU; g.C2 = wk + Wl.dG; g.amax_bits = part_du; g.amax_bits2 = part_dg;
     ssg::launch_gemm(g, st);
 
     // a11: two tensors, two E5M2 scales
     c.kind = ssg::SRC_BF16; c.rows = T; c.cols = f;
-    c.src = wk + Wl.dU; c.amax = wsc + W_AMAX_DU; c.scale_out = wsc + W_SDU; c.dst = wk + Wl.du_q; c.dst_t = wk + Wl.du_qT;
+    c.src = wk + Wl.dU; c.amax = reinterpret_cast<float *>(part_du); c.amax_out = wsc + W_AMAX_DU; c.scale_out = wsc + W_SDU; c.dst = wk + Wl.du_q; c.dst_t = wk + Wl.du_qT;
     ssg::launch_cast(c, st);
-    c.src = wk + Wl.dG; c.amax = wsc + W_AMAX_DG; c.scale_out = wsc + W_SDG; c.dst = wk + Wl.dg_q; c.dst_t = wk + Wl.dg_qT;
+    c.src = wk + Wl.dG; c.amax = reinterpret_cast<float *>(part_dg); c.amax_out = wsc + W_AMAX_DG; c.scale_out = wsc + W_SDG; c.dst = wk + Wl.dg_q; c.dst_t = wk + Wl.dg_qT;
     ssg::launch_cast(c, st);
 
     // a12: dW3[j,i] = sinv_i * sum_t dY^[t,j] h^[t,i] / sdy   (plain: / (sdy * sigma_h))

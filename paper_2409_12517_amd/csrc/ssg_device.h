@@ -63,11 +63,24 @@ __device__ __forceinline__ uint32_t satcast_pk4(float a, float b, float c, float
 // SwiGLU neuron of Section 4.1 in fp32: u * Swish(g), Swish(g) = g * sigma(g).
 // Every operation is a single rounded fp32 operation in a fixed order so that
 // the GEMM epilogue and the stand-alone pass produce identical bits.
+//
+// sigma(g) = 1/(1+e^-g) = e^g/(1+e^g) is evaluated with t = e^-|g| <= 1 so that nothing
+// overflows for strongly negative g (the large-|g| regime is the one the method is about).
+// t = 2^(y) with y = -|g| * log2(e) carried as a rounded product plus its exact remainder
+// (two fused multiply-adds against a split constant), so the hardware exp2 (1 ulp) sees an
+// argument that is exact to ~2^-48 and the error does not grow with |g|; the reciprocal is the
+// hardware one (1 ulp).  Total error of u*g*sigma(g): < 6 ulp.  t below the smallest normal
+// float is flushed to zero by the hardware exp2.
 __device__ __forceinline__ float sigmoid_f32(float g) {
-    // sigma(g) = 1/(1+e^-g) = e^g/(1+e^g): evaluate with t = e^-|g| <= 1 so that nothing
-    // overflows for strongly negative g (the large-|g| regime is the one the method is about).
-    const float t = expf(-fabsf(g));
-    const float r = __fdiv_rn(1.0f, __fadd_rn(1.0f, t));
+    const float x = -fabsf(g);
+    constexpr float kLog2eHi = 1.44269502162933349609375f;        // float(log2 e)
+    constexpr float kLog2eLo = 1.925963033500011e-08f;            // log2 e - kLog2eHi
+    const float y_hi = __fmul_rn(x, kLog2eHi);
+    const float y_lo = __fmaf_rn(x, kLog2eLo, __fmaf_rn(x, kLog2eHi, -y_hi));
+    // 2^(y_hi + y_lo) = 2^y_hi * (1 + y_lo * ln 2 + ...), |y_lo| < 2^-17
+    const float e_hi = __builtin_amdgcn_exp2f(y_hi);
+    const float t = __fmaf_rn(e_hi, __fmul_rn(y_lo, 0.693147182464599609375f), e_hi);
+    const float r = __builtin_amdgcn_rcpf(__fadd_rn(1.0f, t));
     return g >= 0.0f ? r : __fmul_rn(t, r);
 }
 __device__ __forceinline__ float swiglu_f32(float u, float g) {

@@ -49,7 +49,7 @@ struct GemmParams {
     const float *sa, *sb, *sa2, *sb2, *col_scale;
     void *C, *C2;
     const uint16_t *U, *G;
-    uint32_t *camax_bits, *amax_bits;
+    uint32_t *camax_bits, *amax_bits, *amax_bits2;
     int c_f32;
     int tiles_m, tiles_n;
 };
@@ -388,8 +388,24 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
             for (int k = 0; k < 8; ++k) f[k] = __fmul_rn(alpha, p.col_scale[col + k]);
         }
         uint32_t du_max = 0, dg_max = 0;
+        // SWIGLU_BWD: the stored U, G of slab mb+1 are fetched while slab mb is processed, so that
+        // their memory latency is not paid once per pass
+        uint4 ru[2][4], rg[2][4];
+        auto fetch_ug = [&](int mb, int buf) {
+#pragma unroll
+            for (int pass = 0; pass < 4; ++pass) {
+                const int64_t row = m0 + wm * 128 + mb * 32 + pass * 8 + (l >> 3);
+                if (col_ok && row < p.M) {
+                    const size_t at = (size_t)row * (size_t)p.N + (size_t)col;
+                    ru[buf][pass] = *reinterpret_cast<const uint4 *>(p.U + at);
+                    rg[buf][pass] = *reinterpret_cast<const uint4 *>(p.G + at);
+                }
+            }
+        };
+        if (EPI == EPI_SWIGLU_BWD) fetch_ug(0, 0);
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
+            if (EPI == EPI_SWIGLU_BWD && mb + 1 < 4) fetch_ug(mb + 1, (mb + 1) & 1);
             stage_slab(mb);
 #pragma unroll
             for (int pass = 0; pass < 4; ++pass) {
@@ -411,8 +427,8 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                     }
                 } else {
                     float u[8], g[8], du[8], dg[8];
-                    unpack_bf16x8(*reinterpret_cast<const uint4 *>(p.U + at), u);
-                    unpack_bf16x8(*reinterpret_cast<const uint4 *>(p.G + at), g);
+                    unpack_bf16x8(ru[mb & 1][pass], u);
+                    unpack_bf16x8(rg[mb & 1][pass], g);
 #pragma unroll
                     for (int k = 0; k < 8; ++k) swiglu_grad_f32(u[k], g[k], v[k], du[k], dg[k]);
                     const uint4 qu = pack_bf16x8(du), qg = pack_bf16x8(dg);
@@ -444,7 +460,8 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                 uint32_t m = 0;
 #pragma unroll
                 for (int k = 0; k < 8; ++k) m = m > red[2 * k + tid] ? m : red[2 * k + tid];
-                if (m) atomicMax(&p.amax_bits[tid], m << 16);
+                uint32_t *dst = tid == 0 ? p.amax_bits : p.amax_bits2;
+                if (m) atomicMax(dst + (blockIdx.x % kAmaxSlots) * kAmaxSlotStride, m << 16);
             }
         }
     } else {   // EPI_SWIGLU: slab columns 0..31 are u, 32..63 are g of the same 32 channels
@@ -521,7 +538,7 @@ void launch_gemm(const GemmArgs &a, hipStream_t st) {
     p.sa = a.sa; p.sb = a.sb; p.sa2 = a.sa2; p.sb2 = a.sb2; p.col_scale = a.col_scale;
     p.C = a.C; p.C2 = a.C2;
     p.U = (const uint16_t *)a.U; p.G = (const uint16_t *)a.G;
-    p.camax_bits = a.camax_bits; p.amax_bits = a.amax_bits;
+    p.camax_bits = a.camax_bits; p.amax_bits = a.amax_bits; p.amax_bits2 = a.amax_bits2;
     p.c_f32 = a.c_f32;
     p.tiles_m = (int)((a.M + BM - 1) / BM);
     const int n_per_tile = a.epilogue == EPI_SWIGLU ? BN / 2 : BN;

@@ -14,8 +14,15 @@ void launch_fill_u32(uint32_t *p, size_t n, uint32_t value, hipStream_t st);
 // zero scalar slots selected by mask (bit i -> scalars[i], i < 32) and two vectors (either may be empty)
 void launch_reset(uint32_t *scalars, uint32_t mask, uint32_t *v1, size_t n1, uint32_t *v2, size_t n2, hipStream_t st);
 
-// amax_bits: running maximum of |x| as float bits (must be zeroed by the caller).
-void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, hipStream_t st);
+// Running maxima of |x| as float bits, spread over `slots` words that are kAmaxSlotStride words
+// (one cache line) apart and must be zeroed by the caller: workgroup b folds into slot b % slots.
+// Same-address atomics serialise in L2 (~12 ns each), so a pass that wants thousands of workgroups
+// for bandwidth uses kAmaxSlots slots and the consumer takes the maximum over them; slots = 1 is
+// the plain single-word form of the public entry points.
+constexpr int kAmaxSlots = 64;
+constexpr int kAmaxSlotStride = 32;
+constexpr size_t kAmaxSlotWords = (size_t)kAmaxSlots * kAmaxSlotStride;
+void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, int slots, hipStream_t st);
 
 struct CastArgs {
     const void *src = nullptr;       // bf16 / f32 [rows, cols]; U for SRC_SWIGLU
@@ -24,7 +31,9 @@ struct CastArgs {
     int64_t rows = 0, cols = 0;
     int fmt = 0;                     // kE4M3 / kE5M2
     const float *col_scale = nullptr;   // optional per-column factor applied first (one fp32 multiply)
-    const float *amax = nullptr;     // per-tensor: scale = scale_from_amax(*amax) ...
+    const float *amax = nullptr;     // per-tensor: scale = scale_from_amax(max over amax_slots slots) ...
+    int amax_slots = 1;
+    float *amax_out = nullptr;       // where the reduced amax is recorded (may be null)
     const float *scale_in = nullptr; // ... or a given scale; both null = no per-tensor factor
     int pow2 = 0;
     float *scale_out = nullptr;      // where the per-tensor scale is recorded (may be null)
@@ -74,7 +83,8 @@ struct GemmArgs {
     int c_f32 = 0;                      // EPI_STORE: 1 = fp32 output, 0 = bf16
     const void *U = nullptr, *G = nullptr;      // EPI_SWIGLU_BWD inputs (bf16 [M,N])
     uint32_t *camax_bits = nullptr;     // EPI_SWIGLU: [N] running max |h| (float bits)
-    uint32_t *amax_bits = nullptr;      // EPI_SWIGLU_BWD: [2] running max |dU|, |dG| (float bits)
+    uint32_t *amax_bits = nullptr;      // EPI_SWIGLU_BWD: running max |dU| (float bits), kAmaxSlots slots
+    uint32_t *amax_bits2 = nullptr;     //                 same for |dG|
 };
 void launch_gemm(const GemmArgs &a, hipStream_t st);
 

@@ -8,6 +8,9 @@
 #include "ssg_device.h"
 #include "ssg_internal.h"
 
+#ifndef SSG_AMAX_BLOCKS
+#define SSG_AMAX_BLOCKS 512
+#endif
 namespace ssg {
 
 // ------------------------------------------------------------------ fill
@@ -70,16 +73,19 @@ struct LoadSwiglu {          // h = u * Swish(g) from stored bf16 U, G
 
 // ------------------------------------------------------------------ amax
 template <class Loader>
-__global__ void __launch_bounds__(256) amax_kernel(Loader ld, size_t n8, uint32_t *amax_bits) {
+__global__ void __launch_bounds__(256) amax_kernel(Loader ld, size_t n8, uint32_t *amax_bits, int slots) {
     uint32_t m = 0;
-    const size_t stride = (size_t)gridDim.x * 256;
-    // eight independent 16-byte loads in flight per lane and iteration
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += 8 * stride) {
+    // each workgroup owns one contiguous slice of the tensor (page locality); inside it a lane keeps
+    // eight independent 16-byte loads in flight, 4 KB apart
+    const size_t per_block = (n8 + gridDim.x - 1) / gridDim.x;
+    const size_t begin = (size_t)blockIdx.x * per_block;
+    const size_t end = begin + per_block < n8 ? begin + per_block : n8;
+    for (size_t i = begin + threadIdx.x; i < end; i += 8 * 256) {
         float v[8][8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const size_t j = i + u * stride;
-            if (j < n8) ld.load8(j * 8, v[u]);
+            const size_t j = i + u * 256;
+            if (j < end) ld.load8(j * 8, v[u]);
             else {
 #pragma unroll
                 for (int k = 0; k < 8; ++k) v[u][k] = 0.0f;
@@ -100,22 +106,23 @@ __global__ void __launch_bounds__(256) amax_kernel(Loader ld, size_t n8, uint32_
     if (threadIdx.x == 0) {
         uint32_t r = part[0];
         for (int w = 1; w < 4; ++w) r = r > part[w] ? r : part[w];
-        if (r) atomicMax(amax_bits, r);
+        if (r) atomicMax(amax_bits + (blockIdx.x % slots) * kAmaxSlotStride, r);
     }
 }
 
-void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, hipStream_t st) {
+void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, int slots, hipStream_t st) {
     size_t n8 = n / 8;      // n is a multiple of 256 at every call site (rows, cols multiples of 16)
     if (n8 == 0) return;
-    size_t want = (n8 + 255) / 256;
-    // few workgroups: every one ends with an atomic on the same word, and those serialise
-    unsigned blocks = (unsigned)(want < 512 ? want : 512);
+    size_t want = (n8 + 2047) / 2048;       // at least one full iteration (8 x 256 chunks) per workgroup
+    const size_t cap = slots > 1 ? 2048 : SSG_AMAX_BLOCKS;
+    unsigned blocks = (unsigned)(want < cap ? want : cap);
+    if (blocks == 0) blocks = 1;
     if (kind == SRC_BF16)
         hipLaunchKernelGGL(amax_kernel<LoadBf16>, dim3(blocks), dim3(256), 0, st,
-                           LoadBf16{(const uint16_t *)src}, n8, amax_bits);
+                           LoadBf16{(const uint16_t *)src}, n8, amax_bits, slots);
     else
         hipLaunchKernelGGL(amax_kernel<LoadF32>, dim3(blocks), dim3(256), 0, st,
-                           LoadF32{(const float *)src}, n8, amax_bits);
+                           LoadF32{(const float *)src}, n8, amax_bits, slots);
 }
 
 // ------------------------------------------------------------------ cast
@@ -143,14 +150,26 @@ __device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint3
 template <class Loader, int FMT, bool COLSCALE, bool TRANSPOSED>
 __global__ void __launch_bounds__(256)
 cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col_scale,
-            const float *__restrict__ amax, const float *__restrict__ scale_in, int pow2,
+            const float *__restrict__ amax, int amax_slots, float *__restrict__ amax_out,
+            const float *__restrict__ scale_in, int pow2,
             float *__restrict__ scale_out, uint8_t *__restrict__ dst, uint8_t *__restrict__ dst_t) {
     __shared__ uint32_t tile[TRANSPOSED ? kTile * kTPitchWords : 1];
 
     float sigma = 1.0f;
     bool tensor_scale = false;
     if (scale_in) { sigma = *scale_in; tensor_scale = true; }
-    else if (amax) { sigma = scale_from_amax(*amax, Fp8Traits<FMT>::fmax, pow2); tensor_scale = true; }
+    else if (amax) {
+        // maximum over the slots the producers folded into: lane i of every wave takes slot i
+        // (kAmaxSlots = wave size), then a wave-wide maximum
+        const uint32_t *ab = reinterpret_cast<const uint32_t *>(amax);
+        const int lane = threadIdx.x & 63;
+        uint32_t mbits = lane < amax_slots ? ab[lane * kAmaxSlotStride] : 0u;
+        mbits = wave_max_u32(mbits);
+        const float m = __uint_as_float(mbits);
+        sigma = scale_from_amax(m, Fp8Traits<FMT>::fmax, pow2);
+        tensor_scale = true;
+        if (amax_out && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *amax_out = m;
+    }
     if (scale_out && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *scale_out = sigma;
 
     const int64_t row0 = (int64_t)blockIdx.y * kTile;
@@ -222,7 +241,7 @@ static void launch_cast_l(const Loader &ld, const CastArgs &a, hipStream_t st) {
     const bool cs = a.col_scale != nullptr, tr = a.dst_t != nullptr;
 #define SSG_CAST(CS, TR)                                                                               \
     hipLaunchKernelGGL((cast_kernel<Loader, FMT, CS, TR>), grid, dim3(256), 0, st, ld, a.rows, a.cols, \
-                       a.col_scale, a.amax, a.scale_in, a.pow2, a.scale_out, a.dst, a.dst_t)
+                       a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst, a.dst_t)
     if (cs && tr) SSG_CAST(true, true);
     else if (cs) SSG_CAST(true, false);
     else if (tr) SSG_CAST(false, true);
@@ -265,14 +284,24 @@ col_amax_kernel(Loader ld, int64_t rows, int64_t cols, uint32_t *__restrict__ ca
     const int64_t row1 = row0 + kSlabRows < rows ? row0 + kSlabRows : rows;
     if (col < cols) {
         uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        for (int64_t r = row0 + rg; r < row1; r += 16) {
-            float v[8];
-            ld.load8((size_t)r * (size_t)cols + (size_t)col, v);
+        for (int64_t r = row0 + rg; r < row1; r += 64) {       // four independent row loads in flight
+            float v[4][8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                uint32_t b = abs_bits_ignore_nan(v[i]);
-                m[i] = m[i] > b ? m[i] : b;
+            for (int u = 0; u < 4; ++u) {
+                const int64_t rr = r + 16 * u;
+                if (rr < row1) ld.load8((size_t)rr * (size_t)cols + (size_t)col, v[u]);
+                else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[u][i] = 0.0f;
+                }
             }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    uint32_t b = abs_bits_ignore_nan(v[u][i]);
+                    m[i] = m[i] > b ? m[i] : b;
+                }
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i)

@@ -85,7 +85,7 @@ def run_and_check(name, backward=True, n_samples=192):
     # sampled h against the oracle's fp64 product
     ti = torch.from_numpy(rng.integers(0, T, 4096)).to(gu.DEV); ci = torch.from_numpy(rng.integers(0, f, 4096)).to(gu.DEV)
     h_ref = swiglu.swiglu(gu.f32(U[ti, ci]), gu.f32(G[ti, ci]))
-    assert np.all(np.abs(gu.f32(h[ti, ci]) - h_ref) <= 4 * 2.0 ** -23 * np.abs(h_ref) + 1e-37)
+    assert np.all(np.abs(gu.f32(h[ti, ci]) - h_ref) <= 6 * 2.0 ** -23 * np.abs(h_ref) + 1e-30)
     del h
     # folded w3: sampled columns, full range
     w3_q = blk.sv("w3_q", (d, f), torch.uint8)

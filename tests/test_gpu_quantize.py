@@ -154,7 +154,7 @@ def test_gpu_swiglu_product_close_to_oracle():
     ref = swiglu.swiglu(synth.bf16_to_f32_numpy(U), synth.bf16_to_f32_numpy(G))
     got = gu.f32(h).astype(np.float64)
     # fp32 evaluation: exp (1 ulp), add, divide, two multiplies -> a few ulps of the result
-    assert np.all(np.abs(got - ref) <= 4 * 2.0 ** -23 * np.abs(ref) + 1e-37)
+    assert np.all(np.abs(got - ref) <= 6 * 2.0 ** -23 * np.abs(ref) + 1e-30)
 
 
 @pytest.mark.parametrize("d,f", [(256, 688), (1024, 2048)])
