@@ -75,17 +75,17 @@ struct LoadSwiglu {          // h = u * Swish(g) from stored bf16 U, G
 template <class Loader>
 __global__ void __launch_bounds__(256) amax_kernel(Loader ld, size_t n8, uint32_t *amax_bits, int slots) {
     uint32_t m = 0;
-    // each workgroup owns one contiguous slice of the tensor (page locality); inside it a lane keeps
-    // eight independent 16-byte loads in flight, 4 KB apart
-    const size_t per_block = (n8 + gridDim.x - 1) / gridDim.x;
-    const size_t begin = (size_t)blockIdx.x * per_block;
-    const size_t end = begin + per_block < n8 ? begin + per_block : n8;
-    for (size_t i = begin + threadIdx.x; i < end; i += 8 * 256) {
+    // work is cut into units of 2048 chunks (32 KB of bf16): 8 independent 16-byte loads per lane,
+    // 4 KB apart; workgroup b takes units b, b + gridDim.x, ... (the launch picks gridDim.x so that
+    // every workgroup gets the same number of units)
+    const size_t units = (n8 + 2047) / 2048;
+    for (size_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
+        const size_t i = unit * 2048 + threadIdx.x;
         float v[8][8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const size_t j = i + u * 256;
-            if (j < end) ld.load8(j * 8, v[u]);
+            if (j < n8) ld.load8(j * 8, v[u]);
             else {
 #pragma unroll
                 for (int k = 0; k < 8; ++k) v[u][k] = 0.0f;
@@ -113,10 +113,10 @@ __global__ void __launch_bounds__(256) amax_kernel(Loader ld, size_t n8, uint32_
 void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, int slots, hipStream_t st) {
     size_t n8 = n / 8;      // n is a multiple of 256 at every call site (rows, cols multiples of 16)
     if (n8 == 0) return;
-    size_t want = (n8 + 2047) / 2048;       // at least one full iteration (8 x 256 chunks) per workgroup
+    const size_t units = (n8 + 2047) / 2048;
     const size_t cap = slots > 1 ? 2048 : SSG_AMAX_BLOCKS;
-    unsigned blocks = (unsigned)(want < cap ? want : cap);
-    if (blocks == 0) blocks = 1;
+    const size_t per_block = (units + cap - 1) / cap;               // units per workgroup, the same for all
+    unsigned blocks = (unsigned)((units + per_block - 1) / per_block);
     if (kind == SRC_BF16)
         hipLaunchKernelGGL(amax_kernel<LoadBf16>, dim3(blocks), dim3(256), 0, st,
                            LoadBf16{(const uint16_t *)src}, n8, amax_bits, slots);
