@@ -27,17 +27,18 @@ if ROOT not in sys.path:
 
 PEAK_FP8_TFLOPS = 5000.0          # MI355X dense FP8 MFMA peak (published: 5.0 PFLOP/s)
 METRIC = "FP8 Smooth-SwiGLU MLP fwd+bwd TFLOP/s (7B shape), % of FP8 MFMA peak"
-# tag of ssg_profile_read -> kernel symbol as rocprofv3 prints it (template args: epilogue, A format, two products)
-TAG_NAMES = {0: "gemm_kernel<0, 0, false>", 1: "gemm_kernel<0, 1, false>", 2: "gemm_kernel<1, 0, false>",
-             5: "gemm_kernel<2, 1, false>", 9: "gemm_kernel<0, 1, true>"}
+# tag of ssg_profile_read -> kernel symbol as rocprofv3 prints it (template args: epilogue, A format[, two products]);
+# single-product GEMMs run the 4-wave kernel, the two-product one the 8-wave kernel
+TAG_NAMES = {0: "gemm4_kernel<0, 0>", 1: "gemm4_kernel<0, 1>", 2: "gemm4_kernel<1, 0>",
+             5: "gemm4_kernel<2, 1>", 9: "gemm_kernel<0, 1, true>"}
 TAG_ROLES = {0: "y = h^ w3~^T", 1: "dW3, dW1, dW2", 2: "U, G + SwiGLU + channel maxima", 5: "dH + SwiGLU backward",
              9: "dX (two products)"}
 
-# L2<->memory bytes per launch of the dominant kernel (gemm_kernel<0, 1, false>: dW3, dW1, dW2) from two
+# L2<->memory bytes per launch of the dominant kernel (gemm4_kernel<0, 1>: dW3, dW1, dW2) from two
 # rocprofv3 --pmc runs of this command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
 # reads for a 1 GiB copy (factors 2.000 and 1.000); see profiles/bench_7b_hbm_traffic.txt.  Algorithmic
 # bytes of that launch: 61.9 MB of FP8 operands read + 180.4 MB of fp32 written.
-MEASURED_TRAFFIC_BYTES = {"gemm_kernel<0, 1, false>": 319.7e6 + 180.8e6}
+MEASURED_TRAFFIC_BYTES = {"gemm4_kernel<0, 1>": 319.7e6 + 180.8e6}
 
 
 def gemm_flops_by_tag(T, d, f):

@@ -24,6 +24,15 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     return u >> 16;
 }
 
+// Two fp32 -> one packed pair of bf16 (lo in bits 0..15), round to nearest even, with the chip's
+// conversion instruction (v_cvt_pk_bf16_f32): one operation instead of a dozen per pair.
+typedef __bf16 ssg_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float ssg_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const ssg_f32x2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, ssg_bf16x2));
+}
+
 // Per-tensor scale (Section 2; Q of Eq. 2): fl32(fmax / amax), 1 for an empty
 // range, clamped to the largest finite float; optionally rounded down to a
 // power of two by clearing the mantissa.
@@ -93,9 +102,10 @@ __device__ __forceinline__ float swiglu_f32(float u, float g) {
 // argument) instead of the correctly rounded sequence of the forward pass: ~4x fewer VALU
 // instructions in an epilogue that is otherwise ALU bound.
 __device__ __forceinline__ float sigmoid_fast_f32(float g) {
-    const float t = __builtin_amdgcn_exp2f(-fabsf(g) * 1.44269504088896340736f);
-    const float r = __builtin_amdgcn_rcpf(1.0f + t);
-    return g >= 0.0f ? r : t * r;
+    // 1 / (1 + 2^(-g log2 e)); for g below about -88 the power overflows to +inf and the quotient is 0
+    // where the true value is below the smallest normal number
+    const float t = __builtin_amdgcn_exp2f(g * -1.44269504088896340736f);
+    return __builtin_amdgcn_rcpf(1.0f + t);
 }
 __device__ __forceinline__ void swiglu_grad_f32(float u, float g, float dh, float &du, float &dg) {
     const float sg = sigmoid_fast_f32(g);

@@ -23,6 +23,8 @@
 //               max_t |u * Swish(g)| into the per-channel maxima (Section 4.4).
 //   SWIGLU_BWD  acc -> dH (times the channel factor s_i), reads bf16 U, G, stores
 //               bf16 dU, dG and folds their amax.
+#include <cstdlib>
+
 #include "ssg_device.h"
 #include "ssg_internal.h"
 
@@ -43,6 +45,18 @@ constexpr int kUnits = 5;                         // ring of operand tiles in LD
 
 __device__ uint4 g_zero_chunk = {0u, 0u, 0u, 0u}; // source of the zero fill of a ragged K tail
 
+#ifndef SSG_GEMM_TIMELINE
+#define SSG_GEMM_TIMELINE 0     /* 1: every workgroup stamps its phases (100 MHz clock) into a debug buffer */
+#endif
+#if SSG_GEMM_TIMELINE
+constexpr int kTlLaunches = 8, kTlBlocks = 4096, kTlStamps = 4;
+__device__ unsigned long long g_timeline[kTlLaunches * kTlBlocks * kTlStamps];
+#define SSG_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < kTlBlocks) \
+    g_timeline[((size_t)p.tl_slot * kTlBlocks + blockIdx.x) * kTlStamps + (i)] = wall_clock64(); } while (0)
+#else
+#define SSG_STAMP(i) do { } while (0)
+#endif
+
 struct GemmParams {
     const uint8_t *A, *B, *A2, *B2;
     int64_t M, N, K, K2;
@@ -52,6 +66,7 @@ struct GemmParams {
     uint32_t *camax_bits, *amax_bits, *amax_bits2;
     int c_f32;
     int tiles_m, tiles_n;
+    int tl_slot;
 };
 
 // An LDS row holds the 128 bytes (eight 16-byte chunks, one full cache line) of one matrix row for one
@@ -95,6 +110,28 @@ __device__ __forceinline__ float inv_scale_product(const float *sa, const float 
     return __fdiv_rn(1.0f, p);
 }
 
+// Workgroup -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its
+// own L2, so give every XCD a contiguous range of a tile order in which any 32 consecutive tiles
+// (one per CU of the XCD) form a 4 x 8 patch: 12 operand tiles fetched for 32 computed.
+__device__ __forceinline__ void map_tile(const GemmParams &p, int &tile_m, int &tile_n) {
+    const int total = p.tiles_m * p.tiles_n;
+    const int per_xcd = (total + 7) / 8;
+    int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if ((total & 7) != 0) {
+        // ranges are uneven: fall back to the identity when the remapped id would leave the grid
+        const int full = total & ~7;
+        t = (int)blockIdx.x < full ? (int)(blockIdx.x & 7) * (full >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    }
+    constexpr int kGroupM = 4;
+    const int group_tiles = kGroupM * p.tiles_n;
+    const int gidx = t / group_tiles;
+    const int first_m = gidx * kGroupM;
+    const int gsize = (p.tiles_m - first_m) < kGroupM ? (p.tiles_m - first_m) : kGroupM;
+    const int in_group = t - gidx * group_tiles;
+    tile_m = first_m + in_group % gsize;
+    tile_n = in_group / gsize;
+}
+
 template <int EPI, int AFMT, bool TWO_SEG>
 __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     __shared__ __attribute__((aligned(1024))) uint8_t smem[kUnits * kUnitBytes];
@@ -103,28 +140,8 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;   // wave index is uniform: keep it scalar
     const int wm = w >> 2, wn = w & 3;
 
-    // Workgroup -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with
-    // its own L2, so give every XCD a contiguous range of a tile order in which any 32 consecutive
-    // tiles (one per CU of the XCD) form a 4 x 8 patch: 12 operand tiles fetched for 32 computed.
     int tile_m, tile_n;
-    {
-        const int total = p.tiles_m * p.tiles_n;
-        const int per_xcd = (total + 7) / 8;
-        int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-        if ((total & 7) != 0) {
-            // ranges are uneven: fall back to the identity when the remapped id would leave the grid
-            const int full = total & ~7;
-            t = (int)blockIdx.x < full ? (int)(blockIdx.x & 7) * (full >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
-        }
-        constexpr int kGroupM = 4;
-        const int group_tiles = kGroupM * p.tiles_n;
-        const int gidx = t / group_tiles;
-        const int first_m = gidx * kGroupM;
-        const int gsize = (p.tiles_m - first_m) < kGroupM ? (p.tiles_m - first_m) : kGroupM;
-        const int in_group = t - gidx * group_tiles;
-        tile_m = first_m + in_group % gsize;
-        tile_n = in_group / gsize;
-    }
+    map_tile(p, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM;
     // SWIGLU: a tile covers 128 channels (128 rows of W1 + the same 128 rows of W2)
     const int64_t n0 = (int64_t)tile_n * (EPI == EPI_SWIGLU ? BN / 2 : BN);
@@ -361,7 +378,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     auto pack_bf16x8 = [&](const float (&v)[8]) {
         uint32_t q[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) q[k] = f32_to_bf16_bits(v[2 * k]) | (f32_to_bf16_bits(v[2 * k + 1]) << 16);
+        for (int k = 0; k < 4; ++k) q[k] = pack_bf16x2(v[2 * k], v[2 * k + 1]);
         return make_uint4(q[0], q[1], q[2], q[3]);
     };
     auto unpack_bf16x8 = [&](const uint4 q, float (&v)[8]) {
@@ -516,19 +533,400 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Variant with 4 waves (one per SIMD) and 128 x 128 wave tiles: 256 accumulator registers per lane,
+// one third fewer LDS reads per flop than the 8-wave form (each A row block is read by 2 waves
+// instead of 4).  With a single wave per SIMD there is no partner to hide stalls, so the wave
+// software-pipelines itself: while the 16 MFMAs of one 64-wide K half run from one fragment set,
+// the next half's fragments are read into the other set, one fragment after every second MFMA, and
+// the DMA of new operand tiles is spread over the second half of every K step.  One barrier per K
+// step, in its middle: by then every wave holds both halves of step k in registers, so the barrier
+// both retires step k's ring slots and publishes step k+1 (each wave first waits for its own DMA share).
+constexpr int kThreads4 = 256;
+
+template <int EPI, int AFMT>
+__global__ void __launch_bounds__(kThreads4) gemm4_kernel(GemmParams p) {
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[kUnits * kUnitBytes];
+
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
+    const int wm = w >> 1, wn = w & 1;
+    int tile_m, tile_n;
+    map_tile(p, tile_m, tile_n);
+    const int64_t m0 = (int64_t)tile_m * BM;
+    const int64_t n0 = (int64_t)tile_n * (EPI == EPI_SWIGLU ? BN / 2 : BN);
+    SSG_STAMP(0);
+
+    // DMA slots: a unit is 32 instructions of 8 rows x 128 B, 8 per wave (rows (8w+j)*8 + l/8)
+    const int lrow = l >> 3;
+    const int chunk_even = (l & 7) ^ swz(lrow), chunk_odd = (l & 7) ^ swz(8 + lrow);
+    uint32_t a_lane[8], b_lane[8];
+    const uint8_t *b_src = p.B;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int row = (w * 8 + j) * 8 + lrow;
+        const int ck = ((j & 1) ? chunk_odd : chunk_even) * 16;
+        int64_t gm = m0 + row;
+        gm = gm < p.M ? gm : p.M - 1;
+        a_lane[j] = (uint32_t)(gm * p.K) + ck;
+        int64_t gn;
+        if (EPI == EPI_SWIGLU) gn = n0 + (row & 127);
+        else gn = n0 + row;
+        gn = gn < p.N ? gn : p.N - 1;
+        b_lane[j] = (uint32_t)(gn * p.K) + ck;
+    }
+    if (EPI == EPI_SWIGLU && w >= 2) b_src = p.B2;      // waves 2, 3 fill tile rows 128..255
+    const uint32_t lds_w = (uint32_t)(w * 8) * 1024u;
+
+    // LDS byte offset of this lane's two 16-byte chunks of a fragment row, per K half; the row block of a
+    // fragment adds a wave-uniform base and a compile-time multiple of 4 KB (an instruction immediate)
+    uint32_t frag_off[2][2];
+#pragma unroll
+    for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            frag_off[kh][e] = (uint32_t)((l & 31) * BK + (((kh * 4 + (l >> 5) * 2 + e) ^ swz(l & 31)) << 4));
+    const uint32_t a_wave_base = (uint32_t)(wm * 128) * BK;
+    const uint32_t b_wave_base = (uint32_t)(EPI == EPI_SWIGLU ? wn * 64 : wn * 128) * BK;
+    auto b_block_off = [](int nb) -> uint32_t {      // SWIGLU: blocks 0, 1 from the W1 rows, 2, 3 from the W2 rows
+        return (uint32_t)(EPI == EPI_SWIGLU ? (nb >> 1) * 128 + (nb & 1) * 32 : nb * 32) * BK;
+    };
+
+    v16f acc[4][4];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mb][nb][i] = 0.0f;
+
+    const int nk = (int)((p.K + BK - 1) / BK);
+    {
+        const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
+        // general issue of unit u (unit u = A (even) / B (odd) tile of K step u/2, ring slot u % 5): any
+        // K, zero fill of a ragged K tail
+        auto issue_unit = [&](int u) {
+            const int k = u >> 1;
+            if (k >= nk) return;
+            const uint32_t dst = smem_base + (uint32_t)(u % kUnits) * kUnitBytes + lds_w;
+            const int64_t kbase = (int64_t)k * BK;
+            const int64_t Kseg = p.K;
+            const bool is_b = (u & 1) != 0;
+            const uint8_t *base = is_b ? b_src : p.A;
+            const uint8_t *zero = reinterpret_cast<const uint8_t *>(&g_zero_chunk);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int row = (w * 8 + j) * 8 + lrow;
+                const int ck = ((j & 1) ? chunk_odd : chunk_even) * 16;
+                int64_t g = (is_b ? n0 + ((EPI == EPI_SWIGLU) ? (row & 127) : row) : m0 + row);
+                const int64_t lim = is_b ? p.N : p.M;
+                g = g < lim ? g : lim - 1;
+                const bool k_ok = kbase + ck < Kseg;
+                dma16(k_ok ? base + g * Kseg + kbase + ck : zero, dst + j * 1024);
+            }
+        };
+        v8i fa[2][4], fb[2][4];
+        // The i-th fragment read of a K half, in the order the MFMAs need them (B0 A0 B1 B2 B3 A1 A2 A3:
+        // the first four MFMAs use A0 with B0..B3), from ring slots sa / sb; g = 0..3: A row blocks,
+        // 4..7: B row blocks
+        auto load_frag = [&](int set, uint32_t sa, uint32_t sb, int kh, int i) {
+            constexpr int kOrder[8] = {4, 0, 5, 6, 7, 1, 2, 3};
+            const int g = kOrder[i];
+            const uint32_t ub = g < 4 ? sa * kUnitBytes + a_wave_base : sb * kUnitBytes + b_wave_base;   // uniform
+            const uint32_t imm = g < 4 ? (uint32_t)(g * 32 * BK) : b_block_off(g - 4);
+            const uint4 lo = *reinterpret_cast<const uint4 *>(smem + (frag_off[kh][0] + ub) + imm);
+            const uint4 hi = *reinterpret_cast<const uint4 *>(smem + (frag_off[kh][1] + ub) + imm);
+            const v8i f = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            if (g < 4) fa[set][g] = f; else fb[set][g - 4] = f;
+        };
+        auto mfma2 = [&](int set, int g) {          // MFMAs 2g and 2g+1 of the 16 of a half step
+#pragma unroll
+            for (int q = 2 * g; q < 2 * g + 2; ++q)
+                acc[q >> 2][q & 3] = mfma<AFMT>(fa[set][q >> 2], fb[set][q & 3], acc[q >> 2][q & 3]);
+        };
+        // s_waitcnt lgkmcnt(0) through the builtin (gfx9 encoding: vmcnt and expcnt fields at their
+        // maxima), so that the compiler's own wait bookkeeping sees it
+        auto wait_lds = [&]() { __builtin_amdgcn_s_waitcnt(0xC07F); };
+
+        // Schedule of a K step k (units 2k, 2k+1 in ring slots sa, sb):
+        //   first half   16 MFMAs on fragment set 0 (k, K half 0); reads (k, half 1) into set 1;
+        //                issues unit 2k+4 (A of step k+2) into the slot that B of step k-1 left
+        //   barrier      each wave first waits for its share of units 2k+2, 2k+3 and for its LDS reads:
+        //                step k's slots are free, step k+1 is visible to all
+        //   second half  16 MFMAs on set 1; reads (k+1, half 0) into set 0; issues unit 2k+5 (B of
+        //                step k+2) into the slot of unit 2k
+        // so one DMA instruction follows every pair of MFMAs throughout and the texture path never
+        // sees a burst.
+#pragma unroll
+        for (int u = 0; u < 4; ++u) issue_unit(u);
+        if (nk >= 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");       // units 0 and 1 have landed
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        SSG_STAMP(1);
+#pragma unroll
+        for (int g = 0; g < 8; ++g) load_frag(0, 0, 1, 0, g);
+
+        // Steady state: when every K step is whole, the steps whose new units exist run a body without
+        // any per-instruction check: wave-uniform source pointers, lane offsets from registers.  The
+        // last two steps, and every step of a ragged shape, take the general body.
+        const int kfast = (p.K % BK) == 0 ? (nk > 2 ? nk - 2 : 0) : 0;
+        uint32_t sa = 0, sb = 1, sp = 4;             // ring slots of units 2k, 2k+1 and 2k+4
+        auto next_slot = [](uint32_t s) { const uint32_t t = s + 2; return t >= (uint32_t)kUnits ? t - kUnits : t; };
+        // wave-uniform sources of the units issued during step k (K step k+2): running pointers in scalar registers
+        const uint8_t *ua = p.A + 2 * BK, *ub = b_src + 2 * BK;
+        for (int k = 0; k < kfast; ++k) {
+            const uint32_t sa_n = next_slot(sa), sb_n = next_slot(sb);
+            const uint32_t d4 = smem_base + sp * kUnitBytes + lds_w;
+            const uint32_t d5 = smem_base + sa * kUnitBytes + lds_w;
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                mfma2(0, g);
+                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frag(1, sa, sb, 1, g);
+                if (!(SSG_GEMM_EXPERIMENT & 1)) dma16_s(ua, a_lane[g], d4 + g * 1024);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");       // all but unit 2k+4 have landed
+            wait_lds();
+            if (!(SSG_GEMM_EXPERIMENT & 4)) __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                mfma2(1, g);
+                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frag(0, sa_n, sb_n, 0, g);
+                if (!(SSG_GEMM_EXPERIMENT & 1)) dma16_s(ub, b_lane[g], d5 + g * 1024);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            sp = sb; sa = sa_n; sb = sb_n;
+            ua += BK; ub += BK;
+        }
+        for (int k = kfast; k < nk; ++k) {
+            const uint32_t sa_n = next_slot(sa), sb_n = next_slot(sb);
+            issue_unit(2 * k + 4);
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                mfma2(0, g);
+                load_frag(1, sa, sb, 1, g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (k + 2 < nk) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            wait_lds();
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            issue_unit(2 * k + 5);
+            // (after the last step the fragment reads touch a stale slot and are never used)
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                mfma2(1, g);
+                load_frag(0, sa_n, sb_n, 0, g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            sa = sa_n; sb = sb_n;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+    SSG_STAMP(2);
+
+    // ---- epilogue: per-wave LDS patch, one 32 x 128 slab (mb) at a time
+    constexpr int kPitch = 136;                        // floats; 4 rows apart lands on the other 32 banks
+    float *stg = reinterpret_cast<float *>(smem) + w * (32 * kPitch);
+    const int lcol = l & 31;
+    const int lrow4 = (l >> 5) * 4;
+    auto stage_slab = [&](int mb) {
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                stg[((i >> 2) * 8 + lrow4 + (i & 3)) * kPitch + nb * 32 + lcol] = acc[mb][nb][i];
+    };
+    auto load8 = [&](int r, int c, float (&v)[8]) {
+        const float4 a = *reinterpret_cast<const float4 *>(stg + r * kPitch + c);
+        const float4 b = *reinterpret_cast<const float4 *>(stg + r * kPitch + c + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    };
+    auto pack_bf16x8 = [&](const float (&v)[8]) {
+        uint32_t q[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) q[k] = pack_bf16x2(v[2 * k], v[2 * k + 1]);
+        return make_uint4(q[0], q[1], q[2], q[3]);
+    };
+    auto unpack_bf16x8 = [&](const uint4 q, float (&v)[8]) {
+        const uint32_t w4[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[2 * k] = __uint_as_float(w4[k] << 16);
+            v[2 * k + 1] = __uint_as_float(w4[k] & 0xffff0000u);
+        }
+    };
+
+    if (EPI == EPI_STORE || EPI == EPI_SWIGLU_BWD) {
+        // lane -> (row of the slab in 8 passes of 4 rows, 8 columns c8 of the wave's 128)
+        const int c8 = (l & 15) * 8;
+        const int64_t col = n0 + wn * 128 + c8;
+        const bool col_ok = col < p.N;
+        const float alpha = inv_scale_product(p.sa, p.sb);
+        float f[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) f[k] = alpha;
+        if (p.col_scale && col_ok) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) f[k] = __fmul_rn(alpha, p.col_scale[col + k]);
+        }
+        // running |.| maxima of the stored dU, dG as floats: rounding to bf16 is monotone, so the
+        // maximum of the rounded values is the rounded maximum (taken once, at the end); fmaxf drops NaN
+        float du_maxf = 0.0f, dg_maxf = 0.0f;
+        uint4 ru[2][8], rg[2][8];
+        auto fetch_ug = [&](int mb) {                  // the slab's stored U, G: rows in 8 passes of 4
+            if (EPI != EPI_SWIGLU_BWD) return;
+#pragma unroll
+            for (int pass = 0; pass < 8; ++pass) {
+                const int64_t row = m0 + wm * 128 + mb * 32 + pass * 4 + (l >> 4);
+                if (col_ok && row < p.M) {
+                    const size_t at = (size_t)row * (size_t)p.N + (size_t)col;
+                    ru[mb & 1][pass] = *reinterpret_cast<const uint4 *>(p.U + at);
+                    rg[mb & 1][pass] = *reinterpret_cast<const uint4 *>(p.G + at);
+                }
+            }
+        };
+        fetch_ug(0);
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            if (mb + 1 < 4) fetch_ug(mb + 1);          // one slab ahead: the loads fly while this slab is worked
+            stage_slab(mb);
+#pragma unroll
+            for (int pass = 0; pass < 8; ++pass) {
+                const int r = pass * 4 + (l >> 4);
+                const int64_t row = m0 + wm * 128 + mb * 32 + r;
+                float v[8];
+                load8(r, c8, v);
+                if (!col_ok || row >= p.M) continue;
+                const size_t at = (size_t)row * (size_t)p.N + (size_t)col;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = __fmul_rn(v[k], f[k]);
+                if (EPI == EPI_STORE) {
+                    if (p.c_f32) {
+                        float *out = reinterpret_cast<float *>(p.C) + at;
+                        *reinterpret_cast<float4 *>(out) = make_float4(v[0], v[1], v[2], v[3]);
+                        *reinterpret_cast<float4 *>(out + 4) = make_float4(v[4], v[5], v[6], v[7]);
+                    } else {
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = pack_bf16x8(v);
+                    }
+                } else {
+                    float u[8], g[8], du[8], dg[8];
+                    unpack_bf16x8(ru[mb & 1][pass], u);
+                    unpack_bf16x8(rg[mb & 1][pass], g);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        swiglu_grad_f32(u[k], g[k], v[k], du[k], dg[k]);
+                        du_maxf = fmaxf(du_maxf, fabsf(du[k]));
+                        dg_maxf = fmaxf(dg_maxf, fabsf(dg[k]));
+                    }
+                    *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = pack_bf16x8(du);
+                    *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C2) + at) = pack_bf16x8(dg);
+                }
+            }
+        }
+        // bf16 bits of the rounded maxima (an infinite maximum, 0x7f80, is kept; NaN never enters)
+        uint32_t du_max = pack_bf16x2(du_maxf, 0.0f) & 0x7fffu, dg_max = pack_bf16x2(dg_maxf, 0.0f) & 0x7fffu;
+        if (EPI == EPI_SWIGLU_BWD) {
+            du_max = wave_max_u32(du_max);
+            dg_max = wave_max_u32(dg_max);
+            uint32_t *red = reinterpret_cast<uint32_t *>(smem + 4 * 32 * kPitch * 4);   // past the staging patches
+            if (l == 0) { red[2 * w] = du_max; red[2 * w + 1] = dg_max; }
+            __syncthreads();
+            if (tid < 2) {
+                uint32_t m = 0;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) m = m > red[2 * k + tid] ? m : red[2 * k + tid];
+                uint32_t *dst = tid == 0 ? p.amax_bits : p.amax_bits2;
+                if (m) atomicMax(dst + (blockIdx.x % kAmaxSlots) * kAmaxSlotStride, m << 16);
+            }
+        }
+    } else {   // EPI_SWIGLU: slab columns 0..63 are u, 64..127 are g of the same 64 channels
+        const int c8 = (l & 7) * 8;
+        const int64_t col = n0 + wn * 64 + c8;
+        const bool col_ok = col < p.N;
+        const float alpha_u = inv_scale_product(p.sa, p.sb);
+        const float alpha_g = inv_scale_product(p.sa, p.sb2);
+        float hmaxf[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};   // fmaxf drops NaN
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            stage_slab(mb);
+#pragma unroll
+            for (int pass = 0; pass < 4; ++pass) {
+                const int r = pass * 8 + (l >> 3);
+                const int64_t row = m0 + wm * 128 + mb * 32 + r;
+                float u[8], g[8];
+                load8(r, c8, u);
+                load8(r, 64 + c8, g);
+                if (!col_ok || row >= p.M) continue;
+                const size_t at = (size_t)row * (size_t)p.N + (size_t)col;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    u[k] = __fmul_rn(u[k], alpha_u);
+                    g[k] = __fmul_rn(g[k], alpha_g);
+                }
+                const uint4 qu = pack_bf16x8(u), qg = pack_bf16x8(g);
+                *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = qu;
+                *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C2) + at) = qg;
+                unpack_bf16x8(qu, u);
+                unpack_bf16x8(qg, g);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) hmaxf[k] = fmaxf(hmaxf[k], fabsf(swiglu_f32(u[k], g[k])));
+            }
+        }
+        uint32_t hmax[8];                                // non-negative floats order like their bit patterns
+#pragma unroll
+        for (int k = 0; k < 8; ++k) hmax[k] = __float_as_uint(hmaxf[k]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+#pragma unroll
+            for (int off = 8; off < 64; off <<= 1) {
+                const uint32_t o = (uint32_t)__shfl_xor((int)hmax[k], off, 64);
+                hmax[k] = hmax[k] > o ? hmax[k] : o;
+            }
+        if (l < 8 && col_ok) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (hmax[k]) atomicMax(&p.camax_bits[col + k], hmax[k]);
+        }
+    }
+    SSG_STAMP(3);
+}
+
+// Which kernel runs a single-product GEMM: the 4-wave form unless SSG_GEMM_VARIANT=0 asks for the
+// 8-wave one (tests run both).  The two-product GEMM always takes the 8-wave kernel.
+static int g_gemm_variant = -1;
+static bool use_four_waves() {
+    if (g_gemm_variant < 0) {
+        const char *e = getenv("SSG_GEMM_VARIANT");
+        g_gemm_variant = (e && e[0] == '0') ? 0 : 1;
+    }
+    return g_gemm_variant == 1;
+}
+
+template <int EPI, int AFMT, bool TWO>
+static void launch_one(const GemmParams &p, unsigned blocks, hipStream_t st) {
+    if constexpr (!TWO) {
+        if (use_four_waves()) {
+            hipLaunchKernelGGL((gemm4_kernel<EPI, AFMT>), dim3(blocks), dim3(kThreads4), 0, st, p);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((gemm_kernel<EPI, AFMT, TWO>), dim3(blocks), dim3(kThreads), 0, st, p);
+}
+
 template <int EPI>
 static void launch_epi(const GemmParams &p, int a_fmt, unsigned blocks, hipStream_t st) {
-    if (EPI == EPI_STORE && p.A2) {        // two K segments: only the E5M2 x E4M3 input-gradient product uses it
-        if (a_fmt == kE4M3)
-            hipLaunchKernelGGL((gemm_kernel<EPI_STORE, kE4M3, true>), dim3(blocks), dim3(kThreads), 0, st, p);
-        else
-            hipLaunchKernelGGL((gemm_kernel<EPI_STORE, kE5M2, true>), dim3(blocks), dim3(kThreads), 0, st, p);
+    if (EPI == EPI_STORE && p.A2) {        // two K segments: the input gradient sums two products
+        if (a_fmt == kE4M3) launch_one<EPI_STORE, kE4M3, true>(p, blocks, st);
+        else launch_one<EPI_STORE, kE5M2, true>(p, blocks, st);
         return;
     }
-    if (a_fmt == kE4M3)
-        hipLaunchKernelGGL((gemm_kernel<EPI, kE4M3, false>), dim3(blocks), dim3(kThreads), 0, st, p);
-    else
-        hipLaunchKernelGGL((gemm_kernel<EPI, kE5M2, false>), dim3(blocks), dim3(kThreads), 0, st, p);
+    if (a_fmt == kE4M3) launch_one<EPI, kE4M3, false>(p, blocks, st);
+    else launch_one<EPI, kE5M2, false>(p, blocks, st);
 }
 
 void launch_gemm(const GemmArgs &a, hipStream_t st) {
@@ -540,6 +938,11 @@ void launch_gemm(const GemmArgs &a, hipStream_t st) {
     p.U = (const uint16_t *)a.U; p.G = (const uint16_t *)a.G;
     p.camax_bits = a.camax_bits; p.amax_bits = a.amax_bits; p.amax_bits2 = a.amax_bits2;
     p.c_f32 = a.c_f32;
+    p.tl_slot = 0;
+#if SSG_GEMM_TIMELINE
+    static int tl_launch = 0;
+    p.tl_slot = tl_launch++ % kTlLaunches;
+#endif
     p.tiles_m = (int)((a.M + BM - 1) / BM);
     const int n_per_tile = a.epilogue == EPI_SWIGLU ? BN / 2 : BN;
     p.tiles_n = (int)((a.N + n_per_tile - 1) / n_per_tile);
@@ -554,3 +957,9 @@ void launch_gemm(const GemmArgs &a, hipStream_t st) {
 }
 
 }  // namespace ssg
+
+#if SSG_GEMM_TIMELINE
+extern "C" int ssg_debug_timeline(unsigned long long *host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(ssg::g_timeline), sizeof(unsigned long long) * (size_t)n);
+}
+#endif
