@@ -38,7 +38,7 @@ TAG_ROLES = {0: "y = h^ w3~^T", 1: "dW3, dW1, dW2", 2: "U, G + SwiGLU + channel 
 # rocprofv3 --pmc runs of this command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
 # reads for a 1 GiB copy (factors 2.000 and 1.000); see profiles/bench_7b_hbm_traffic.txt.  Algorithmic
 # bytes of that launch: 61.9 MB of FP8 operands read + 180.4 MB of fp32 written.
-MEASURED_TRAFFIC_BYTES = {"gemm4_kernel<0, 1>": 319.7e6 + 180.8e6}
+MEASURED_TRAFFIC_BYTES = {"gemm4_kernel<0, 1>": 329.2e6 + 191.6e6}
 
 
 def gemm_flops_by_tag(T, d, f):
@@ -73,6 +73,33 @@ def cpu_baseline(T_sample: int, cfg):
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
             "sample": f"first {T_sample} of {cfg.T} tokens, full weights, fwd+bwd, {dt:.1f} s wall",
             "seconds": dt}
+
+
+def mfma_ceiling(ssg, torch, saved_view_bytes, stream):
+    """Sustained rate of a register-only MFMA loop (no memory traffic): on one repeated FP8 code, and on
+    FP8 codes taken from this workload's quantized x and W1.  The clock under a dense MFMA load follows
+    the power the operand data draws, so the second figure is the ceiling a GEMM on this data can approach."""
+    dev = saved_view_bytes[0].device
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
+    out = {}
+    for name in ("constant_operands", "workload_operands"):
+        if name == "constant_operands":
+            ws[:65536].fill_(0x38)
+        else:
+            ws[:32768].copy_(saved_view_bytes[0].reshape(-1)[:32768])
+            ws[32768:65536].copy_(saved_view_bytes[1].reshape(-1)[:32768])
+        best = 0.0
+        for _ in range(2):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            flops = ssg.ssg_probe_mfma_rate(ws, 16000, stream)
+            e1.record(stream)
+            e1.synchronize()
+            best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        out[name] = best
+    out["unit"] = "TFLOP/s"
+    out["note"] = "256 workgroups x 4 waves x 16 accumulator blocks of v_mfma_f32_32x32x64_f8f6f4, best of 2 launches of about 8 ms (long enough for the clock to settle)"
+    return out
 
 
 def main() -> int:
@@ -198,6 +225,10 @@ def main() -> int:
                    "T": T, "d_model": d, "d_ffn": f, "seed": cfg.seed},
         "roofline": roofline,
     }
+    view = ssg.ssg_mlp_view_saved(desc, saved)
+    x_q = ssg.view_tensor(saved, saved.data_ptr(), view.x_q, (T, d), torch.uint8)
+    w1_q = ssg.view_tensor(saved, saved.data_ptr(), view.w1_q, (f, d), torch.uint8)
+    out["roofline"]["measured_mfma_ceiling"] = mfma_ceiling(ssg, torch, (x_q, w1_q), stream)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(min(args.cpu_sample_tokens, T), cfg)
     print(json.dumps(out))

@@ -176,6 +176,17 @@ ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspac
 ssg_status ssg_profile_enable(int max_records);
 int ssg_profile_read(float *ms, int *tags, int cap);
 
+/* ---- matrix-core ceiling probe (optional diagnostic) ---------------------------
+ * Launches a register-only loop of v_mfma_f32_32x32x64_f8f6f4 (256 workgroups of 4 waves, 16
+ * accumulator blocks per wave, no memory traffic inside the loop): `iters` passes of 16 MFMAs per
+ * wave.  The A/B fragments are the first 64 KiB of `workspace` (device; the caller fills them,
+ * e.g. with one repeated FP8 code or with random codes -- the sustained clock, and so the rate,
+ * depends on the data); a 256 KiB checksum is written after them.  `workspace_bytes` >= 320 KiB.
+ * *flops (host, may be NULL) receives the flop count of the launch; the caller times it.
+ * The measured rate is the ceiling the GEMMs of this library can approach on such data; it prices
+ * them beside the published dense FP8 peak.  Asynchronous; errors as for the other entry points. */
+ssg_status ssg_probe_mfma_rate(void *workspace, size_t workspace_bytes, int iters, double *flops, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -33,7 +33,7 @@ EXPORTS = [
     "ssg_last_error", "ssg_version", "ssg_amax", "ssg_quantize", "ssg_gemm_fp8", "ssg_swiglu",
     "ssg_smooth_swiglu_quantize", "ssg_fold_w3", "ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes",
     "ssg_mlp_fwd", "ssg_mlp_bwd", "ssg_mlp_view_saved", "ssg_mlp_view_workspace",
-    "ssg_profile_enable", "ssg_profile_read",
+    "ssg_profile_enable", "ssg_profile_read", "ssg_probe_mfma_rate",
 ]
 
 
@@ -74,6 +74,7 @@ _lib.ssg_mlp_view_saved.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg
 _lib.ssg_mlp_view_workspace.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_workspace_view)]
 _lib.ssg_profile_enable.argtypes = [c_int]
 _lib.ssg_profile_read.argtypes = [POINTER(c_float), POINTER(c_int), c_int]
+_lib.ssg_probe_mfma_rate.argtypes = [c_void_p, c_size_t, c_int, POINTER(ctypes.c_double), c_void_p]
 for _n in EXPORTS[2:]:
     if _n not in ("ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes"):
         getattr(_lib, _n).restype = c_int
@@ -189,6 +190,15 @@ def ssg_profile_read(cap: int):
     if n < 0:
         raise SsgError(n, ssg_last_error())
     return list(ms[:n]), list(tags[:n])
+
+
+def ssg_probe_mfma_rate(workspace, iters: int, stream=None) -> float:
+    """Launches the register-only MFMA loop on the operand bytes at the start of `workspace`
+    (a device byte tensor of at least 320 KiB); returns the flop count of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(_lib.ssg_probe_mfma_rate(_ptr(workspace), workspace.numel() * workspace.element_size(), iters,
+                                    ctypes.byref(flops), _stream(stream)))
+    return flops.value
 
 
 def view_tensor(saved, base_ptr: int, field_ptr: int, shape, dtype):

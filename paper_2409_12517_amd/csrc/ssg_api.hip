@@ -173,6 +173,18 @@ int ssg_profile_read(float *ms, int *tags, int cap) {
     return n;
 }
 
+ssg_status ssg_probe_mfma_rate(void *workspace, size_t workspace_bytes, int iters, double *flops, void *stream) {
+    SSG_REQUIRE_PTR(workspace);
+    const size_t need = ssg::mfma_rate_operand_bytes() + ssg::mfma_rate_sink_bytes();
+    if (workspace_bytes < need)
+        return fail(SSG_ERR_WORKSPACE, "ssg_probe_mfma_rate: workspace of %zu bytes, %zu needed", workspace_bytes, need);
+    if (iters <= 0 || iters > (1 << 24)) return fail(SSG_ERR_ARG, "ssg_probe_mfma_rate: iters %d out of range", iters);
+    if (flops) *flops = ssg::mfma_rate_flops(iters);
+    ssg::launch_mfma_rate(workspace, static_cast<uint8_t *>(workspace) + ssg::mfma_rate_operand_bytes(), iters,
+                          static_cast<hipStream_t>(stream));
+    return check_launch("ssg_probe_mfma_rate");
+}
+
 const char *ssg_last_error(void) { return g_err; }
 const char *ssg_version(void) { return "ssg 0.1 (gfx950)"; }
 

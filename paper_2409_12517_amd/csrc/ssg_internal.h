@@ -92,4 +92,10 @@ void launch_gemm(const GemmArgs &a, hipStream_t st);
 void profile_before(int tag, hipStream_t st);
 void profile_after(hipStream_t st);
 
+// register-only MFMA loop (ssg_probe.hip): 64 KiB of operand bytes in, 256 KiB checksum sink out
+double mfma_rate_flops(int iters);
+size_t mfma_rate_operand_bytes();
+size_t mfma_rate_sink_bytes();
+void launch_mfma_rate(const void *operands, void *sink, int iters, hipStream_t st);
+
 }  // namespace ssg

@@ -79,3 +79,17 @@ def test_gemm_uniform_codes_full_dynamic_range():
     got = _run(a, ssg.SSG_E5M2, b, None, None, ssg.SSG_F32)
     ref = gemm.matmul_nt(a, fp8.E5M2, b, fp8.E4M3)
     gu.assert_close_gemm(got, ref, False, "uniform codes")
+
+
+@pytest.mark.gpu
+def test_mfma_rate_probe_runs_and_checks_its_arguments():
+    """The register-only MFMA loop: flop count as documented, checksum written, small workspace refused."""
+    ws = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda:0")
+    ws[:65536].fill_(0x38)                       # E4M3 1.0 everywhere: every accumulator ends at iters * 64
+    flops = ssg.ssg_probe_mfma_rate(ws, 3)
+    torch.cuda.synchronize()
+    assert flops == 256 * 4 * 3 * 16 * 2.0 * 32 * 32 * 64
+    sink = ws[65536:65536 + 256 * 256 * 4].view(torch.float32)
+    assert torch.all(sink == 16 * 16 * 3 * 64.0)
+    with pytest.raises(ssg.SsgError):
+        ssg.ssg_probe_mfma_rate(ws[:4096], 3)
