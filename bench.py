@@ -75,6 +75,75 @@ def cpu_baseline(T_sample: int, cfg):
             "seconds": dt}
 
 
+PEAK_HBM_GBS = 8000.0             # MI355X HBM3E (published: 8 TB/s)
+ADAM_KERNELS = {32: "adam_range_kernel<false, 2>", 33: "adam_update_kernel<false, 1>"}
+# algorithmic bytes per element: range pass reads g (4) + two codes; update pass reads g, two codes and w (4),
+# writes w (4), the bf16 copy (2) and two codes
+ADAM_BYTES = {32: 6.0, 33: 18.0}
+
+
+def bench_adam(ssg, torch, grads, weights, steps, warmup, stream, cpu_sample=1 << 22, with_cpu=True):
+    """Next row after the block: the Adam step with E4M3 / E5M2 moments (Section 5) on the block's three
+    weight tensors, gradients = the fp32 dW1, dW2, dW3 the backward just produced.  One step = the
+    three tensors; HBM-bound."""
+    states, ws, wbs = [], [], []
+    for w in weights:
+        n = w.numel()
+        st = torch.empty(ssg.ssg_adam_state_bytes(n), dtype=torch.uint8, device=w.device)
+        ssg.ssg_adam_init(n, st, stream)
+        states.append(st)
+        ws.append(w.float().reshape(-1).contiguous())
+        wbs.append(torch.empty(n, dtype=torch.bfloat16, device=w.device))
+    gs = [g.reshape(-1) for g in grads]
+    t = [0]
+
+    def step():
+        t[0] += 1
+        for g, w, wb, st in zip(gs, ws, wbs, states):
+            desc = ssg.make_adam_desc(g.numel(), t[0], lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+            ssg.ssg_adam_step(desc, g, w, wb, st, stream)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ssg.ssg_profile_enable(6 * steps)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_list, tags = ssg.ssg_profile_read(6 * steps)
+    ssg.ssg_profile_enable(0)
+    n_total = sum(g.numel() for g in gs)
+    n_one = gs[0].numel()
+    per = {tg: [m for m, x in zip(ms_list, tags) if x == tg] for tg in (32, 33)}
+    avg = {tg: sum(v) / len(v) for tg, v in per.items()}
+    dom = 33
+    achieved = ADAM_BYTES[dom] * n_one / (avg[dom] * 1e-3) / 1e9
+    out = {"metric": "FP8-moment Adam step over the block's weights, algorithmic GB/s", "unit": "GB/s",
+           "value": (ADAM_BYTES[32] + ADAM_BYTES[33]) * n_total / (dt / steps) / 1e9,
+           "ms_per_step": dt * 1e3 / steps, "elements": n_total, "steps": steps, "dtype": "f32 (moments e4m3 / e5m2)",
+           "roofline": {"bound": "hbm", "kernel": ADAM_KERNELS[dom], "achieved": achieved, "peak": PEAK_HBM_GBS,
+                        "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                        "avg_launch_ms": avg[dom], "bytes_per_launch": ADAM_BYTES[dom] * n_one,
+                        "kernels": {ADAM_KERNELS[tg]: {"avg_ms": avg[tg], "gbs": ADAM_BYTES[tg] * n_one / (avg[tg] * 1e-3) / 1e9}
+                                    for tg in (32, 33)}}}
+    if with_cpu:
+        import numpy as np
+        from oracle import adam as oadam
+        ns = min(cpu_sample, n_one)
+        g = gs[0][:ns].cpu().numpy()
+        w = ws[0][:ns].cpu().numpy()
+        st = oadam.init(ns)
+        c0 = time.perf_counter()
+        for _ in range(3):
+            w, st = oadam.step(w, g, st, lr=3e-4, weight_decay=0.1)
+        cdt = (time.perf_counter() - c0) / 3
+        out["cpu_baseline"] = {"value": 24.0 * ns / cdt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first {ns} elements of dW1, 3 steps, {cdt:.2f} s per step"}
+    return out
+
+
 def mfma_ceiling(ssg, torch, saved_view_bytes, stream):
     """Sustained rate of a register-only MFMA loop (no memory traffic): on one repeated FP8 code, and on
     FP8 codes taken from this workload's quantized x and W1.  The clock under a dense MFMA load follows
@@ -110,6 +179,7 @@ def main() -> int:
     ap.add_argument("--workload", default="7b", help="name in synth.CONFIGS (default: the headline shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=512)
+    ap.add_argument("--no-adam", action="store_true", help="skip the FP8-moment Adam step reported under 'adam_step'")
     ap.add_argument("--copy-probe", action="store_true",
                     help="first run three 1 GiB device-to-device copies (a kernel of known traffic, used to "
                          "calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -231,6 +301,9 @@ def main() -> int:
     out["roofline"]["measured_mfma_ceiling"] = mfma_ceiling(ssg, torch, (x_q, w1_q), stream)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(min(args.cpu_sample_tokens, T), cfg)
+    if not args.no_adam:
+        out["adam_step"] = bench_adam(ssg, torch, (dW1, dW2, dW3), (W1, W2, W3), max(5, args.steps // 5), 3, stream,
+                                      with_cpu=not args.no_cpu_baseline)
     print(json.dumps(out))
     return 0
 

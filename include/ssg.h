@@ -161,9 +161,49 @@ typedef struct {
 ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_mlp_saved_view *out);
 ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspace, ssg_mlp_workspace_view *out);
 
+/* ---- Adam with both moments in FP8 (Section 5) -------------------------------
+ * The first moment is stored in E4M3 and the second in E5M2 (Section 5.2), each with one
+ * per-tensor scale chosen from the range of the new moment as in Section 2
+ * (scale = fl32(fmax / amax), code = satcast(fl32(value * scale))).  One step on a flat tensor:
+ *     m_prev = fl32(decode(m_q) fl32(1/scale_m))  v_prev = fl32(decode(v_q) fl32(1/scale_v))
+ *     m = fl32(fl32(beta1 m_prev) + fl32((1-beta1) g))
+ *     v = fl32(fl32(beta2 v_prev) + fl32(fl32((1-beta2) g) g))
+ *     upd = fl32(fl32(m c1) / fl32(sqrt(fl32(v c2)) + eps)),  c_i = fl32(1 / (1 - beta_i^step))
+ *     w = fl32(w - fl32(lr fl32(upd + fl32(weight_decay w))))           (decoupled decay)
+ *     m_q, scale_m = Q_E4M3(m);  v_q, scale_v = Q_E5M2(v)
+ * (the update uses the unrounded moments of this step; fl32 = one rounded binary32 operation).
+ * The paper fixes the two formats; the rest is this library's reading.
+ *
+ * state (device, caller-owned, ssg_adam_state_bytes(n) bytes, 256-byte aligned): scale and range
+ * words kept twice by step parity, the range slots of the reduction, then m_q[n] and v_q[n].
+ * ssg_adam_init writes zero moments (codes 0, scales 1).  ssg_adam_step takes step = 1, 2, 3, ...
+ * in order (the parity of `step` selects which scalar set is read and which is written).
+ * grad: [n] device, grad_dtype SSG_F32 or SSG_BF16.  w: [n] fp32 device, updated in place.
+ * w_bf16: optional [n] bf16 device copy of the new weights (NULL to skip).  n: multiple of 16,
+ * below 2^40.  All calls are asynchronous on `stream` and allocate nothing; a negative status
+ * means nothing was launched. */
+typedef struct {
+    int64_t n;
+    float lr, beta1, beta2, eps, weight_decay;
+    int32_t step;            /* >= 1 */
+    int32_t grad_dtype;      /* ssg_dtype */
+    int32_t rnd;             /* ssg_scale_round of the two moment scales */
+    int32_t reserved[3];     /* must be zero */
+} ssg_adam_desc;
+typedef struct {
+    const uint8_t *m_q, *v_q;   /* [n] E4M3 / E5M2 codes */
+    const float *scales;        /* [0]=scale_m [1]=scale_v [2]=amax_m [3]=amax_v as written by step `step` */
+} ssg_adam_state_view;
+size_t ssg_adam_state_bytes(int64_t n);
+ssg_status ssg_adam_init(int64_t n, void *state, void *stream);
+ssg_status ssg_adam_step(const ssg_adam_desc *desc, const void *grad, float *w, void *w_bf16, void *state,
+                         void *stream);
+/* pointers into `state` as left by step `step` (0 = after ssg_adam_init) */
+ssg_status ssg_adam_view_state(int64_t n, int32_t step, const void *state, ssg_adam_state_view *out);
+
 /* ---- kernel timing for benchmarks (optional) --------------------------------
  * The one piece of state the library keeps, off by default.  While enabled,
- * every GEMM launch is bracketed by two HIP events recorded on the launch's
+ * every GEMM launch (and each pass of the Adam step) is bracketed by two HIP events recorded on the launch's
  * own stream (events are host objects; no device memory is allocated).
  *   ssg_profile_enable(n)  n > 0: create n event pairs and start recording (records beyond n are
  *                          dropped); n = 0: stop and destroy the events.
@@ -172,7 +212,9 @@ ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspac
  *                          returns the number written, or a negative ssg_status.
  *                          tag = 2 * epilogue + a_fmt with epilogue 0 = plain store (y, dx, dW),
  *                          1 = fused SwiGLU forward (U, G, channel maxima), 2 = fused SwiGLU backward;
- *                          +8 for the two-product form of the plain store (dx). */
+ *                          +8 for the two-product form of the plain store (dx).
+ *                          The two passes of ssg_adam_step are recorded too: tag 32 = range pass,
+ *                          33 = update pass. */
 ssg_status ssg_profile_enable(int max_records);
 int ssg_profile_read(float *ms, int *tags, int cap);
 

@@ -11,7 +11,8 @@ the textbook optimizer and against invariants):
   * each moment tensor carries one scale, chosen from the range of the *new*
     moment exactly as the per-tensor scaling of Section 2
     (scale = fl32(fmax / amax), code = satcast(fl32(value * scale)));
-  * a stored moment is read back as fl32(decode(code) / scale);
+  * a stored moment is read back as fl32(decode(code) * fl32(1 / scale)): one
+    reciprocal per tensor, one multiplication per element;
   * the parameter update uses the freshly computed binary32 moments of this
     step, before they are re-encoded; the master weights are binary32.
 
@@ -56,11 +57,12 @@ def bias_corrections(beta1: float, beta2: float, t: int):
 
 
 def moments_from_state(st: State, quantize: bool = True):
-    """The stored moments as binary32: fl32(decode(code) / scale)."""
+    """The stored moments as binary32: fl32(decode(code) * fl32(1 / scale))."""
     if not quantize:
         return st.m.astype(F32), st.v.astype(F32)
-    m = (fp8.decode_table(fp8.E4M3)[st.m].astype(F32) / st.scale_m).astype(F32)
-    v = (fp8.decode_table(fp8.E5M2)[st.v].astype(F32) / st.scale_v).astype(F32)
+    inv_m, inv_v = F32(F32(1.0) / F32(st.scale_m)), F32(F32(1.0) / F32(st.scale_v))
+    m = (fp8.decode_table(fp8.E4M3)[st.m].astype(F32) * inv_m).astype(F32)
+    v = (fp8.decode_table(fp8.E5M2)[st.v].astype(F32) * inv_v).astype(F32)
     return m, v
 
 

@@ -33,6 +33,7 @@ EXPORTS = [
     "ssg_last_error", "ssg_version", "ssg_amax", "ssg_quantize", "ssg_gemm_fp8", "ssg_swiglu",
     "ssg_smooth_swiglu_quantize", "ssg_fold_w3", "ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes",
     "ssg_mlp_fwd", "ssg_mlp_bwd", "ssg_mlp_view_saved", "ssg_mlp_view_workspace",
+    "ssg_adam_state_bytes", "ssg_adam_init", "ssg_adam_step", "ssg_adam_view_state",
     "ssg_profile_enable", "ssg_profile_read", "ssg_probe_mfma_rate",
 ]
 
@@ -40,6 +41,16 @@ EXPORTS = [
 class ssg_mlp_desc(Structure):
     _fields_ = [("T", c_int64), ("d", c_int64), ("f", c_int64), ("smooth", c_int32), ("rnd", c_int32),
                 ("y_dtype", c_int32), ("dw_dtype", c_int32), ("weights_cached", c_int32), ("reserved", c_int32 * 3)]
+
+
+class ssg_adam_desc(Structure):
+    _fields_ = [("n", c_int64), ("lr", c_float), ("beta1", c_float), ("beta2", c_float), ("eps", c_float),
+                ("weight_decay", c_float), ("step", c_int32), ("grad_dtype", c_int32), ("rnd", c_int32),
+                ("reserved", c_int32 * 3)]
+
+
+class ssg_adam_state_view(Structure):
+    _fields_ = [(n, c_void_p) for n in ("m_q", "v_q", "scales")]
 
 
 class ssg_mlp_saved_view(Structure):
@@ -74,6 +85,11 @@ _lib.ssg_mlp_view_saved.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg
 _lib.ssg_mlp_view_workspace.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_workspace_view)]
 _lib.ssg_profile_enable.argtypes = [c_int]
 _lib.ssg_profile_read.argtypes = [POINTER(c_float), POINTER(c_int), c_int]
+_lib.ssg_adam_state_bytes.argtypes = [c_int64]
+_lib.ssg_adam_state_bytes.restype = c_size_t
+_lib.ssg_adam_init.argtypes = [c_int64, c_void_p, c_void_p]
+_lib.ssg_adam_step.argtypes = [POINTER(ssg_adam_desc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+_lib.ssg_adam_view_state.argtypes = [c_int64, c_int32, c_void_p, POINTER(ssg_adam_state_view)]
 _lib.ssg_probe_mfma_rate.argtypes = [c_void_p, c_size_t, c_int, POINTER(ctypes.c_double), c_void_p]
 for _n in EXPORTS[2:]:
     if _n not in ("ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes"):
@@ -190,6 +206,32 @@ def ssg_profile_read(cap: int):
     if n < 0:
         raise SsgError(n, ssg_last_error())
     return list(ms[:n]), list(tags[:n])
+
+
+def make_adam_desc(n, step, lr, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, grad_dtype=SSG_F32,
+                   rnd=SSG_ROUND_EXACT_DIV) -> ssg_adam_desc:
+    d = ssg_adam_desc()
+    d.n, d.step, d.lr, d.beta1, d.beta2, d.eps, d.weight_decay = n, step, lr, beta1, beta2, eps, weight_decay
+    d.grad_dtype, d.rnd = grad_dtype, rnd
+    return d
+
+
+def ssg_adam_state_bytes(n: int) -> int:
+    return int(_lib.ssg_adam_state_bytes(n))
+
+
+def ssg_adam_init(n: int, state, stream=None) -> None:
+    _check(_lib.ssg_adam_init(n, _ptr(state), _stream(stream)))
+
+
+def ssg_adam_step(desc, grad, w, w_bf16, state, stream=None) -> None:
+    _check(_lib.ssg_adam_step(ctypes.byref(desc), _ptr(grad), _ptr(w), _ptr(w_bf16), _ptr(state), _stream(stream)))
+
+
+def ssg_adam_view_state(n: int, step: int, state) -> ssg_adam_state_view:
+    v = ssg_adam_state_view()
+    _check(_lib.ssg_adam_view_state(n, step, _ptr(state), ctypes.byref(v)))
+    return v
 
 
 def ssg_probe_mfma_rate(workspace, iters: int, stream=None) -> float:

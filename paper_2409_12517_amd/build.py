@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssg.so")
-SOURCES = ["ssg_api.hip", "ssg_quant.hip", "ssg_gemm.hip", "ssg_probe.hip"]
+SOURCES = ["ssg_api.hip", "ssg_quant.hip", "ssg_gemm.hip", "ssg_probe.hip", "ssg_adam.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

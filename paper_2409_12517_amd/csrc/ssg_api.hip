@@ -3,6 +3,7 @@
 // method runs in the kernels of ssg_quant.hip / ssg_gemm.hip.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -171,6 +172,68 @@ int ssg_profile_read(float *ms, int *tags, int cap) {
     }
     g_prof.used = 0;
     return n;
+}
+
+// ---- Adam with FP8 moments -----------------------------------------------------
+namespace {
+size_t adam_scalar_bytes() { return align256(ssg::adam_scalar_words() * sizeof(uint32_t)); }
+bool adam_n_ok(int64_t n) { return n > 0 && (n % 16) == 0 && n < ((int64_t)1 << 40); }
+}  // namespace
+
+size_t ssg_adam_state_bytes(int64_t n) {
+    if (!adam_n_ok(n)) return 0;
+    return adam_scalar_bytes() + 2 * align256((size_t)n);
+}
+
+ssg_status ssg_adam_init(int64_t n, void *state, void *stream) {
+    if (!adam_n_ok(n)) return fail(SSG_ERR_SHAPE, "ssg_adam_init: n = %lld must be a positive multiple of 16", (long long)n);
+    SSG_REQUIRE_PTR(state);
+    uint8_t *base = static_cast<uint8_t *>(state);
+    ssg::launch_adam_init(reinterpret_cast<uint32_t *>(base), base + adam_scalar_bytes(), 2 * align256((size_t)n),
+                          static_cast<hipStream_t>(stream));
+    return check_launch("ssg_adam_init");
+}
+
+ssg_status ssg_adam_step(const ssg_adam_desc *desc, const void *grad, float *w, void *w_bf16, void *state,
+                         void *stream) {
+    if (!desc) return fail(SSG_ERR_ARG, "ssg_adam_step: desc is NULL");
+    if (!adam_n_ok(desc->n)) return fail(SSG_ERR_SHAPE, "ssg_adam_step: n = %lld must be a positive multiple of 16", (long long)desc->n);
+    if (desc->step < 1) return fail(SSG_ERR_ARG, "ssg_adam_step: step %d (steps count from 1)", desc->step);
+    if (!dtype_ok(desc->grad_dtype)) return fail(SSG_ERR_ARG, "ssg_adam_step: grad_dtype %d", desc->grad_dtype);
+    if (desc->rnd != SSG_ROUND_EXACT_DIV && desc->rnd != SSG_ROUND_POW2) return fail(SSG_ERR_ARG, "ssg_adam_step: rnd %d", desc->rnd);
+    if (desc->reserved[0] || desc->reserved[1] || desc->reserved[2]) return fail(SSG_ERR_ARG, "ssg_adam_step: reserved fields must be zero");
+    if (!(desc->beta1 >= 0.0f && desc->beta1 < 1.0f) || !(desc->beta2 >= 0.0f && desc->beta2 < 1.0f))
+        return fail(SSG_ERR_ARG, "ssg_adam_step: beta1, beta2 must lie in [0, 1)");
+    if (!(desc->eps >= 0.0f) || !(desc->lr == desc->lr) || !(desc->weight_decay == desc->weight_decay))
+        return fail(SSG_ERR_ARG, "ssg_adam_step: eps must be >= 0 and lr, weight_decay must be numbers");
+    SSG_REQUIRE_PTR(grad);
+    SSG_REQUIRE_PTR(w);
+    SSG_OPTIONAL_PTR(w_bf16);
+    SSG_REQUIRE_PTR(state);
+    uint8_t *base = static_cast<uint8_t *>(state);
+    ssg::AdamArgs a;
+    a.grad = grad; a.grad_bf16 = desc->grad_dtype == SSG_BF16; a.w = w; a.w_bf16 = w_bf16;
+    a.scalars = reinterpret_cast<uint32_t *>(base);
+    a.m_q = base + adam_scalar_bytes();
+    a.v_q = a.m_q + align256((size_t)desc->n);
+    a.n = desc->n; a.step = desc->step;
+    a.beta1 = desc->beta1; a.beta2 = desc->beta2;
+    a.one_minus_beta1 = 1.0f - desc->beta1; a.one_minus_beta2 = 1.0f - desc->beta2;
+    // bias corrections: formed in double from the binary32 betas, rounded once
+    a.c1 = (float)(1.0 / (1.0 - std::pow((double)desc->beta1, (double)desc->step)));
+    a.c2 = (float)(1.0 / (1.0 - std::pow((double)desc->beta2, (double)desc->step)));
+    a.lr = desc->lr; a.eps = desc->eps; a.weight_decay = desc->weight_decay; a.pow2 = desc->rnd == SSG_ROUND_POW2;
+    ssg::launch_adam_step(a, static_cast<hipStream_t>(stream));
+    return check_launch("ssg_adam_step");
+}
+
+ssg_status ssg_adam_view_state(int64_t n, int32_t step, const void *state, ssg_adam_state_view *out) {
+    if (!adam_n_ok(n) || step < 0 || !state || !out) return fail(SSG_ERR_ARG, "ssg_adam_view_state: bad argument");
+    const uint8_t *base = static_cast<const uint8_t *>(state);
+    out->scales = reinterpret_cast<const float *>(base) + 8 * (step & 1);
+    out->m_q = base + adam_scalar_bytes();
+    out->v_q = out->m_q + align256((size_t)n);
+    return SSG_OK;
 }
 
 ssg_status ssg_probe_mfma_rate(void *workspace, size_t workspace_bytes, int iters, double *flops, void *stream) {

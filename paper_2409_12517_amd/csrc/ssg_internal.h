@@ -92,6 +92,24 @@ void launch_gemm(const GemmArgs &a, hipStream_t st);
 void profile_before(int tag, hipStream_t st);
 void profile_after(hipStream_t st);
 
+// ---- Adam with FP8 moments (ssg_adam.hip) ---------------------------------------
+struct AdamArgs {
+    const void *grad = nullptr;      // [n] fp32 or bf16
+    int grad_bf16 = 0;
+    float *w = nullptr;              // [n] fp32 master weights, updated in place
+    void *w_bf16 = nullptr;          // optional [n] bf16 copy of the new weights
+    uint8_t *m_q = nullptr, *v_q = nullptr;   // [n] E4M3 / E5M2 codes, updated in place
+    uint32_t *scalars = nullptr;     // adam_scalar_words() words
+    int64_t n = 0;
+    int step = 1;                    // the step being taken (>= 1)
+    float beta1 = 0, beta2 = 0, one_minus_beta1 = 0, one_minus_beta2 = 0, c1 = 1, c2 = 1;
+    float lr = 0, eps = 0, weight_decay = 0;
+    int pow2 = 0;
+};
+size_t adam_scalar_words();
+void launch_adam_init(uint32_t *scalars, uint8_t *codes, size_t code_bytes, hipStream_t st);
+void launch_adam_step(const AdamArgs &a, hipStream_t st);
+
 // register-only MFMA loop (ssg_probe.hip): 64 KiB of operand bytes in, 256 KiB checksum sink out
 double mfma_rate_flops(int iters);
 size_t mfma_rate_operand_bytes();

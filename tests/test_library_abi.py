@@ -69,3 +69,21 @@ def test_entry_points_reject_bad_arguments_before_launching():
     with pytest.raises(ssg.SsgError) as e:
         ssg.ssg_mlp_bwd(ssg.make_desc(256, 256, 100), 256, 256, 256, 256, 256, 256, 256, stream=0)
     assert e.value.status == ssg.SSG_ERR_SHAPE
+
+
+def test_adam_entry_points_validate_before_launching():
+    """No GPU here: every call must be refused on its arguments alone."""
+    import paper_2409_12517_amd as ssg
+    assert ssg.ssg_adam_state_bytes(1 << 20) >= 2 * (1 << 20)
+    assert ssg.ssg_adam_state_bytes(1 << 20) % 256 == 0
+    assert ssg.ssg_adam_state_bytes(0) == 0 and ssg.ssg_adam_state_bytes(24) == 0
+    with pytest.raises(ssg.SsgError):
+        ssg.ssg_adam_init(24, 4096, stream=0)
+    with pytest.raises(ssg.SsgError):
+        ssg.ssg_adam_init(64, None, stream=0)
+    with pytest.raises(ssg.SsgError):
+        ssg.ssg_adam_step(ssg.make_adam_desc(64, 0, 1e-3), 4096, 4096, None, 4096, stream=0)
+    with pytest.raises(ssg.SsgError):
+        ssg.ssg_adam_step(ssg.make_adam_desc(64, 1, 1e-3, beta2=1.5), 4096, 4096, None, 4096, stream=0)
+    with pytest.raises(ssg.SsgError):
+        ssg.ssg_adam_step(ssg.make_adam_desc(64, 1, 1e-3), 4096, 4100, None, 4096, stream=0)      # misaligned weights
