@@ -105,6 +105,7 @@ class Forward:
     W1: Optional[np.ndarray] = None
     W2: Optional[np.ndarray] = None
     W3: Optional[np.ndarray] = None
+    amax: Optional[dict] = None              # ranges of x, w1, w2 seen in this call (for an amax history)
 
 
 def fold_w3(W3: np.ndarray, sinv: np.ndarray):
@@ -115,10 +116,13 @@ def fold_w3(W3: np.ndarray, sinv: np.ndarray):
 
 
 def forward(x, W1, W2, W3, *, quantized: bool = True, smooth: bool = True,
-            y_dtype: str = "bf16", h_scale=None) -> Forward:
+            y_dtype: str = "bf16", h_scale=None, scales=None) -> Forward:
     """One forward pass of the block.  x, W1, W2, W3 are float arrays holding
     the (bf16-representable) inputs.  ``h_scale`` (plain mode only) is a
-    caller-given per-tensor scale for h, as under delayed scaling."""
+    caller-given per-tensor scale for h, as under delayed scaling.  ``scales``
+    may give the per-tensor scales of "x", "w1", "w2" (delayed scaling,
+    Section 2: the scale comes from earlier iterations; values beyond the range
+    it allows saturate); the ranges seen in this call are returned in ``amax``."""
     x = np.asarray(x); W1 = np.asarray(W1); W2 = np.asarray(W2); W3 = np.asarray(W3)
     out = Forward(quantized=quantized, smooth=smooth)
 
@@ -140,9 +144,11 @@ def forward(x, W1, W2, W3, *, quantized: bool = True, smooth: bool = True,
         return out
 
     # 1. per-tensor E4M3 of the input and of the first two weight matrices
-    out.x_q, out.sx, _ = quant.quantize_per_tensor(x, fp8.E4M3)
-    out.w1_q, out.sw1, _ = quant.quantize_per_tensor(W1, fp8.E4M3)
-    out.w2_q, out.sw2, _ = quant.quantize_per_tensor(W2, fp8.E4M3)
+    given = scales or {}
+    out.amax = {}
+    out.x_q, out.sx, out.amax["x"] = quant.quantize_per_tensor(x, fp8.E4M3, scale=given.get("x"))
+    out.w1_q, out.sw1, out.amax["w1"] = quant.quantize_per_tensor(W1, fp8.E4M3, scale=given.get("w1"))
+    out.w2_q, out.sw2, out.amax["w2"] = quant.quantize_per_tensor(W2, fp8.E4M3, scale=given.get("w2"))
     # 2. the two inner products of Eq. 2, dequantized, stored as bf16
     out.U = round_bf16(gemm.matmul_nt(out.x_q, fp8.E4M3, out.w1_q, fp8.E4M3)
                        / (np.float64(out.sx) * np.float64(out.sw1)))
@@ -183,17 +189,21 @@ class Backward:
     dW1: np.ndarray = field(default=None)
     dW2: np.ndarray = field(default=None)
     dW3: np.ndarray = field(default=None)
+    amax: Optional[dict] = None              # ranges of dy, du, dg seen in this call
 
 
 def backward(fw: Forward, dY, *, dx_dtype: str = "bf16", dw_dtype: str = "f32",
-             stored_dU_dG=None) -> Backward:
+             stored_dU_dG=None, scales=None) -> Backward:
     """Gradients of sum(Y * dY) with respect to x, W1, W2, W3.
 
     ``stored_dU_dG`` = (dU, dG), bf16-valued arrays: continue from step 10 with
     these stored activations' gradients instead of the ones step 9 produced.
     Tests use it to check the later steps on identical inputs when an earlier
-    step differed from another implementation by a bf16 rounding."""
+    step differed from another implementation by a bf16 rounding.
+    ``scales`` may give the per-tensor scales of "dy", "du", "dg" (delayed scaling)."""
     bw = Backward()
+    given = scales or {}
+    bw.amax = {}
     if not fw.quantized:
         dY64 = np.asarray(dY, np.float64)
         if fw.smooth:
@@ -210,7 +220,7 @@ def backward(fw: Forward, dY, *, dx_dtype: str = "bf16", dw_dtype: str = "f32",
         return bw
 
     # 7. upstream gradient to E5M2
-    bw.dy_q, bw.sdy, _ = quant.quantize_per_tensor(dY, fp8.E5M2)
+    bw.dy_q, bw.sdy, bw.amax["dy"] = quant.quantize_per_tensor(dY, fp8.E5M2, scale=given.get("dy"))
     sdy, sw3 = np.float64(bw.sdy), np.float64(fw.sw3)
     # 8. gradient at h: contract dY^ with w3~ over the model dimension
     #    (w3_q is [d,f]; its transpose [f,d] has the contraction index last)
@@ -225,8 +235,8 @@ def backward(fw: Forward, dY, *, dx_dtype: str = "bf16", dw_dtype: str = "f32",
     if stored_dU_dG is not None:
         bw.dU, bw.dG = (np.asarray(v, np.float64) for v in stored_dU_dG)
     # 10. two tensors, two E5M2 scales
-    bw.du_q, bw.sdu, _ = quant.quantize_per_tensor(bw.dU, fp8.E5M2)
-    bw.dg_q, bw.sdg, _ = quant.quantize_per_tensor(bw.dG, fp8.E5M2)
+    bw.du_q, bw.sdu, bw.amax["du"] = quant.quantize_per_tensor(bw.dU, fp8.E5M2, scale=given.get("du"))
+    bw.dg_q, bw.sdg, bw.amax["dg"] = quant.quantize_per_tensor(bw.dG, fp8.E5M2, scale=given.get("dg"))
     sdu, sdg = np.float64(bw.sdu), np.float64(bw.sdg)
     sx, sw1, sw2 = np.float64(fw.sx), np.float64(fw.sw1), np.float64(fw.sw2)
     # 11. input gradient: two contractions over the channel index
