@@ -17,7 +17,7 @@ def test_stationary_tensors_reduce_to_current_scaling():
     npi = _np(synth.make_inputs(64, 64, 96, seed=5))
     cur_f = mlp.forward(npi["x"], npi["W1"], npi["W2"], npi["W3"])
     cur_b = mlp.backward(cur_f, npi["dY"])
-    ds = scaling.DelayedScaling()
+    ds = scaling.DelayedScaling(history=1)       # only the previous call counts: no older, larger range lingers
     for call in range(3):
         fw = mlp.forward(npi["x"], npi["W1"], npi["W2"], npi["W3"], scales=ds.scales(("x", "w1", "w2")))
         bw = mlp.backward(fw, npi["dY"], scales=ds.scales(("dy", "du", "dg")))
