@@ -51,7 +51,8 @@ typedef enum {
 typedef enum { SSG_E4M3 = 0, SSG_E5M2 = 1 } ssg_fp8_format;      /* OCP FP8 encodings (Section 2) */
 typedef enum { SSG_BF16 = 0, SSG_F32 = 1 } ssg_dtype;
 typedef enum { SSG_SCALE_CURRENT = 0,   /* scale from this tensor's own range ("just-in-time", Section 2) */
-               SSG_SCALE_GIVEN = 1      /* caller supplies the scale, e.g. from earlier iterations ("delayed") */
+               SSG_SCALE_GIVEN = 1,     /* caller supplies the scale, e.g. from earlier iterations ("delayed") */
+               SSG_SCALE_DELAYED = 2    /* ssg_mlp_desc only: scales come from the amax history in `scaling_state` */
 } ssg_scale_mode;
 typedef enum { SSG_ROUND_EXACT_DIV = 0, /* scale = fl32(fmax / amax) */
                SSG_ROUND_POW2 = 1       /* scale = 2^floor(log2(fmax / amax)) */
@@ -126,8 +127,26 @@ typedef struct {
                                 buffer: keep its Q(w1), Q(w2), their transposes and scales and W3's per-channel
                                 ranges instead of recomputing them (quantize once per optimizer step, run many
                                 micro-batches).  0 = quantize the weights in this call. */
-    int32_t reserved[3];     /* must be 0 */
+    int32_t scale_mode;      /* SSG_SCALE_CURRENT, or SSG_SCALE_DELAYED (needs scaling_state): the per-tensor scales of
+                                x, W1, W2, dY, dU, dG come from the ranges of earlier calls (Section 2 "delayed
+                                scaling", what the runs of Section 6.2 used), so no stand-alone range pass runs;
+                                values beyond the remembered range saturate.  The per-channel factors of
+                                Smooth-SwiGLU and the scale of the folded w3 stay current. */
+    int32_t reserved[2];     /* must be 0 */
+    void *scaling_state;     /* device, ssg_mlp_scaling_state_bytes() bytes, or NULL.  When given, every call
+                                (current or delayed) enters the ranges it saw into the history. */
 } ssg_mlp_desc;
+
+/* Amax history of delayed scaling.  One state per block instance, kept by the caller across steps,
+ * initialised once with ssg_mlp_scaling_init (empty history: scale 1).  Reading used (the paper gives
+ * none): history of the last 16 calls per tensor, scale = fl32(fmax / largest entry) with the rounding
+ * of desc.rnd, margin 0; the range seen in a call replaces the oldest entry after the call.  A first
+ * call under SSG_SCALE_CURRENT with the state attached fills the history with real ranges.
+ * Layout (32-bit words): tensor k = 0..5 (x, w1, w2, dy, du, dg) owns words [32k, 32k+32):
+ * [0] scale the next call uses (float), [1] ring position, [2] range seen in the last call (float),
+ * [8..24) the ring of ranges (float).  With weights_cached = 1 the entries of w1, w2 are left alone. */
+size_t ssg_mlp_scaling_state_bytes(void);
+ssg_status ssg_mlp_scaling_init(void *scaling_state, void *stream);
 
 /* Sizes of the two caller-allocated device buffers.  `saved` carries what the
  * backward pass needs (quantized operands, their transposed copies, bf16 U and
@@ -148,13 +167,14 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
 
 /* Pointers into `saved` / `workspace` for tests and reports (host struct of device pointers). */
 typedef struct {
-    const float *scales;     /* [0]=sx [1]=sw1 [2]=sw2 [3]=sw3 [4]=amax_x [5]=amax_w1 [6]=amax_w2 [7]=amax of s^-1*w3 */
+    const float *scales;     /* [0]=sx [1]=sw1 [2]=sw2 [3]=sw3 [4]=amax_x [5]=amax_w1 [6]=amax_w2 [7]=amax of s^-1*w3
+                                ([4..6] are written under current scaling only) */
     const float *s, *sinv, *h_camax, *w3_camax;          /* f floats each */
     const uint8_t *x_q, *x_qT, *w1_q, *w2_q, *w1_qT, *w2_qT, *h_q, *h_qT, *w3_q, *w3_qT;
     const void *U, *G;                                   /* bf16 [T,f] */
 } ssg_mlp_saved_view;
 typedef struct {
-    const float *scales;     /* [0]=sdy [1]=sdu [2]=sdg [3]=amax_dy [4]=amax_du [5]=amax_dg */
+    const float *scales;     /* [0]=sdy [1]=sdu [2]=sdg [3]=amax_dy [4]=amax_du [5]=amax_dg ([3..5]: current scaling only) */
     const uint8_t *dy_q, *dy_qT, *du_q, *du_qT, *dg_q, *dg_qT;
     const void *dU, *dG;                                 /* bf16 [T,f] */
 } ssg_mlp_workspace_view;

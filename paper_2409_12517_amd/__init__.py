@@ -26,13 +26,14 @@ _lib = ctypes.CDLL(LIB_PATH)
 SSG_OK, SSG_ERR_ARG, SSG_ERR_SHAPE, SSG_ERR_WORKSPACE, SSG_ERR_HIP, SSG_ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
 SSG_E4M3, SSG_E5M2 = 0, 1
 SSG_BF16, SSG_F32 = 0, 1
-SSG_SCALE_CURRENT, SSG_SCALE_GIVEN = 0, 1
+SSG_SCALE_CURRENT, SSG_SCALE_GIVEN, SSG_SCALE_DELAYED = 0, 1, 2
 SSG_ROUND_EXACT_DIV, SSG_ROUND_POW2 = 0, 1
 
 EXPORTS = [
     "ssg_last_error", "ssg_version", "ssg_amax", "ssg_quantize", "ssg_gemm_fp8", "ssg_swiglu",
     "ssg_smooth_swiglu_quantize", "ssg_fold_w3", "ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes",
     "ssg_mlp_fwd", "ssg_mlp_bwd", "ssg_mlp_view_saved", "ssg_mlp_view_workspace",
+    "ssg_mlp_scaling_state_bytes", "ssg_mlp_scaling_init",
     "ssg_adam_state_bytes", "ssg_adam_init", "ssg_adam_step", "ssg_adam_view_state",
     "ssg_profile_enable", "ssg_profile_read", "ssg_probe_mfma_rate",
 ]
@@ -40,7 +41,8 @@ EXPORTS = [
 
 class ssg_mlp_desc(Structure):
     _fields_ = [("T", c_int64), ("d", c_int64), ("f", c_int64), ("smooth", c_int32), ("rnd", c_int32),
-                ("y_dtype", c_int32), ("dw_dtype", c_int32), ("weights_cached", c_int32), ("reserved", c_int32 * 3)]
+                ("y_dtype", c_int32), ("dw_dtype", c_int32), ("weights_cached", c_int32), ("scale_mode", c_int32),
+                ("reserved", c_int32 * 2), ("scaling_state", c_void_p)]
 
 
 class ssg_adam_desc(Structure):
@@ -85,6 +87,9 @@ _lib.ssg_mlp_view_saved.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg
 _lib.ssg_mlp_view_workspace.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_workspace_view)]
 _lib.ssg_profile_enable.argtypes = [c_int]
 _lib.ssg_profile_read.argtypes = [POINTER(c_float), POINTER(c_int), c_int]
+_lib.ssg_mlp_scaling_state_bytes.argtypes = []
+_lib.ssg_mlp_scaling_state_bytes.restype = c_size_t
+_lib.ssg_mlp_scaling_init.argtypes = [c_void_p, c_void_p]
 _lib.ssg_adam_state_bytes.argtypes = [c_int64]
 _lib.ssg_adam_state_bytes.restype = c_size_t
 _lib.ssg_adam_init.argtypes = [c_int64, c_void_p, c_void_p]
@@ -92,7 +97,7 @@ _lib.ssg_adam_step.argtypes = [POINTER(ssg_adam_desc), c_void_p, c_void_p, c_voi
 _lib.ssg_adam_view_state.argtypes = [c_int64, c_int32, c_void_p, POINTER(ssg_adam_state_view)]
 _lib.ssg_probe_mfma_rate.argtypes = [c_void_p, c_size_t, c_int, POINTER(ctypes.c_double), c_void_p]
 for _n in EXPORTS[2:]:
-    if _n not in ("ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes"):
+    if not _n.endswith("_bytes"):          # the size queries return size_t, everything else a status
         getattr(_lib, _n).restype = c_int
 
 
@@ -132,8 +137,11 @@ def _stream(stream):
 
 
 def make_desc(T: int, d: int, f: int, smooth: int = 1, rnd: int = SSG_ROUND_EXACT_DIV,
-              y_dtype: int = SSG_BF16, dw_dtype: int = SSG_F32, weights_cached: int = 0) -> ssg_mlp_desc:
-    return ssg_mlp_desc(T, d, f, smooth, rnd, y_dtype, dw_dtype, weights_cached, (c_int32 * 3)(0, 0, 0))
+              y_dtype: int = SSG_BF16, dw_dtype: int = SSG_F32, weights_cached: int = 0,
+              scale_mode: int = SSG_SCALE_CURRENT, scaling_state=None) -> ssg_mlp_desc:
+    """`scaling_state`: a device byte tensor of ssg_mlp_scaling_state_bytes() bytes (kept alive by the caller)."""
+    return ssg_mlp_desc(T, d, f, smooth, rnd, y_dtype, dw_dtype, weights_cached, scale_mode, (c_int32 * 2)(0, 0),
+                        _ptr(scaling_state))
 
 
 def ssg_amax(src, src_dtype, n, amax_dev, stream=None):
@@ -192,6 +200,14 @@ def ssg_mlp_view_workspace(desc, workspace) -> ssg_mlp_workspace_view:
     v = ssg_mlp_workspace_view()
     _check(_lib.ssg_mlp_view_workspace(ctypes.byref(desc), _ptr(workspace), ctypes.byref(v)))
     return v
+
+
+def ssg_mlp_scaling_state_bytes() -> int:
+    return int(_lib.ssg_mlp_scaling_state_bytes())
+
+
+def ssg_mlp_scaling_init(state, stream=None) -> None:
+    _check(_lib.ssg_mlp_scaling_init(_ptr(state), _stream(stream)))
 
 
 def ssg_profile_enable(max_records: int) -> None:

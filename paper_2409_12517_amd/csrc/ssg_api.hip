@@ -112,7 +112,13 @@ ssg_status check_desc(const ssg_mlp_desc *d, const char *who) {
     if (d->rnd != SSG_ROUND_EXACT_DIV && d->rnd != SSG_ROUND_POW2) return fail(SSG_ERR_ARG, "%s: bad rnd", who);
     if (!dtype_ok(d->y_dtype) || !dtype_ok(d->dw_dtype)) return fail(SSG_ERR_ARG, "%s: bad output dtype", who);
     if (d->weights_cached != 0 && d->weights_cached != 1) return fail(SSG_ERR_ARG, "%s: weights_cached must be 0 or 1", who);
-    for (int i = 0; i < 3; ++i)
+    if (d->scale_mode != SSG_SCALE_CURRENT && d->scale_mode != SSG_SCALE_DELAYED)
+        return fail(SSG_ERR_ARG, "%s: scale_mode must be SSG_SCALE_CURRENT or SSG_SCALE_DELAYED", who);
+    if (d->scale_mode == SSG_SCALE_DELAYED && d->scaling_state == nullptr)
+        return fail(SSG_ERR_ARG, "%s: SSG_SCALE_DELAYED needs scaling_state", who);
+    if (d->scaling_state != nullptr && !aligned16(d->scaling_state))
+        return fail(SSG_ERR_ARG, "%s: scaling_state is not 16-byte aligned", who);
+    for (int i = 0; i < 2; ++i)
         if (d->reserved[i] != 0) return fail(SSG_ERR_ARG, "%s: reserved fields must be 0", who);
     return SSG_OK;
 }
@@ -381,6 +387,14 @@ size_t ssg_mlp_workspace_bytes(const ssg_mlp_desc *desc) {
     return work_layout(*desc).total;
 }
 
+size_t ssg_mlp_scaling_state_bytes(void) { return align256(ssg::kScalingWords * sizeof(uint32_t)); }
+
+ssg_status ssg_mlp_scaling_init(void *scaling_state, void *stream) {
+    SSG_REQUIRE_PTR(scaling_state);
+    ssg::launch_scaling_init(static_cast<uint32_t *>(scaling_state), static_cast<hipStream_t>(stream));
+    return check_launch("ssg_mlp_scaling_init");
+}
+
 ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_mlp_saved_view *out) {
     ssg_status rc = check_desc(desc, "ssg_mlp_view_saved");
     if (rc != SSG_OK) return rc;
@@ -440,21 +454,30 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     // a1 + a2: per-tensor range (Section 2), then Q (Eq. 2) with the transposed copy the backward
     // contractions read.  Range and cast of one tensor run back to back so that the second read of
     // the tensor can still be served from the memory-side cache.
+    // Delayed scaling (Section 2): the scale comes from the history in the caller's state and the
+    // cast itself records the range it sees, so the stand-alone range pass disappears.
+    const bool delayed = desc->scale_mode == SSG_SCALE_DELAYED;
+    uint32_t *state = static_cast<uint32_t *>(desc->scaling_state);
+    auto state_scale = [&](int k) { return reinterpret_cast<float *>(state + (size_t)k * ssg::kScalingStride); };
+    auto state_slots = [&](int j) { return state + ssg::kScalingHeaderWords + (size_t)j * ssg::kAmaxSlotWords; };
     ssg::CastArgs c;
     c.kind = ssg::SRC_BF16; c.fmt = ssg::kE4M3; c.pow2 = pow2;
     c.amax_slots = ssg::kAmaxSlots;
-    ssg::launch_amax(x, ssg::SRC_BF16, (size_t)(T * dm), part_x, ssg::kAmaxSlots, st);
-    c.src = x; c.rows = T; c.cols = dm; c.amax = reinterpret_cast<float *>(part_x); c.amax_out = sc + S_AMAX_X; c.scale_out = sc + S_SX;
-    c.dst = b + L.x_q; c.dst_t = b + L.x_qT;
-    ssg::launch_cast(c, st);
+    auto quantize_input = [&](const void *src, int64_t rows, int64_t cols, uint32_t *part, int k, float *amax_out,
+                              float *scale_out, uint8_t *dst, uint8_t *dst_t) {
+        c.src = src; c.rows = rows; c.cols = cols; c.scale_out = scale_out; c.dst = dst; c.dst_t = dst_t;
+        if (delayed) {
+            c.amax = nullptr; c.amax_out = nullptr; c.scale_in = state_scale(k); c.record = state_slots(k);
+        } else {
+            ssg::launch_amax(src, ssg::SRC_BF16, (size_t)(rows * cols), part, ssg::kAmaxSlots, st);
+            c.amax = reinterpret_cast<float *>(part); c.amax_out = amax_out; c.scale_in = nullptr; c.record = nullptr;
+        }
+        ssg::launch_cast(c, st);
+    };
+    quantize_input(x, T, dm, part_x, 0, sc + S_AMAX_X, sc + S_SX, b + L.x_q, b + L.x_qT);
     if (!cached) {
-        ssg::launch_amax(W1, ssg::SRC_BF16, (size_t)(f * dm), part_w1, ssg::kAmaxSlots, st);
-        c.src = W1; c.rows = f; c.cols = dm; c.amax = reinterpret_cast<float *>(part_w1); c.amax_out = sc + S_AMAX_W1; c.scale_out = sc + S_SW1;
-        c.dst = b + L.w1_q; c.dst_t = b + L.w1_qT;
-        ssg::launch_cast(c, st);
-        ssg::launch_amax(W2, ssg::SRC_BF16, (size_t)(f * dm), part_w2, ssg::kAmaxSlots, st);
-        c.src = W2; c.amax = reinterpret_cast<float *>(part_w2); c.amax_out = sc + S_AMAX_W2; c.scale_out = sc + S_SW2; c.dst = b + L.w2_q; c.dst_t = b + L.w2_qT;
-        ssg::launch_cast(c, st);
+        quantize_input(W1, f, dm, part_w1, 1, sc + S_AMAX_W1, sc + S_SW1, b + L.w1_q, b + L.w1_qT);
+        quantize_input(W2, f, dm, part_w2, 2, sc + S_AMAX_W2, sc + S_SW2, b + L.w2_q, b + L.w2_qT);
         // per-channel range of w3, needed for the range of s^-1 * w3 (constant between weight updates)
         ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
     }
@@ -490,6 +513,19 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     g2.sa = desc->smooth ? nullptr : s; g2.sb = sc + S_SW3;
     g2.C = y; g2.c_f32 = desc->y_dtype == SSG_F32;
     ssg::launch_gemm(g2, st);
+
+    if (state) {
+        // enter this call's ranges into the history; the scales written here serve the next call
+        ssg::ScalingUpdate u;
+        u.pow2 = pow2;
+        u.slots[0] = delayed ? state_slots(0) : part_x; u.tensor[0] = 0; u.fmt[0] = ssg::kE4M3; u.count = 1;
+        if (!cached) {
+            u.slots[1] = delayed ? state_slots(1) : part_w1; u.tensor[1] = 1; u.fmt[1] = ssg::kE4M3;
+            u.slots[2] = delayed ? state_slots(2) : part_w2; u.tensor[2] = 2; u.fmt[2] = ssg::kE4M3;
+            u.count = 3;
+        }
+        ssg::launch_scaling_update(state, u, st);
+    }
     return check_launch("ssg_mlp_fwd");
 }
 
@@ -516,12 +552,23 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     uint32_t *part_dy = wpart, *part_du = wpart + ssg::kAmaxSlotWords, *part_dg = wpart + 2 * ssg::kAmaxSlotWords;
     ssg::launch_fill_u32(wscb, (Wl.partials - Wl.scalars) / 4 + 3 * ssg::kAmaxSlotWords, 0u, st);
 
+    const bool delayed = desc->scale_mode == SSG_SCALE_DELAYED;
+    uint32_t *state = static_cast<uint32_t *>(desc->scaling_state);
+    auto state_scale = [&](int k) { return reinterpret_cast<float *>(state + (size_t)k * ssg::kScalingStride); };
+    uint32_t *state_dy_slots = state ? state + ssg::kScalingHeaderWords + 3 * ssg::kAmaxSlotWords : nullptr;
+
     // a9: upstream gradient to E5M2 (Section 6.2), with its transposed copy
-    ssg::launch_amax(dy, ssg::SRC_BF16, (size_t)(T * dm), part_dy, ssg::kAmaxSlots, st);
     ssg::CastArgs c;
     c.src = dy; c.kind = ssg::SRC_BF16; c.rows = T; c.cols = dm; c.fmt = ssg::kE5M2; c.pow2 = pow2;
-    c.amax = reinterpret_cast<float *>(part_dy); c.amax_slots = ssg::kAmaxSlots; c.amax_out = wsc + W_AMAX_DY; c.scale_out = wsc + W_SDY; c.dst = wk + Wl.dy_q; c.dst_t = wk + Wl.dy_qT;
+    c.amax_slots = ssg::kAmaxSlots; c.scale_out = wsc + W_SDY; c.dst = wk + Wl.dy_q; c.dst_t = wk + Wl.dy_qT;
+    if (delayed) {
+        c.scale_in = state_scale(3); c.record = state_dy_slots;
+    } else {
+        ssg::launch_amax(dy, ssg::SRC_BF16, (size_t)(T * dm), part_dy, ssg::kAmaxSlots, st);
+        c.amax = reinterpret_cast<float *>(part_dy); c.amax_out = wsc + W_AMAX_DY;
+    }
     ssg::launch_cast(c, st);
+    c.record = nullptr;
 
     // a10: dH = s_i * dY^ w3~ / (sdy sw3), then through the SwiGLU product
     ssg::GemmArgs g;
@@ -532,12 +579,24 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     g.U = sv + L.U; g.G = sv + L.G; g.C = wk + Wl.dU; g.C2 = wk + Wl.dG; g.amax_bits = part_du; g.amax_bits2 = part_dg;
     ssg::launch_gemm(g, st);
 
-    // a11: two tensors, two E5M2 scales
+    // a11: two tensors, two E5M2 scales (their ranges came out of the epilogue above either way)
     c.kind = ssg::SRC_BF16; c.rows = T; c.cols = f;
-    c.src = wk + Wl.dU; c.amax = reinterpret_cast<float *>(part_du); c.amax_out = wsc + W_AMAX_DU; c.scale_out = wsc + W_SDU; c.dst = wk + Wl.du_q; c.dst_t = wk + Wl.du_qT;
+    c.src = wk + Wl.dU; c.scale_out = wsc + W_SDU; c.dst = wk + Wl.du_q; c.dst_t = wk + Wl.du_qT;
+    if (delayed) { c.amax = nullptr; c.amax_out = nullptr; c.scale_in = state_scale(4); }
+    else { c.amax = reinterpret_cast<float *>(part_du); c.amax_out = wsc + W_AMAX_DU; }
     ssg::launch_cast(c, st);
-    c.src = wk + Wl.dG; c.amax = reinterpret_cast<float *>(part_dg); c.amax_out = wsc + W_AMAX_DG; c.scale_out = wsc + W_SDG; c.dst = wk + Wl.dg_q; c.dst_t = wk + Wl.dg_qT;
+    c.src = wk + Wl.dG; c.scale_out = wsc + W_SDG; c.dst = wk + Wl.dg_q; c.dst_t = wk + Wl.dg_qT;
+    if (delayed) { c.scale_in = state_scale(5); }
+    else { c.amax = reinterpret_cast<float *>(part_dg); c.amax_out = wsc + W_AMAX_DG; }
     ssg::launch_cast(c, st);
+    if (state) {
+        ssg::ScalingUpdate u;
+        u.pow2 = pow2; u.count = 3;
+        u.slots[0] = delayed ? state_dy_slots : part_dy; u.tensor[0] = 3; u.fmt[0] = ssg::kE5M2;
+        u.slots[1] = part_du; u.tensor[1] = 4; u.fmt[1] = ssg::kE5M2;
+        u.slots[2] = part_dg; u.tensor[2] = 5; u.fmt[2] = ssg::kE5M2;
+        ssg::launch_scaling_update(state, u, st);
+    }
 
     // a12: dW3[j,i] = sinv_i * sum_t dY^[t,j] h^[t,i] / sdy   (plain: / (sdy * sigma_h))
     ssg::GemmArgs g3;

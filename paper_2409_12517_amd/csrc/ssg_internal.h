@@ -37,6 +37,8 @@ struct CastArgs {
     const float *scale_in = nullptr; // ... or a given scale; both null = no per-tensor factor
     int pow2 = 0;
     float *scale_out = nullptr;      // where the per-tensor scale is recorded (may be null)
+    uint32_t *record = nullptr;      // optional kAmaxSlots slotted words: max |src| seen by this pass is folded in
+                                     // (bf16 source, no per-column factor, transposed copy requested)
     uint8_t *dst = nullptr;          // [rows, cols]
     uint8_t *dst_t = nullptr;        // [cols, rows] or null
 };
@@ -91,6 +93,24 @@ void launch_gemm(const GemmArgs &a, hipStream_t st);
 // Benchmark hook: called by launch_gemm before and after the kernel launch (no-ops unless enabled).
 void profile_before(int tag, hipStream_t st);
 void profile_after(hipStream_t st);
+
+// ---- delayed scaling: amax history per tensor (ssg_quant.hip) ----------------------
+// State words: tensor k (0..5 = x, w1, w2, dy, du, dg) owns words [32k, 32k+32): [0] the scale the next
+// call uses (float), [1] position in the history ring, [2] the range seen in the last call (float),
+// [8, 8+kScalingHistory) the ring of ranges.  From word kScalingHeaderWords on: four slotted range
+// accumulators (x, w1, w2, dy) of kAmaxSlotWords words each, zero between calls.
+constexpr int kScalingTensors = 6, kScalingHistory = 16, kScalingStride = 32;
+constexpr size_t kScalingHeaderWords = 256;
+constexpr size_t kScalingWords = kScalingHeaderWords + 4 * kAmaxSlotWords;
+struct ScalingUpdate {
+    uint32_t *slots[3] = {nullptr, nullptr, nullptr};   // slotted range words of the call just made (cleared afterwards)
+    int tensor[3] = {0, 0, 0};
+    int fmt[3] = {0, 0, 0};
+    int count = 0;
+    int pow2 = 0;
+};
+void launch_scaling_init(uint32_t *state, hipStream_t st);
+void launch_scaling_update(uint32_t *state, const ScalingUpdate &u, hipStream_t st);
 
 // ---- Adam with FP8 moments (ssg_adam.hip) ---------------------------------------
 struct AdamArgs {

@@ -5,6 +5,8 @@
 // All loads and stores are 16-byte (8-byte for row-major code stores) vectors
 // along the contiguous index; reductions use one atomic max per workgroup or
 // per column on the float's bit pattern (|x| orders like an unsigned integer).
+#include <type_traits>
+
 #include "ssg_device.h"
 #include "ssg_internal.h"
 
@@ -147,12 +149,13 @@ __device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint3
     o[3] = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x07060302u);
 }
 
-template <class Loader, int FMT, bool COLSCALE, bool TRANSPOSED>
+template <class Loader, int FMT, bool COLSCALE, bool TRANSPOSED, bool RECORD = false>
 __global__ void __launch_bounds__(256)
 cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col_scale,
             const float *__restrict__ amax, int amax_slots, float *__restrict__ amax_out,
             const float *__restrict__ scale_in, int pow2,
-            float *__restrict__ scale_out, uint8_t *__restrict__ dst, uint8_t *__restrict__ dst_t) {
+            float *__restrict__ scale_out, uint8_t *__restrict__ dst, uint8_t *__restrict__ dst_t,
+            uint32_t *__restrict__ record = nullptr) {
     __shared__ uint32_t tile[TRANSPOSED ? kTile * kTPitchWords : 1];
 
     float sigma = 1.0f;
@@ -189,6 +192,7 @@ cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col
         cs[4] = b.x; cs[5] = b.y; cs[6] = b.z; cs[7] = b.w;
     }
 
+    uint32_t seen = 0;                                 // RECORD: largest |source value| this lane met
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         const int lr = half * 64 + r4 * 4;             // local row of the 4-row group
@@ -199,6 +203,13 @@ cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col
                 const size_t off = (size_t)(row0 + lr + r) * (size_t)cols + (size_t)col;
                 float v[8];
                 ld.load8(off, v);
+                if (RECORD) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const uint32_t ab = abs_bits_ignore_nan(v[i]);
+                        seen = seen > ab ? seen : ab;
+                    }
+                }
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     if (COLSCALE) v[i] = __fmul_rn(v[i], cs[i]);
@@ -218,6 +229,12 @@ cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col
 #pragma unroll
             for (int j = 0; j < 4; ++j) tile[(c8 * 8 + 4 + j) * kTPitchWords + (lr >> 2)] = t[j];
         }
+    }
+    if (RECORD) {
+        // the range this pass saw, for the history of delayed scaling: one atomic per wave
+        seen = wave_max_u32(seen);
+        if ((threadIdx.x & 63) == 0 && seen)
+            atomicMax(record + ((blockIdx.y * gridDim.x + blockIdx.x) % kAmaxSlots) * kAmaxSlotStride, seen);
     }
     if (TRANSPOSED) {
         __syncthreads();
@@ -242,6 +259,14 @@ static void launch_cast_l(const Loader &ld, const CastArgs &a, hipStream_t st) {
 #define SSG_CAST(CS, TR)                                                                               \
     hipLaunchKernelGGL((cast_kernel<Loader, FMT, CS, TR>), grid, dim3(256), 0, st, ld, a.rows, a.cols, \
                        a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst, a.dst_t)
+    if constexpr (std::is_same<Loader, LoadBf16>::value) {
+        if (a.record && !cs && tr) {
+            hipLaunchKernelGGL((cast_kernel<Loader, FMT, false, true, true>), grid, dim3(256), 0, st, ld, a.rows, a.cols,
+                               a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst,
+                               a.dst_t, a.record);
+            return;
+        }
+    }
     if (cs && tr) SSG_CAST(true, true);
     else if (cs) SSG_CAST(true, false);
     else if (tr) SSG_CAST(false, true);
@@ -407,6 +432,44 @@ void launch_swiglu(const void *U, const void *G, int64_t n, float *h, hipStream_
     if (n8 == 0) return;
     hipLaunchKernelGGL(swiglu_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, st,
                        LoadSwiglu{(const uint16_t *)U, (const uint16_t *)G}, n8, h);
+}
+
+// ------------------------------------------------------------------ delayed scaling state
+__global__ void __launch_bounds__(256) scaling_init_kernel(uint32_t *state, size_t words) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= words) return;
+    const bool is_scale = i < (size_t)kScalingTensors * kScalingStride && (i % kScalingStride) == 0;
+    state[i] = is_scale ? 0x3f800000u : 0u;            // empty history: scale 1
+}
+void launch_scaling_init(uint32_t *state, hipStream_t st) {
+    hipLaunchKernelGGL(scaling_init_kernel, dim3((unsigned)((kScalingWords + 255) / 256)), dim3(256), 0, st, state,
+                       kScalingWords);
+}
+
+// One wave per tensor: the range of the call just made (maximum over its slots, which are cleared
+// for the next call) replaces the oldest history entry; the next call's scale is fmax over the
+// largest entry (Section 2, delayed scaling).
+__global__ void __launch_bounds__(64) scaling_update_kernel(uint32_t *state, ScalingUpdate u) {
+    const int k = blockIdx.x, lane = threadIdx.x;
+    uint32_t *slots = u.slots[k];
+    const uint32_t seen = wave_max_u32(slots[lane * kAmaxSlotStride]);
+    slots[lane * kAmaxSlotStride] = 0u;
+    uint32_t *w = state + (size_t)u.tensor[k] * kScalingStride;
+    const uint32_t pos = w[1] % kScalingHistory;
+    uint32_t h = lane < kScalingHistory ? w[8 + lane] : 0u;
+    if (lane == (int)pos) h = seen;
+    const float largest = __uint_as_float(wave_max_u32(h));
+    const float fmax = u.fmt[k] == kE4M3 ? Fp8Traits<kE4M3>::fmax : Fp8Traits<kE5M2>::fmax;
+    if (lane == 0) {
+        w[8 + pos] = seen;
+        w[1] = (pos + 1) % kScalingHistory;
+        w[2] = seen;
+        w[0] = __float_as_uint(scale_from_amax(largest, fmax, u.pow2));
+    }
+}
+void launch_scaling_update(uint32_t *state, const ScalingUpdate &u, hipStream_t st) {
+    if (u.count <= 0) return;
+    hipLaunchKernelGGL(scaling_update_kernel, dim3((unsigned)u.count), dim3(64), 0, st, state, u);
 }
 
 }  // namespace ssg
