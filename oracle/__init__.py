@@ -19,4 +19,4 @@ readings stated in the docstrings of ``quant.py`` and ``mlp.py``.  Everything
 else is pinned by the CPU tests (closed forms, exhaustive code round trips,
 exact integer brute force, fp64 autograd of the unquantized function).
 """
-from . import fp8, quant, swiglu, gemm, mlp, adam, scaling  # noqa: F401
+from . import fp8, quant, swiglu, gemm, mlp, adam, scaling, infer  # noqa: F401
