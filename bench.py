@@ -280,6 +280,24 @@ def main() -> int:
     step()
     torch.cuda.synchronize()
 
+    # fourth figure: the inference form (end of Section 4.4): factors of a calibration call folded into w1, w3 once;
+    # a forward is Q(x), one GEMM with the SwiGLU product and its E4M3 cast fused, one GEMM.  6*T*d*f flops.
+    sview = ssg.ssg_mlp_view_saved(desc, saved)
+    s_vec = ssg.view_tensor(saved, saved.data_ptr(), sview.s, (f,), torch.float32).clone()
+    sinv_vec = ssg.view_tensor(saved, saved.data_ptr(), sview.sinv, (f,), torch.float32).clone()
+    prep = torch.empty(ssg.ssg_infer_prepared_bytes(desc), dtype=torch.uint8, device=dev)
+    iwork = torch.empty(ssg.ssg_infer_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    ssg.ssg_infer_prepare(desc, W1, W2, W3, s_vec, sinv_vec, prep, stream)
+    for _ in range(3):
+        ssg.ssg_infer_fwd(desc, x, prep, y, iwork, stream)
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    for _ in range(args.steps):
+        ssg.ssg_infer_fwd(desc, x, prep, y, iwork, stream)
+    torch.cuda.synchronize()
+    dt_infer = time.perf_counter() - t3
+    del prep, iwork
+
     ms_per_step = dt * 1e3 / args.steps
     flops_step = 18.0 * T * d * f
     value = flops_step / (ms_per_step * 1e-3) / 1e12
@@ -319,6 +337,10 @@ def main() -> int:
                             "ms_per_step": dt_delayed * 1e3 / args.steps,
                             "note": "same step with the per-tensor scales taken from a 16-call amax history "
                                     "(no range passes over x, W1, W2, dY); not the headline"},
+        "inference_forward": {"value": 6.0 * T * d * f / (dt_infer / args.steps) / 1e12, "unit": "TFLOP/s",
+                              "ms_per_call": dt_infer * 1e3 / args.steps,
+                              "note": "forward only with the calibrated factors folded into w1 and w3 "
+                                      "(ssg_infer_fwd): Q(x), GEMM + SwiGLU + E4M3 cast, GEMM; not the headline"},
         "config": {"workload": f"{cfg.name}: Llama2-7B MLP fwd+bwd, T={T} d_model={d} d_ffn={f}, Smooth-SwiGLU, "
                                "current scaling, W1/W2 quantized every step",
                    "T": T, "d_model": d, "d_ffn": f, "seed": cfg.seed},

@@ -181,6 +181,33 @@ typedef struct {
 ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_mlp_saved_view *out);
 ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspace, ssg_mlp_workspace_view *out);
 
+/* ---- inference with the factors folded into the weights (end of Section 4.4) --------
+ * With the per-channel factors fixed (s, sinv: the two f-vectors a calibration call of ssg_mlp_fwd
+ * left in its `saved` buffer), they are absorbed once into the weights,
+ *     w1~_i = Q(s_i w1_i)     w2^ = Q(w2)     w3~_i = Q(s_i^-1 w3_i)        (per-tensor E4M3 each)
+ * and a forward call does no per-channel work: x^ = Q(x); one GEMM kernel forms both inner
+ * products, the SwiGLU product (s_i u_i) Swish(g_i) from the dequantized fp32 inner products and
+ * casts it to E4M3 as it stands (no bf16 U, G are stored: nothing is kept for a backward pass);
+ * y = h^ w3~^T / sigma_w3.
+ * desc: the block's T, d, f, rnd, y_dtype (smooth must be 1, scale_mode current; T may differ from call
+ * to call with the same `prepared`).  prepared / workspace: device, caller-owned, sizes from the two
+ * queries.  W1, W2 [f,d], W3 [d,f], x [T,d] bf16; s, sinv [f] fp32; y [T,d] y_dtype.  Asynchronous,
+ * nothing allocated; a negative status means nothing was launched. */
+typedef struct {
+    const float *weight_scales;   /* [0]=scale of w1~ [1]=scale of w2^ [2]=scale of w3~ [4..6] their ranges */
+    const uint8_t *w1_q, *w2_q;   /* [f,d] */
+    const uint8_t *w3_q;          /* [d,f] */
+    const float *x_scale;         /* [0]=scale of x^ [1]=range of x (last call) */
+    const uint8_t *x_q, *h_q;     /* [T,d], [T,f] of the last call */
+} ssg_infer_view_t;
+size_t ssg_infer_prepared_bytes(const ssg_mlp_desc *desc);
+size_t ssg_infer_workspace_bytes(const ssg_mlp_desc *desc);
+ssg_status ssg_infer_prepare(const ssg_mlp_desc *desc, const void *W1, const void *W2, const void *W3, const float *s,
+                             const float *sinv, void *prepared, void *stream);
+ssg_status ssg_infer_fwd(const ssg_mlp_desc *desc, const void *x, const void *prepared, void *y, void *workspace,
+                         void *stream);
+ssg_status ssg_infer_view(const ssg_mlp_desc *desc, const void *prepared, const void *workspace, ssg_infer_view_t *out);
+
 /* ---- Adam with both moments in FP8 (Section 5) -------------------------------
  * The first moment is stored in E4M3 and the second in E5M2 (Section 5.2), each with one
  * per-tensor scale chosen from the range of the new moment as in Section 2
@@ -231,7 +258,8 @@ ssg_status ssg_adam_view_state(int64_t n, int32_t step, const void *state, ssg_a
  *                          milliseconds and their tags (host arrays), clears the record list and
  *                          returns the number written, or a negative ssg_status.
  *                          tag = 2 * epilogue + a_fmt with epilogue 0 = plain store (y, dx, dW),
- *                          1 = fused SwiGLU forward (U, G, channel maxima), 2 = fused SwiGLU backward;
+ *                          1 = fused SwiGLU forward (U, G, channel maxima), 2 = fused SwiGLU backward,
+ *                          3 = fused SwiGLU product + E4M3 cast of the inference form;
  *                          +8 for the two-product form of the plain store (dx).
  *                          The two passes of ssg_adam_step are recorded too: tag 32 = range pass,
  *                          33 = update pass. */

@@ -34,6 +34,7 @@ EXPORTS = [
     "ssg_smooth_swiglu_quantize", "ssg_fold_w3", "ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes",
     "ssg_mlp_fwd", "ssg_mlp_bwd", "ssg_mlp_view_saved", "ssg_mlp_view_workspace",
     "ssg_mlp_scaling_state_bytes", "ssg_mlp_scaling_init",
+    "ssg_infer_prepared_bytes", "ssg_infer_workspace_bytes", "ssg_infer_prepare", "ssg_infer_fwd", "ssg_infer_view",
     "ssg_adam_state_bytes", "ssg_adam_init", "ssg_adam_step", "ssg_adam_view_state",
     "ssg_profile_enable", "ssg_profile_read", "ssg_probe_mfma_rate",
 ]
@@ -43,6 +44,10 @@ class ssg_mlp_desc(Structure):
     _fields_ = [("T", c_int64), ("d", c_int64), ("f", c_int64), ("smooth", c_int32), ("rnd", c_int32),
                 ("y_dtype", c_int32), ("dw_dtype", c_int32), ("weights_cached", c_int32), ("scale_mode", c_int32),
                 ("reserved", c_int32 * 2), ("scaling_state", c_void_p)]
+
+
+class ssg_infer_view_t(Structure):
+    _fields_ = [(n, c_void_p) for n in ("weight_scales", "w1_q", "w2_q", "w3_q", "x_scale", "x_q", "h_q")]
 
 
 class ssg_adam_desc(Structure):
@@ -90,6 +95,13 @@ _lib.ssg_profile_read.argtypes = [POINTER(c_float), POINTER(c_int), c_int]
 _lib.ssg_mlp_scaling_state_bytes.argtypes = []
 _lib.ssg_mlp_scaling_state_bytes.restype = c_size_t
 _lib.ssg_mlp_scaling_init.argtypes = [c_void_p, c_void_p]
+_lib.ssg_infer_prepared_bytes.argtypes = [POINTER(ssg_mlp_desc)]
+_lib.ssg_infer_prepared_bytes.restype = c_size_t
+_lib.ssg_infer_workspace_bytes.argtypes = [POINTER(ssg_mlp_desc)]
+_lib.ssg_infer_workspace_bytes.restype = c_size_t
+_lib.ssg_infer_prepare.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 7
+_lib.ssg_infer_fwd.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 5
+_lib.ssg_infer_view.argtypes = [POINTER(ssg_mlp_desc), c_void_p, c_void_p, POINTER(ssg_infer_view_t)]
 _lib.ssg_adam_state_bytes.argtypes = [c_int64]
 _lib.ssg_adam_state_bytes.restype = c_size_t
 _lib.ssg_adam_init.argtypes = [c_int64, c_void_p, c_void_p]
@@ -222,6 +234,29 @@ def ssg_profile_read(cap: int):
     if n < 0:
         raise SsgError(n, ssg_last_error())
     return list(ms[:n]), list(tags[:n])
+
+
+def ssg_infer_prepared_bytes(desc) -> int:
+    return int(_lib.ssg_infer_prepared_bytes(ctypes.byref(desc)))
+
+
+def ssg_infer_workspace_bytes(desc) -> int:
+    return int(_lib.ssg_infer_workspace_bytes(ctypes.byref(desc)))
+
+
+def ssg_infer_prepare(desc, W1, W2, W3, s, sinv, prepared, stream=None) -> None:
+    _check(_lib.ssg_infer_prepare(ctypes.byref(desc), _ptr(W1), _ptr(W2), _ptr(W3), _ptr(s), _ptr(sinv),
+                                  _ptr(prepared), _stream(stream)))
+
+
+def ssg_infer_fwd(desc, x, prepared, y, workspace, stream=None) -> None:
+    _check(_lib.ssg_infer_fwd(ctypes.byref(desc), _ptr(x), _ptr(prepared), _ptr(y), _ptr(workspace), _stream(stream)))
+
+
+def ssg_infer_view(desc, prepared, workspace) -> ssg_infer_view_t:
+    v = ssg_infer_view_t()
+    _check(_lib.ssg_infer_view(ctypes.byref(desc), _ptr(prepared), _ptr(workspace), ctypes.byref(v)))
+    return v
 
 
 def make_adam_desc(n, step, lr, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, grad_dtype=SSG_F32,

@@ -180,6 +180,141 @@ int ssg_profile_read(float *ms, int *tags, int cap) {
     return n;
 }
 
+// ---- inference with the factors folded into the weights ---------------------------
+namespace {
+// prepared: scalars (64 floats: [0] s1 [1] s2 [2] s3 [4] amax of s*w1 [5] amax_w2 [6] amax of s^-1*w3),
+// three slotted range accumulators, w3's per-channel ranges, then the three code matrices
+struct InferPrepared {
+    size_t scalars, slots, w3_camax, w1_q, w2_q, w3_q, total;
+};
+InferPrepared infer_prepared_layout(int64_t d, int64_t f) {
+    InferPrepared L;
+    size_t off = 0;
+    L.scalars = off; off += 256;
+    L.slots = off; off += 3 * ssg::kAmaxSlotWords * 4;
+    L.w3_camax = off; off = align256(off + (size_t)f * 4);
+    L.w1_q = off; off = align256(off + (size_t)f * d);
+    L.w2_q = off; off = align256(off + (size_t)f * d);
+    L.w3_q = off; off = align256(off + (size_t)f * d);
+    L.total = off;
+    return L;
+}
+// workspace: scalars ([0] sx [1] amax_x), one slotted range accumulator, x^ [T,d], h^ [T,f]
+struct InferWork {
+    size_t scalars, slots, x_q, h_q, total;
+};
+InferWork infer_work_layout(int64_t T, int64_t d, int64_t f) {
+    InferWork L;
+    size_t off = 0;
+    L.scalars = off; off += 256;
+    L.slots = off; off += ssg::kAmaxSlotWords * 4;
+    L.x_q = off; off = align256(off + (size_t)T * d);
+    L.h_q = off; off = align256(off + (size_t)T * f);
+    L.total = off;
+    return L;
+}
+ssg_status check_infer_desc(const ssg_mlp_desc *d, const char *who) {
+    ssg_status rc = check_desc(d, who);
+    if (rc != SSG_OK) return rc;
+    if (d->smooth != 1) return fail(SSG_ERR_UNSUPPORTED, "%s: the folded form is Smooth-SwiGLU (smooth = 1)", who);
+    if (d->scale_mode != SSG_SCALE_CURRENT) return fail(SSG_ERR_UNSUPPORTED, "%s: current scaling of x only", who);
+    return SSG_OK;
+}
+}  // namespace
+
+size_t ssg_infer_prepared_bytes(const ssg_mlp_desc *desc) {
+    if (check_infer_desc(desc, "ssg_infer_prepared_bytes") != SSG_OK) return 0;
+    return infer_prepared_layout(desc->d, desc->f).total;
+}
+size_t ssg_infer_workspace_bytes(const ssg_mlp_desc *desc) {
+    if (check_infer_desc(desc, "ssg_infer_workspace_bytes") != SSG_OK) return 0;
+    return infer_work_layout(desc->T, desc->d, desc->f).total;
+}
+
+ssg_status ssg_infer_prepare(const ssg_mlp_desc *desc, const void *W1, const void *W2, const void *W3, const float *s,
+                             const float *sinv, void *prepared, void *stream) {
+    ssg_status rc = check_infer_desc(desc, "ssg_infer_prepare");
+    if (rc != SSG_OK) return rc;
+    SSG_REQUIRE_PTR(W1); SSG_REQUIRE_PTR(W2); SSG_REQUIRE_PTR(W3); SSG_REQUIRE_PTR(s); SSG_REQUIRE_PTR(sinv);
+    SSG_REQUIRE_PTR(prepared);
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t dm = desc->d, f = desc->f;
+    const int pow2 = desc->rnd == SSG_ROUND_POW2;
+    const InferPrepared L = infer_prepared_layout(dm, f);
+    uint8_t *b = static_cast<uint8_t *>(prepared);
+    float *sc = reinterpret_cast<float *>(b + L.scalars);
+    uint32_t *slots = reinterpret_cast<uint32_t *>(b + L.slots);
+    float *w3_camax = reinterpret_cast<float *>(b + L.w3_camax);
+    ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(b), (L.w1_q - L.scalars) / 4, 0u, st);
+    // w1~ = Q(s_i * w1_i): the factor goes into row i of w1 (end of Section 4.4)
+    ssg::launch_rowscale_quantize(W1, s, f, dm, slots, pow2, sc + 0, sc + 4, b + L.w1_q, st);
+    // w2^ = Q(w2)
+    ssg::launch_amax(W2, ssg::SRC_BF16, (size_t)(f * dm), slots + ssg::kAmaxSlotWords, ssg::kAmaxSlots, st);
+    ssg::CastArgs c;
+    c.src = W2; c.kind = ssg::SRC_BF16; c.rows = f; c.cols = dm; c.fmt = ssg::kE4M3; c.pow2 = pow2;
+    c.amax = reinterpret_cast<float *>(slots + ssg::kAmaxSlotWords); c.amax_slots = ssg::kAmaxSlots;
+    c.amax_out = sc + 5; c.scale_out = sc + 1; c.dst = b + L.w2_q;
+    ssg::launch_cast(c, st);
+    // w3~ = Q(s_i^-1 * w3_i): column i of the stored [d,f] matrix
+    ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
+    ssg::launch_fold_range(w3_camax, sinv, f, reinterpret_cast<uint32_t *>(sc + 6), st);
+    ssg::CastArgs w;
+    w.src = W3; w.kind = ssg::SRC_BF16; w.rows = dm; w.cols = f; w.fmt = ssg::kE4M3; w.pow2 = pow2;
+    w.col_scale = sinv; w.amax = sc + 6; w.scale_out = sc + 2; w.dst = b + L.w3_q;
+    ssg::launch_cast(w, st);
+    return check_launch("ssg_infer_prepare");
+}
+
+ssg_status ssg_infer_fwd(const ssg_mlp_desc *desc, const void *x, const void *prepared, void *y, void *workspace,
+                         void *stream) {
+    ssg_status rc = check_infer_desc(desc, "ssg_infer_fwd");
+    if (rc != SSG_OK) return rc;
+    SSG_REQUIRE_PTR(x); SSG_REQUIRE_PTR(prepared); SSG_REQUIRE_PTR(y); SSG_REQUIRE_PTR(workspace);
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t T = desc->T, dm = desc->d, f = desc->f;
+    const InferPrepared P = infer_prepared_layout(dm, f);
+    const InferWork Wl = infer_work_layout(T, dm, f);
+    const uint8_t *pb = static_cast<const uint8_t *>(prepared);
+    const float *psc = reinterpret_cast<const float *>(pb + P.scalars);
+    uint8_t *wk = static_cast<uint8_t *>(workspace);
+    float *wsc = reinterpret_cast<float *>(wk + Wl.scalars);
+    uint32_t *slots = reinterpret_cast<uint32_t *>(wk + Wl.slots);
+    ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(wk), (Wl.x_q - Wl.scalars) / 4, 0u, st);
+    // x^ = Q(x)
+    ssg::launch_amax(x, ssg::SRC_BF16, (size_t)(T * dm), slots, ssg::kAmaxSlots, st);
+    ssg::CastArgs c;
+    c.src = x; c.kind = ssg::SRC_BF16; c.rows = T; c.cols = dm; c.fmt = ssg::kE4M3; c.pow2 = desc->rnd == SSG_ROUND_POW2;
+    c.amax = reinterpret_cast<float *>(slots); c.amax_slots = ssg::kAmaxSlots; c.amax_out = wsc + 1; c.scale_out = wsc + 0;
+    c.dst = wk + Wl.x_q;
+    ssg::launch_cast(c, st);
+    // both inner products, the SwiGLU product and its cast in one kernel: h^ = cast((s_i u_i) Swish(g_i))
+    ssg::GemmArgs g;
+    g.epilogue = ssg::EPI_SWIGLU_Q; g.a_fmt = ssg::kE4M3; g.M = T; g.N = f; g.K = dm;
+    g.A = wk + Wl.x_q; g.B = pb + P.w1_q; g.B2 = pb + P.w2_q; g.sa = wsc + 0; g.sb = psc + 0; g.sb2 = psc + 1;
+    g.C = wk + Wl.h_q;
+    ssg::launch_gemm(g, st);
+    // y = h^ w3~^T / sigma_w3
+    ssg::GemmArgs g2;
+    g2.epilogue = ssg::EPI_STORE; g2.a_fmt = ssg::kE4M3; g2.M = T; g2.N = dm; g2.K = f;
+    g2.A = wk + Wl.h_q; g2.B = pb + P.w3_q; g2.sb = psc + 2; g2.C = y; g2.c_f32 = desc->y_dtype == SSG_F32;
+    ssg::launch_gemm(g2, st);
+    return check_launch("ssg_infer_fwd");
+}
+
+ssg_status ssg_infer_view(const ssg_mlp_desc *desc, const void *prepared, const void *workspace, ssg_infer_view_t *out) {
+    ssg_status rc = check_infer_desc(desc, "ssg_infer_view");
+    if (rc != SSG_OK) return rc;
+    if (!out) return fail(SSG_ERR_ARG, "ssg_infer_view: out is NULL");
+    const InferPrepared P = infer_prepared_layout(desc->d, desc->f);
+    const InferWork Wl = infer_work_layout(desc->T, desc->d, desc->f);
+    const uint8_t *pb = static_cast<const uint8_t *>(prepared), *wb = static_cast<const uint8_t *>(workspace);
+    out->weight_scales = pb ? reinterpret_cast<const float *>(pb + P.scalars) : nullptr;
+    out->w1_q = pb ? pb + P.w1_q : nullptr; out->w2_q = pb ? pb + P.w2_q : nullptr; out->w3_q = pb ? pb + P.w3_q : nullptr;
+    out->x_scale = wb ? reinterpret_cast<const float *>(wb + Wl.scalars) : nullptr;
+    out->x_q = wb ? wb + Wl.x_q : nullptr; out->h_q = wb ? wb + Wl.h_q : nullptr;
+    return SSG_OK;
+}
+
 // ---- Adam with FP8 moments -----------------------------------------------------
 namespace {
 size_t adam_scalar_bytes() { return align256(ssg::adam_scalar_words() * sizeof(uint32_t)); }

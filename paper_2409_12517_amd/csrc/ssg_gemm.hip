@@ -546,6 +546,7 @@ constexpr int kThreads4 = 256;
 
 template <int EPI, int AFMT>
 __global__ void __launch_bounds__(kThreads4) gemm4_kernel(GemmParams p) {
+    constexpr bool kDual = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_Q;     // B tile = 128 rows of W1 + 128 rows of W2
     __shared__ __attribute__((aligned(1024))) uint8_t smem[kUnits * kUnitBytes];
 
     const int tid = threadIdx.x;
@@ -554,7 +555,7 @@ __global__ void __launch_bounds__(kThreads4) gemm4_kernel(GemmParams p) {
     int tile_m, tile_n;
     map_tile(p, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM;
-    const int64_t n0 = (int64_t)tile_n * (EPI == EPI_SWIGLU ? BN / 2 : BN);
+    const int64_t n0 = (int64_t)tile_n * (kDual ? BN / 2 : BN);
     SSG_STAMP(0);
 
     // DMA slots: a unit is 32 instructions of 8 rows x 128 B, 8 per wave (rows (8w+j)*8 + l/8)
@@ -570,12 +571,12 @@ __global__ void __launch_bounds__(kThreads4) gemm4_kernel(GemmParams p) {
         gm = gm < p.M ? gm : p.M - 1;
         a_lane[j] = (uint32_t)(gm * p.K) + ck;
         int64_t gn;
-        if (EPI == EPI_SWIGLU) gn = n0 + (row & 127);
+        if (kDual) gn = n0 + (row & 127);
         else gn = n0 + row;
         gn = gn < p.N ? gn : p.N - 1;
         b_lane[j] = (uint32_t)(gn * p.K) + ck;
     }
-    if (EPI == EPI_SWIGLU && w >= 2) b_src = p.B2;      // waves 2, 3 fill tile rows 128..255
+    if (kDual && w >= 2) b_src = p.B2;      // waves 2, 3 fill tile rows 128..255
     const uint32_t lds_w = (uint32_t)(w * 8) * 1024u;
 
     // LDS byte offset of this lane's two 16-byte chunks of a fragment row, per K half; the row block of a
@@ -587,9 +588,9 @@ __global__ void __launch_bounds__(kThreads4) gemm4_kernel(GemmParams p) {
         for (int e = 0; e < 2; ++e)
             frag_off[kh][e] = (uint32_t)((l & 31) * BK + (((kh * 4 + (l >> 5) * 2 + e) ^ swz(l & 31)) << 4));
     const uint32_t a_wave_base = (uint32_t)(wm * 128) * BK;
-    const uint32_t b_wave_base = (uint32_t)(EPI == EPI_SWIGLU ? wn * 64 : wn * 128) * BK;
+    const uint32_t b_wave_base = (uint32_t)(kDual ? wn * 64 : wn * 128) * BK;
     auto b_block_off = [](int nb) -> uint32_t {      // SWIGLU: blocks 0, 1 from the W1 rows, 2, 3 from the W2 rows
-        return (uint32_t)(EPI == EPI_SWIGLU ? (nb >> 1) * 128 + (nb & 1) * 32 : nb * 32) * BK;
+        return (uint32_t)(kDual ? (nb >> 1) * 128 + (nb & 1) * 32 : nb * 32) * BK;
     };
 
     v16f acc[4][4];
@@ -618,7 +619,7 @@ __global__ void __launch_bounds__(kThreads4) gemm4_kernel(GemmParams p) {
             for (int j = 0; j < 8; ++j) {
                 const int row = (w * 8 + j) * 8 + lrow;
                 const int ck = ((j & 1) ? chunk_odd : chunk_even) * 16;
-                int64_t g = (is_b ? n0 + ((EPI == EPI_SWIGLU) ? (row & 127) : row) : m0 + row);
+                int64_t g = (is_b ? n0 + (kDual ? (row & 127) : row) : m0 + row);
                 const int64_t lim = is_b ? p.N : p.M;
                 g = g < lim ? g : lim - 1;
                 const bool k_ok = kbase + ck < Kseg;
@@ -844,7 +845,7 @@ __global__ void __launch_bounds__(kThreads4) gemm4_kernel(GemmParams p) {
                 if (m) atomicMax(dst + (blockIdx.x % kAmaxSlots) * kAmaxSlotStride, m << 16);
             }
         }
-    } else {   // EPI_SWIGLU: slab columns 0..63 are u, 64..127 are g of the same 64 channels
+    } else {   // EPI_SWIGLU, EPI_SWIGLU_Q: slab columns 0..63 are u, 64..127 are g of the same 64 channels
         const int c8 = (l & 7) * 8;
         const int64_t col = n0 + wn * 64 + c8;
         const bool col_ok = col < p.N;
@@ -868,6 +869,16 @@ __global__ void __launch_bounds__(kThreads4) gemm4_kernel(GemmParams p) {
                     u[k] = __fmul_rn(u[k], alpha_u);
                     g[k] = __fmul_rn(g[k], alpha_g);
                 }
+                if (EPI == EPI_SWIGLU_Q) {
+                    // inference: the factor s_i is already inside u (folded into w1), so the product is cast as
+                    // it stands; nothing else is stored
+                    float h[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) h[k] = swiglu_f32(u[k], g[k]);
+                    *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(p.C) + at) =
+                        make_uint2(satcast_pk4<kE4M3>(h[0], h[1], h[2], h[3]), satcast_pk4<kE4M3>(h[4], h[5], h[6], h[7]));
+                    continue;
+                }
                 const uint4 qu = pack_bf16x8(u), qg = pack_bf16x8(g);
                 *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = qu;
                 *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C2) + at) = qg;
@@ -887,7 +898,7 @@ __global__ void __launch_bounds__(kThreads4) gemm4_kernel(GemmParams p) {
                 const uint32_t o = (uint32_t)__shfl_xor((int)hmax[k], off, 64);
                 hmax[k] = hmax[k] > o ? hmax[k] : o;
             }
-        if (l < 8 && col_ok) {
+        if (EPI == EPI_SWIGLU && l < 8 && col_ok) {
 #pragma unroll
             for (int k = 0; k < 8; ++k)
                 if (hmax[k]) atomicMax(&p.camax_bits[col + k], hmax[k]);
@@ -944,13 +955,17 @@ void launch_gemm(const GemmArgs &a, hipStream_t st) {
     p.tl_slot = tl_launch++ % kTlLaunches;
 #endif
     p.tiles_m = (int)((a.M + BM - 1) / BM);
-    const int n_per_tile = a.epilogue == EPI_SWIGLU ? BN / 2 : BN;
+    const int n_per_tile = (a.epilogue == EPI_SWIGLU || a.epilogue == EPI_SWIGLU_Q) ? BN / 2 : BN;
     p.tiles_n = (int)((a.N + n_per_tile - 1) / n_per_tile);
     const unsigned blocks = (unsigned)p.tiles_m * (unsigned)p.tiles_n;
     profile_before(2 * a.epilogue + a.a_fmt + (a.epilogue == EPI_STORE && a.A2 ? 8 : 0), st);
     switch (a.epilogue) {
         case EPI_STORE: launch_epi<EPI_STORE>(p, a.a_fmt, blocks, st); break;
         case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(p, a.a_fmt, blocks, st); break;
+        case EPI_SWIGLU_Q:      // 4-wave kernel only
+            if (a.a_fmt == kE4M3) hipLaunchKernelGGL((gemm4_kernel<EPI_SWIGLU_Q, kE4M3>), dim3(blocks), dim3(kThreads4), 0, st, p);
+            else hipLaunchKernelGGL((gemm4_kernel<EPI_SWIGLU_Q, kE5M2>), dim3(blocks), dim3(kThreads4), 0, st, p);
+            break;
         default: launch_epi<EPI_SWIGLU_BWD>(p, a.a_fmt, blocks, st); break;
     }
     profile_after(st);

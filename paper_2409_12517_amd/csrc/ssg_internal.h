@@ -60,11 +60,17 @@ void launch_fold_range(const float *w3_camax, const float *sinv, int64_t f, uint
 
 void launch_swiglu(const void *U, const void *G, int64_t n, float *h, hipStream_t st);
 
+// Q_E4M3 of a bf16 [rows, cols] matrix whose row i is first multiplied by row_scale[i]; `slots` are
+// kAmaxSlots zeroed slotted range words (scratch)
+void launch_rowscale_quantize(const void *w, const float *row_scale, int64_t rows, int64_t cols, uint32_t *slots,
+                              int pow2, float *scale_out, float *amax_out, uint8_t *dst, hipStream_t st);
+
 // ---- FP8 MFMA GEMM (ssg_gemm.hip) --------------------------------------------
 enum Epilogue {
     EPI_STORE = 0,        // C = acc * alpha [* col_scale[n]]
     EPI_SWIGLU = 1,       // dual B: U, G bf16 stores + per-channel max of |h|
-    EPI_SWIGLU_BWD = 2    // acc -> dH; loads U, G; stores dU, dG bf16 + their amax
+    EPI_SWIGLU_BWD = 2,   // acc -> dH; loads U, G; stores dU, dG bf16 + their amax
+    EPI_SWIGLU_Q = 3      // dual B as EPI_SWIGLU, but stores only the E4M3 cast of u * Swish(g) (C: bytes [M, N])
 };
 
 struct GemmArgs {

@@ -434,6 +434,56 @@ void launch_swiglu(const void *U, const void *G, int64_t n, float *h, hipStream_
                        LoadSwiglu{(const uint16_t *)U, (const uint16_t *)G}, n8, h);
 }
 
+// ------------------------------------------------------------------ per-row factor, then per-tensor Q
+// w1~ = Q(s_i * w1_i) of the inference form (end of Section 4.4): row i of a [rows, cols] bf16 matrix is
+// multiplied by rs[i] (one fp32 multiply), the result is quantized per tensor to E4M3.  Run once per
+// set of weights, so two plain elementwise passes: range, then cast.  cols is a multiple of 16, so
+// the 8 elements of a lane share a row.
+__global__ void __launch_bounds__(256)
+rowscale_amax_kernel(const uint16_t *__restrict__ w, const float *__restrict__ rs, int64_t rows, int64_t cols,
+                     uint32_t *__restrict__ slots) {
+    const size_t n = (size_t)rows * (size_t)cols, stride = (size_t)gridDim.x * 256 * 8;
+    uint32_t m = 0;
+    for (size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8; i < n; i += stride) {
+        float v[8];
+        LoadBf16{w}.load8(i, v);
+        const float f = rs[i / (size_t)cols];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const uint32_t b = abs_bits_ignore_nan(__fmul_rn(v[k], f));
+            m = m > b ? m : b;
+        }
+    }
+    m = wave_max_u32(m);
+    if ((threadIdx.x & 63) == 0 && m) atomicMax(slots + (blockIdx.x % kAmaxSlots) * kAmaxSlotStride, m);
+}
+__global__ void __launch_bounds__(256)
+rowscale_cast_kernel(const uint16_t *__restrict__ w, const float *__restrict__ rs, int64_t rows, int64_t cols,
+                     const uint32_t *__restrict__ slots, int pow2, float *__restrict__ scale_out,
+                     float *__restrict__ amax_out, uint8_t *__restrict__ dst) {
+    const float amax = __uint_as_float(wave_max_u32(slots[(threadIdx.x & 63) * kAmaxSlotStride]));
+    const float sigma = scale_from_amax(amax, Fp8Traits<kE4M3>::fmax, pow2);
+    if (blockIdx.x == 0 && threadIdx.x == 0) { *scale_out = sigma; if (amax_out) *amax_out = amax; }
+    const size_t n = (size_t)rows * (size_t)cols, stride = (size_t)gridDim.x * 256 * 8;
+    for (size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8; i < n; i += stride) {
+        float v[8];
+        LoadBf16{w}.load8(i, v);
+        const float f = rs[i / (size_t)cols];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = __fmul_rn(__fmul_rn(v[k], f), sigma);
+        *reinterpret_cast<uint2 *>(dst + i) = make_uint2(satcast_pk4<kE4M3>(v[0], v[1], v[2], v[3]),
+                                                         satcast_pk4<kE4M3>(v[4], v[5], v[6], v[7]));
+    }
+}
+void launch_rowscale_quantize(const void *w, const float *row_scale, int64_t rows, int64_t cols, uint32_t *slots,
+                              int pow2, float *scale_out, float *amax_out, uint8_t *dst, hipStream_t st) {
+    const size_t groups = ((size_t)rows * (size_t)cols / 8 + 255) / 256;
+    const unsigned blocks = (unsigned)(groups < 4096 ? groups : 4096);
+    hipLaunchKernelGGL(rowscale_amax_kernel, dim3(blocks), dim3(256), 0, st, (const uint16_t *)w, row_scale, rows, cols, slots);
+    hipLaunchKernelGGL(rowscale_cast_kernel, dim3(blocks), dim3(256), 0, st, (const uint16_t *)w, row_scale, rows, cols,
+                       slots, pow2, scale_out, amax_out, dst);
+}
+
 // ------------------------------------------------------------------ delayed scaling state
 __global__ void __launch_bounds__(256) scaling_init_kernel(uint32_t *state, size_t words) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
