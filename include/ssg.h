@@ -264,6 +264,9 @@ ssg_status ssg_adam_view_state(int64_t n, int32_t step, const void *state, ssg_a
  *                          The two passes of ssg_adam_step are recorded too: tag 32 = range pass,
  *                          33 = update pass. */
 ssg_status ssg_profile_enable(int max_records);
+/* record only launches with this tag (so that the brackets do not perturb the other kernels of a timed
+ * region); tag < 0 = every launch (the default).  Survives ssg_profile_enable. */
+ssg_status ssg_profile_select(int tag);
 int ssg_profile_read(float *ms, int *tags, int cap);
 
 /* ---- matrix-core ceiling probe (optional diagnostic) ---------------------------

@@ -36,7 +36,7 @@ EXPORTS = [
     "ssg_mlp_scaling_state_bytes", "ssg_mlp_scaling_init",
     "ssg_infer_prepared_bytes", "ssg_infer_workspace_bytes", "ssg_infer_prepare", "ssg_infer_fwd", "ssg_infer_view",
     "ssg_adam_state_bytes", "ssg_adam_init", "ssg_adam_step", "ssg_adam_view_state",
-    "ssg_profile_enable", "ssg_profile_read", "ssg_probe_mfma_rate",
+    "ssg_profile_enable", "ssg_profile_select", "ssg_profile_read", "ssg_probe_mfma_rate",
 ]
 
 
@@ -91,6 +91,7 @@ _lib.ssg_mlp_bwd.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 8
 _lib.ssg_mlp_view_saved.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_saved_view)]
 _lib.ssg_mlp_view_workspace.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_workspace_view)]
 _lib.ssg_profile_enable.argtypes = [c_int]
+_lib.ssg_profile_select.argtypes = [c_int]
 _lib.ssg_profile_read.argtypes = [POINTER(c_float), POINTER(c_int), c_int]
 _lib.ssg_mlp_scaling_state_bytes.argtypes = []
 _lib.ssg_mlp_scaling_state_bytes.restype = c_size_t
@@ -224,6 +225,10 @@ def ssg_mlp_scaling_init(state, stream=None) -> None:
 
 def ssg_profile_enable(max_records: int) -> None:
     _check(_lib.ssg_profile_enable(max_records))
+
+
+def ssg_profile_select(tag: int) -> None:
+    _check(_lib.ssg_profile_select(tag))
 
 
 def ssg_profile_read(cap: int):

@@ -128,6 +128,7 @@ struct ProfileState {
     std::vector<hipEvent_t> start, stop;
     std::vector<int> tag;
     int used = 0;
+    int only_tag = -1;       // -1: record every launch; otherwise only launches with this tag
     bool open = false;       // a start event was recorded and waits for its stop
 };
 ProfileState g_prof;
@@ -137,6 +138,7 @@ ProfileState g_prof;
 namespace ssg {
 void profile_before(int tag, hipStream_t st) {
     g_prof.open = false;
+    if (g_prof.only_tag >= 0 && tag != g_prof.only_tag) return;
     if (g_prof.used >= (int)g_prof.start.size()) return;
     if (hipEventRecord(g_prof.start[g_prof.used], st) != hipSuccess) return;
     g_prof.tag[g_prof.used] = tag;
@@ -151,11 +153,18 @@ void profile_after(hipStream_t st) {
 
 extern "C" {
 
+ssg_status ssg_profile_select(int tag) {
+    g_prof.only_tag = tag < 0 ? -1 : tag;
+    return SSG_OK;
+}
+
 ssg_status ssg_profile_enable(int max_records) {
     if (max_records < 0 || max_records > (1 << 20)) return fail(SSG_ERR_ARG, "ssg_profile_enable: bad max_records");
+    const int keep_tag = g_prof.only_tag;
     for (hipEvent_t e : g_prof.start) (void)hipEventDestroy(e);
     for (hipEvent_t e : g_prof.stop) (void)hipEventDestroy(e);
     g_prof = ProfileState();
+    g_prof.only_tag = keep_tag;
     for (int i = 0; i < max_records; ++i) {
         hipEvent_t a, b;
         if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess)

@@ -227,3 +227,30 @@ def test_cached_weights_give_the_same_bytes():
                ("U", (T, f), torch.bfloat16), ("G", (T, f), torch.bfloat16)]
     for name, shape, dt in regions:
         assert torch.equal(blk.sv(name, shape, dt).view(torch.uint8), ref.sv(name, shape, dt).view(torch.uint8)), name
+
+
+def test_graph_capture_replays_match_eager():
+    """The whole step is capturable (kernel launches only, no memset nodes, nothing allocated): three replays,
+    with eager work and synchronisations in between, give the bytes of the eager call every time."""
+    inp = synth.make_inputs(528, 256, 688, seed=61)
+    blk = Block(inp)
+    blk.fwd(); blk.bwd()
+    want = [t.clone() for t in (blk.y, blk.dx, blk.dW1, blk.dW2, blk.dW3)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                     # warm-up on the side stream, as capture requires
+        ssg.ssg_mlp_fwd(blk.desc, blk.x, blk.W1, blk.W2, blk.W3, blk.y, blk.saved)
+        ssg.ssg_mlp_bwd(blk.desc, blk.dY, blk.saved, blk.dx, blk.dW1, blk.dW2, blk.dW3, blk.work)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ssg.ssg_mlp_fwd(blk.desc, blk.x, blk.W1, blk.W2, blk.W3, blk.y, blk.saved)
+        ssg.ssg_mlp_bwd(blk.desc, blk.dY, blk.saved, blk.dx, blk.dW1, blk.dW2, blk.dW3, blk.work)
+    for _ in range(3):
+        for t in (blk.y, blk.dx, blk.dW1, blk.dW2, blk.dW3):
+            t.zero_()                                  # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(want, (blk.y, blk.dx, blk.dW1, blk.dW2, blk.dW3)):
+            assert torch.equal(a, b)
