@@ -38,7 +38,7 @@ TAG_ROLES = {0: "y = h^ w3~^T", 1: "dW3, dW1, dW2", 2: "U, G + SwiGLU + channel 
 # rocprofv3 --pmc runs of this command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
 # reads for a 1 GiB copy (factors 2.000 and 1.000); see profiles/bench_7b_hbm_traffic.txt.  Algorithmic
 # bytes of that launch: 61.9 MB of FP8 operands read + 180.4 MB of fp32 written.
-MEASURED_TRAFFIC_BYTES = {"gemm4_kernel<0, 1>": 329.2e6 + 191.6e6}
+MEASURED_TRAFFIC_BYTES = {"gemm4_kernel<0, 1>": 329.1e6 + 191.6e6}
 
 
 def gemm_flops_by_tag(T, d, f):
@@ -80,6 +80,10 @@ ADAM_KERNELS = {32: "adam_range_kernel<false, 2>", 33: "adam_update_kernel<false
 # algorithmic bytes per element: range pass reads g (4) + two codes; update pass reads g, two codes and w (4),
 # writes w (4), the bf16 copy (2) and two codes
 ADAM_BYTES = {32: 6.0, 33: 18.0}
+# L2<->memory bytes per launch of the update pass at 45.1 M elements, from the same two rocprofv3 --pmc runs as
+# MEASURED_TRAFFIC_BYTES below (profiles/bench_7b_hbm_traffic.txt): 452.2 MB fetched + 375.3 MB written, against
+# 811.6 MB algorithmic
+ADAM_MEASURED_TRAFFIC_BYTES = {45088768: 452.2e6 + 375.3e6}
 
 
 def bench_adam(ssg, torch, grads, weights, steps, warmup, stream, cpu_sample=1 << 22, with_cpu=True):
@@ -124,7 +128,7 @@ def bench_adam(ssg, torch, grads, weights, steps, warmup, stream, cpu_sample=1 <
            "value": (ADAM_BYTES[32] + ADAM_BYTES[33]) * n_total / (dt / steps) / 1e9,
            "ms_per_step": dt * 1e3 / steps, "elements": n_total, "steps": steps, "dtype": "f32 (moments e4m3 / e5m2)",
            "roofline": {"bound": "hbm", "kernel": ADAM_KERNELS[dom], "achieved": achieved, "peak": PEAK_HBM_GBS,
-                        "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                        "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS, "traffic": ADAM_MEASURED_TRAFFIC_BYTES.get(n_one),
                         "avg_launch_ms": avg[dom], "bytes_per_launch": ADAM_BYTES[dom] * n_one,
                         "kernels": {ADAM_KERNELS[tg]: {"avg_ms": avg[tg], "gbs": ADAM_BYTES[tg] * n_one / (avg[tg] * 1e-3) / 1e9}
                                     for tg in (32, 33)}}}
