@@ -7,6 +7,8 @@
 // per column on the float's bit pattern (|x| orders like an unsigned integer).
 #include <type_traits>
 
+typedef short ssg_i16x2 __attribute__((ext_vector_type(2)));
+
 #include "ssg_device.h"
 #include "ssg_internal.h"
 
@@ -43,6 +45,15 @@ void launch_reset(uint32_t *scalars, uint32_t mask, uint32_t *v1, size_t n1, uin
 // Each loader returns 8 consecutive elements of one row as fp32.
 struct LoadBf16 {
     const uint16_t *p;
+    __device__ __forceinline__ uint4 load8_raw(size_t off) const { return *reinterpret_cast<const uint4 *>(p + off); }
+    static __device__ __forceinline__ void widen(const uint4 q, float (&v)[8]) {
+        uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
     __device__ __forceinline__ void load8(size_t off, float (&v)[8]) const {
         uint4 q = *reinterpret_cast<const uint4 *>(p + off);
         uint32_t w[4] = {q.x, q.y, q.z, q.w};
@@ -192,31 +203,46 @@ cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col
         cs[4] = b.x; cs[5] = b.y; cs[6] = b.z; cs[7] = b.w;
     }
 
-    uint32_t seen = 0;                                 // RECORD: largest |source value| this lane met
+    ssg_i16x2 seen2 = {0x7f, 0x7f};                     // RECORD: largest (|bf16 pattern| + 0x7f) this lane met, per half
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         const int lr = half * 64 + r4 * 4;             // local row of the 4-row group
         uint32_t lo[4] = {0, 0, 0, 0}, hi[4] = {0, 0, 0, 0};
         if (col_ok && row0 + lr < rows) {              // rows is a multiple of 16: the group is all in or all out
+            // the four row loads of the group first: four requests in flight per lane (measured: one at a time is
+            // 5-10 % slower, all eight of the lane at once is slower again)
+            float v[4][8];
+            if constexpr (RECORD) {
+                // bf16 source: the range is taken on the raw 16-bit patterns, two per operation.  |x| + 0x7f is
+                // below 0x8000 for every number and infinity and at or above it for NaN, so a signed 16-bit
+                // maximum ignores NaN, as the range pass does.
+                uint4 raw[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) raw[r] = ld.load8_raw((size_t)(row0 + lr + r) * (size_t)cols + (size_t)col);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t w4[4] = {raw[r].x, raw[r].y, raw[r].z, raw[r].w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const ssg_i16x2 b = __builtin_bit_cast(ssg_i16x2, (w4[i] & 0x7fff7fffu) + 0x007f007fu);
+                        seen2 = __builtin_elementwise_max(seen2, b);
+                    }
+                    LoadBf16::widen(raw[r], v[r]);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) ld.load8((size_t)(row0 + lr + r) * (size_t)cols + (size_t)col, v[r]);
+            }
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const size_t off = (size_t)(row0 + lr + r) * (size_t)cols + (size_t)col;
-                float v[8];
-                ld.load8(off, v);
-                if (RECORD) {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const uint32_t ab = abs_bits_ignore_nan(v[i]);
-                        seen = seen > ab ? seen : ab;
-                    }
-                }
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    if (COLSCALE) v[i] = __fmul_rn(v[i], cs[i]);
-                    if (tensor_scale) v[i] = __fmul_rn(v[i], sigma);
+                    if (COLSCALE) v[r][i] = __fmul_rn(v[r][i], cs[i]);
+                    if (tensor_scale) v[r][i] = __fmul_rn(v[r][i], sigma);
                 }
-                lo[r] = satcast_pk4<FMT>(v[0], v[1], v[2], v[3]);
-                hi[r] = satcast_pk4<FMT>(v[4], v[5], v[6], v[7]);
+                lo[r] = satcast_pk4<FMT>(v[r][0], v[r][1], v[r][2], v[r][3]);
+                hi[r] = satcast_pk4<FMT>(v[r][4], v[r][5], v[r][6], v[r][7]);
                 *reinterpret_cast<uint2 *>(dst + off) = make_uint2(lo[r], hi[r]);
             }
         }
@@ -231,10 +257,21 @@ cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col
         }
     }
     if (RECORD) {
-        // the range this pass saw, for the history of delayed scaling: one atomic per wave
+        // the range this pass saw, for the history of delayed scaling: one atomic per workgroup (atomics on
+        // one address from many workgroups serialise, and across XCDs they are slow: one per wave cost 20 us
+        // on a 45 M element tensor)
+        __shared__ uint32_t wave_seen[4];
+        const uint32_t lo16 = (uint32_t)(uint16_t)seen2[0] - 0x7fu, hi16 = (uint32_t)(uint16_t)seen2[1] - 0x7fu;
+        uint32_t seen = (lo16 > hi16 ? lo16 : hi16) << 16;          // bf16 pattern -> fp32 pattern of the same number
         seen = wave_max_u32(seen);
-        if ((threadIdx.x & 63) == 0 && seen)
-            atomicMax(record + ((blockIdx.y * gridDim.x + blockIdx.x) % kAmaxSlots) * kAmaxSlotStride, seen);
+        if ((threadIdx.x & 63) == 0) wave_seen[threadIdx.x >> 6] = seen;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t m = wave_seen[0];
+#pragma unroll
+            for (int k = 1; k < 4; ++k) m = m > wave_seen[k] ? m : wave_seen[k];
+            if (m) atomicMax(record + ((blockIdx.y * gridDim.x + blockIdx.x) % kAmaxSlots) * kAmaxSlotStride, m);
+        }
     }
     if (TRANSPOSED) {
         __syncthreads();
@@ -292,28 +329,30 @@ void launch_cast(const CastArgs &a, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------ per-column amax
-// Grid (cols/128, rows/512).  A thread keeps 8 running column maxima over its
-// share of the slab's rows; the 16 row groups of a workgroup meet in LDS and
+// Grid (cols/512, rows/128).  A wave reads 1 KB of a row per load; a lane keeps 8 running column
+// maxima over its wave's share of the slab's rows; the four waves of a workgroup meet in LDS and
 // one atomic per column goes to memory.
-constexpr int kSlabRows = 512;
+constexpr int kSlabRows = 128;
+constexpr int kColTile = 512;     // one wave reads 1 KB of a row per load: 64 lanes x 8 bf16
 
 template <class Loader>
 __global__ void __launch_bounds__(256)
 col_amax_kernel(Loader ld, int64_t rows, int64_t cols, uint32_t *__restrict__ camax_bits) {
-    __shared__ uint32_t cmax[kTile];
-    if (threadIdx.x < kTile) cmax[threadIdx.x] = 0;
+    __shared__ uint32_t cmax[kColTile];
+    cmax[threadIdx.x] = 0;
+    cmax[threadIdx.x + 256] = 0;
     __syncthreads();
-    const int c8 = threadIdx.x & 15, rg = threadIdx.x >> 4;
-    const int64_t col = (int64_t)blockIdx.x * kTile + c8 * 8;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t col = (int64_t)blockIdx.x * kColTile + lane * 8;
     const int64_t row0 = (int64_t)blockIdx.y * kSlabRows;
     const int64_t row1 = row0 + kSlabRows < rows ? row0 + kSlabRows : rows;
     if (col < cols) {
         uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        for (int64_t r = row0 + rg; r < row1; r += 64) {       // four independent row loads in flight
+        for (int64_t r = row0 + w; r < row1; r += 16) {        // four independent row loads in flight per lane
             float v[4][8];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int64_t rr = r + 16 * u;
+                const int64_t rr = r + 4 * u;
                 if (rr < row1) ld.load8((size_t)rr * (size_t)cols + (size_t)col, v[u]);
                 else {
 #pragma unroll
@@ -330,19 +369,21 @@ col_amax_kernel(Loader ld, int64_t rows, int64_t cols, uint32_t *__restrict__ ca
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            if (m[i]) atomicMax(&cmax[c8 * 8 + i], m[i]);
+            if (m[i]) atomicMax(&cmax[lane * 8 + i], m[i]);
     }
     __syncthreads();
-    if (threadIdx.x < kTile) {
-        const int64_t c = (int64_t)blockIdx.x * kTile + threadIdx.x;
-        if (c < cols && cmax[threadIdx.x]) atomicMax(&camax_bits[c], cmax[threadIdx.x]);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int t = threadIdx.x + 256 * h;
+        const int64_t c = (int64_t)blockIdx.x * kColTile + t;
+        if (c < cols && cmax[t]) atomicMax(&camax_bits[c], cmax[t]);
     }
 }
 
 void launch_col_amax(const void *src, const void *src2, SrcKind kind, int64_t rows, int64_t cols,
                      uint32_t *camax_bits, hipStream_t st) {
     if (rows == 0 || cols == 0) return;
-    dim3 grid((unsigned)((cols + kTile - 1) / kTile), (unsigned)((rows + kSlabRows - 1) / kSlabRows));
+    dim3 grid((unsigned)((cols + kColTile - 1) / kColTile), (unsigned)((rows + kSlabRows - 1) / kSlabRows));
     switch (kind) {
         case SRC_BF16:
             hipLaunchKernelGGL(col_amax_kernel<LoadBf16>, grid, dim3(256), 0, st, LoadBf16{(const uint16_t *)src},
