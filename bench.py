@@ -27,18 +27,18 @@ if ROOT not in sys.path:
 
 PEAK_FP8_TFLOPS = 5000.0          # MI355X dense FP8 MFMA peak (published: 5.0 PFLOP/s)
 METRIC = "FP8 Smooth-SwiGLU MLP fwd+bwd TFLOP/s (7B shape), % of FP8 MFMA peak"
-# tag of ssg_profile_read -> kernel symbol as rocprofv3 prints it (template args: epilogue, A format[, two products]);
-# single-product GEMMs run the 4-wave kernel, the two-product one the 8-wave kernel
-TAG_NAMES = {0: "gemm4_kernel<0, 0>", 1: "gemm4_kernel<0, 1>", 2: "gemm4_kernel<1, 0>",
-             5: "gemm4_kernel<2, 1>", 9: "gemm_kernel<0, 1, true>"}
+# tag of ssg_profile_read -> kernel symbol as rocprofv3 prints it (template args: epilogue, A format, addend);
+# the two-product input gradient is two launches (the second adds the first's fp32 result), timed as one record
+TAG_NAMES = {0: "gemm_kernel<0, 0, false>", 1: "gemm_kernel<0, 1, false>", 2: "gemm_kernel<1, 0, false>",
+             5: "gemm_kernel<2, 1, false>", 9: "gemm_kernel<0, 1, false> + gemm_kernel<0, 1, true>"}
 TAG_ROLES = {0: "y = h^ w3~^T", 1: "dW3, dW1, dW2", 2: "U, G + SwiGLU + channel maxima", 5: "dH + SwiGLU backward",
-             9: "dX (two products)"}
+             9: "dX (two products, two launches)"}
 
-# L2<->memory bytes per launch of the dominant kernel (gemm4_kernel<0, 1>: dW3, dW1, dW2) from two
+# L2<->memory bytes per launch of the dominant kernel (gemm_kernel<0, 1, false>: dW3, dW1, dW2) from two
 # rocprofv3 --pmc runs of this command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
 # reads for a 1 GiB copy (factors 2.000 and 1.000); see profiles/bench_7b_hbm_traffic.txt.  Algorithmic
 # bytes of that launch: 61.9 MB of FP8 operands read + 180.4 MB of fp32 written.
-MEASURED_TRAFFIC_BYTES = {"gemm4_kernel<0, 1>": 329.1e6 + 191.6e6}
+MEASURED_TRAFFIC_BYTES = {"gemm_kernel<0, 1, false>": 329.1e6 + 191.6e6}
 
 
 def gemm_flops_by_tag(T, d, f):
@@ -49,7 +49,7 @@ def gemm_flops_by_tag(T, d, f):
         2: (2 * one, 1),      # U and G in one launch
         5: (one, 1),          # dH
         1: (3 * one, 3),      # dW3, dW1, dW2
-        9: (2 * one, 1),      # dX: two products in one launch
+        9: (2 * one, 1),      # dX: two products, two launches under one timing record
     }
 
 

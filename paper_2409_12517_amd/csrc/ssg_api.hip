@@ -84,7 +84,7 @@ SavedLayout saved_layout(const ssg_mlp_desc &d) {
     return L;
 }
 
-struct WorkLayout { size_t scalars, partials, dy_q, dy_qT, dU, dG, du_q, du_qT, dg_q, dg_qT, total; };
+struct WorkLayout { size_t scalars, partials, dy_q, dy_qT, dU, dG, du_q, du_qT, dg_q, dg_qT, dx_tmp, total; };
 enum { W_SDY = 0, W_SDU, W_SDG, W_AMAX_DY, W_AMAX_DU, W_AMAX_DG, W_COUNT = 64 };
 
 WorkLayout work_layout(const ssg_mlp_desc &d) {
@@ -97,6 +97,7 @@ WorkLayout work_layout(const ssg_mlp_desc &d) {
     L.dy_q = take(T * dm); L.dy_qT = take(T * dm);
     L.dU = take(T * f * 2); L.dG = take(T * f * 2);
     L.du_q = take(T * f); L.du_qT = take(T * f); L.dg_q = take(T * f); L.dg_qT = take(T * f);
+    L.dx_tmp = take(T * dm * 4);                        // fp32 first product of the input gradient
     L.total = o;
     return L;
 }
@@ -301,12 +302,12 @@ ssg_status ssg_infer_fwd(const ssg_mlp_desc *desc, const void *x, const void *pr
     g.epilogue = ssg::EPI_SWIGLU_Q; g.a_fmt = ssg::kE4M3; g.M = T; g.N = f; g.K = dm;
     g.A = wk + Wl.x_q; g.B = pb + P.w1_q; g.B2 = pb + P.w2_q; g.sa = wsc + 0; g.sb = psc + 0; g.sb2 = psc + 1;
     g.C = wk + Wl.h_q;
-    ssg::launch_gemm(g, st);
+    if (!ssg::launch_gemm(g, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
     // y = h^ w3~^T / sigma_w3
     ssg::GemmArgs g2;
     g2.epilogue = ssg::EPI_STORE; g2.a_fmt = ssg::kE4M3; g2.M = T; g2.N = dm; g2.K = f;
     g2.A = wk + Wl.h_q; g2.B = pb + P.w3_q; g2.sb = psc + 2; g2.C = y; g2.c_f32 = desc->y_dtype == SSG_F32;
-    ssg::launch_gemm(g2, st);
+    if (!ssg::launch_gemm(g2, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
     return check_launch("ssg_infer_fwd");
 }
 
@@ -467,7 +468,7 @@ ssg_status ssg_gemm_fp8(const uint8_t *A, ssg_fp8_format a_fmt, const uint8_t *B
     ssg::GemmArgs g;
     g.epilogue = ssg::EPI_STORE; g.a_fmt = a_fmt; g.M = M; g.N = N; g.K = K; g.A = A; g.B = B;
     g.sa = sa_dev; g.sb = sb_dev; g.C = C; g.c_f32 = c_dtype == SSG_F32;
-    ssg::launch_gemm(g, (hipStream_t)stream);
+    if (!ssg::launch_gemm(g, (hipStream_t)stream)) return fail(SSG_ERR_ARG, "ssg_gemm_fp8: internal GEMM arguments");
     return check_launch("ssg_gemm_fp8");
 }
 
@@ -632,7 +633,7 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     g.A = b + L.x_q; g.B = b + L.w1_q; g.B2 = b + L.w2_q;
     g.sa = sc + S_SX; g.sb = sc + S_SW1; g.sb2 = sc + S_SW2;
     g.C = b + L.U; g.C2 = b + L.G; g.camax_bits = reinterpret_cast<uint32_t *>(h_camax);
-    ssg::launch_gemm(g, st);
+    if (!ssg::launch_gemm(g, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
 
     // a5: factors s_i, s_i^-1 and the range of s^-1 * w3 (from the per-channel range of w3)
     ssg::launch_channel_factors(h_camax, w3_camax, f, desc->smooth, s, sinv, scb + S_AMAX_W3S, scb + S_HMAX, st);
@@ -656,7 +657,7 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     g2.A = b + L.h_q; g2.B = b + L.w3_q;
     g2.sa = desc->smooth ? nullptr : s; g2.sb = sc + S_SW3;
     g2.C = y; g2.c_f32 = desc->y_dtype == SSG_F32;
-    ssg::launch_gemm(g2, st);
+    if (!ssg::launch_gemm(g2, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
 
     if (state) {
         // enter this call's ranges into the history; the scales written here serve the next call
@@ -721,7 +722,7 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     // plain block: dH = acc / (sdy sw3), no channel factor
     g.col_scale = desc->smooth ? s : nullptr;
     g.U = sv + L.U; g.G = sv + L.G; g.C = wk + Wl.dU; g.C2 = wk + Wl.dG; g.amax_bits = part_du; g.amax_bits2 = part_dg;
-    ssg::launch_gemm(g, st);
+    if (!ssg::launch_gemm(g, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
 
     // a11: two tensors, two E5M2 scales (their ranges came out of the epilogue above either way)
     c.kind = ssg::SRC_BF16; c.rows = T; c.cols = f;
@@ -747,23 +748,23 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     g3.epilogue = ssg::EPI_STORE; g3.a_fmt = ssg::kE5M2; g3.M = dm; g3.N = f; g3.K = T;
     g3.A = wk + Wl.dy_qT; g3.B = sv + L.h_qT; g3.sa = wsc + W_SDY; g3.sb = desc->smooth ? nullptr : s;
     g3.col_scale = desc->smooth ? sinv : nullptr; g3.C = dW3; g3.c_f32 = dw_f32;
-    ssg::launch_gemm(g3, st);
+    if (!ssg::launch_gemm(g3, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
 
     // a13: dX = dU^ w1^ / (sdu sw1) + dG^ w2^ / (sdg sw2): two K segments, one accumulator
     ssg::GemmArgs g4;
     g4.epilogue = ssg::EPI_STORE; g4.a_fmt = ssg::kE5M2; g4.M = T; g4.N = dm; g4.K = f; g4.K2 = f;
     g4.A = wk + Wl.du_q; g4.B = sv + L.w1_qT; g4.sa = wsc + W_SDU; g4.sb = sc + S_SW1;
     g4.A2 = wk + Wl.dg_q; g4.B2 = sv + L.w2_qT; g4.sa2 = wsc + W_SDG; g4.sb2 = sc + S_SW2;
-    g4.C = dx; g4.c_f32 = desc->y_dtype == SSG_F32;
-    ssg::launch_gemm(g4, st);
+    g4.C = dx; g4.c_f32 = desc->y_dtype == SSG_F32; g4.tmp = reinterpret_cast<float *>(wk + Wl.dx_tmp);
+    if (!ssg::launch_gemm(g4, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
 
     // a14: dW1 = dU^T x^ / (sdu sx), dW2 = dG^T x^ / (sdg sx)
     ssg::GemmArgs g5;
     g5.epilogue = ssg::EPI_STORE; g5.a_fmt = ssg::kE5M2; g5.M = f; g5.N = dm; g5.K = T;
     g5.A = wk + Wl.du_qT; g5.B = sv + L.x_qT; g5.sa = wsc + W_SDU; g5.sb = sc + S_SX; g5.C = dW1; g5.c_f32 = dw_f32;
-    ssg::launch_gemm(g5, st);
+    if (!ssg::launch_gemm(g5, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
     g5.A = wk + Wl.dg_qT; g5.sa = wsc + W_SDG; g5.C = dW2;
-    ssg::launch_gemm(g5, st);
+    if (!ssg::launch_gemm(g5, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
     return check_launch("ssg_mlp_bwd");
 }
 

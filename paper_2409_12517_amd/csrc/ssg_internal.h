@@ -79,10 +79,11 @@ struct GemmArgs {
     int64_t M = 0, N = 0, K = 0;
     const uint8_t *A = nullptr;         // [M, K]
     const uint8_t *B = nullptr;         // [N, K]
-    // second K segment (EPI_STORE only): acc = acc1 * (alpha1/alpha2) + sum A2*B2
+    // second product (EPI_STORE only): C = A B^T / (sa sb) + A2 B2^T / (sa2 sb2), run as two launches through `tmp`
     const uint8_t *A2 = nullptr;        // [M, K2]
     const uint8_t *B2 = nullptr;        // [N, K2]   (EPI_SWIGLU: the second weight matrix, same K)
     int64_t K2 = 0;
+    float *tmp = nullptr;               // optional fp32 [M, N] scratch: lets a sum of two products run as two launches
     // dequantization: alpha = 1 / (sa * sb); null pointer = 1
     const float *sa = nullptr, *sb = nullptr, *sa2 = nullptr, *sb2 = nullptr;
     const float *col_scale = nullptr;   // optional [N] factor (EPI_STORE, EPI_SWIGLU_BWD)
@@ -94,7 +95,8 @@ struct GemmArgs {
     uint32_t *amax_bits = nullptr;      // EPI_SWIGLU_BWD: running max |dU| (float bits), kAmaxSlots slots
     uint32_t *amax_bits2 = nullptr;     //                 same for |dG|
 };
-void launch_gemm(const GemmArgs &a, hipStream_t st);
+// false (nothing launched): a sum of two products was asked for without the fp32 scratch or with a fused epilogue
+bool launch_gemm(const GemmArgs &a, hipStream_t st);
 
 // Benchmark hook: called by launch_gemm before and after the kernel launch (no-ops unless enabled).
 void profile_before(int tag, hipStream_t st);
