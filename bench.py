@@ -27,18 +27,18 @@ if ROOT not in sys.path:
 
 PEAK_FP8_TFLOPS = 5000.0          # MI355X dense FP8 MFMA peak (published: 5.0 PFLOP/s)
 METRIC = "FP8 Smooth-SwiGLU MLP fwd+bwd TFLOP/s (7B shape), % of FP8 MFMA peak"
-# tag of ssg_profile_read -> kernel symbol as rocprofv3 prints it (template args: epilogue, A format, addend);
+# tag of ssg_profile_read -> kernel symbol as rocprofv3 prints it (template args: epilogue, A format, part of a two-launch sum);
 # the two-product input gradient is two launches (the second adds the first's fp32 result), timed as one record
-TAG_NAMES = {0: "gemm_kernel<0, 0, false>", 1: "gemm_kernel<0, 1, false>", 2: "gemm_kernel<1, 0, false>",
-             5: "gemm_kernel<2, 1, false>", 9: "gemm_kernel<0, 1, false> + gemm_kernel<0, 1, true>"}
+TAG_NAMES = {0: "gemm_kernel<0, 0, 0>", 1: "gemm_kernel<0, 1, 0>", 2: "gemm_kernel<1, 0, 0>",
+             5: "gemm_kernel<2, 1, 0>", 9: "gemm_kernel<0, 1, 1> + gemm_kernel<0, 1, 2>"}
 TAG_ROLES = {0: "y = h^ w3~^T", 1: "dW3, dW1, dW2", 2: "U, G + SwiGLU + channel maxima", 5: "dH + SwiGLU backward",
              9: "dX (two products, two launches)"}
 
-# L2<->memory bytes per launch of the dominant kernel (gemm_kernel<0, 1, false>: dW3, dW1, dW2) from two
+# L2<->memory bytes per launch of the dominant kernel (gemm_kernel<0, 1, 0>: dW3, dW1, dW2) from two
 # rocprofv3 --pmc runs of this command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
 # reads for a 1 GiB copy (factors 2.000 and 1.000); see profiles/bench_7b_hbm_traffic.txt.  Algorithmic
 # bytes of that launch: 61.9 MB of FP8 operands read + 180.4 MB of fp32 written.
-MEASURED_TRAFFIC_BYTES = {"gemm_kernel<0, 1, false>": 329.1e6 + 191.6e6}
+MEASURED_TRAFFIC_BYTES = {"gemm_kernel<0, 1, 0>": 329.4e6 + 191.6e6}
 
 
 def gemm_flops_by_tag(T, d, f):
@@ -81,9 +81,9 @@ ADAM_KERNELS = {32: "adam_range_kernel<false, 2>", 33: "adam_update_kernel<false
 # writes w (4), the bf16 copy (2) and two codes
 ADAM_BYTES = {32: 6.0, 33: 18.0}
 # L2<->memory bytes per launch of the update pass at 45.1 M elements, from the same two rocprofv3 --pmc runs as
-# MEASURED_TRAFFIC_BYTES below (profiles/bench_7b_hbm_traffic.txt): 452.2 MB fetched + 375.3 MB written, against
+# MEASURED_TRAFFIC_BYTES below (profiles/bench_7b_hbm_traffic.txt): 452.3 MB fetched + 375.4 MB written, against
 # 811.6 MB algorithmic
-ADAM_MEASURED_TRAFFIC_BYTES = {45088768: 452.2e6 + 375.3e6}
+ADAM_MEASURED_TRAFFIC_BYTES = {45088768: 452.3e6 + 375.4e6}
 
 
 def bench_adam(ssg, torch, grads, weights, steps, warmup, stream, cpu_sample=1 << 22, with_cpu=True):

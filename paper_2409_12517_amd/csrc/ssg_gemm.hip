@@ -143,10 +143,13 @@ __device__ __forceinline__ void map_tile(const GemmParams &p, int &tile_m, int &
 // slots and publishes step k+1 (each wave first waits for its own DMA share).
 constexpr int kThreads = 256;
 
-// ADD (plain store only): the fp32 matrix p.add [M, N] is added to the scaled result before it is rounded and
-// stored -- the second half of a sum of two products run as two launches.
-template <int EPI, int AFMT, bool ADD = false>
+// PART (plain store only) names the role in a sum of two products run as two launches: 1 = first half (stores
+// its scaled product as fp32 scratch; the same code as 0, a separate symbol so that profiles tell it from the
+// weight-gradient GEMMs), 2 = second half (the fp32 matrix p.add [M, N] is added to the scaled result before it
+// is rounded and stored).  0 = an ordinary GEMM.
+template <int EPI, int AFMT, int PART = 0>
 __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
+    constexpr bool ADD = PART == 2;
     constexpr bool kDual = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_Q;     // B tile = 128 rows of W1 + 128 rows of W2
     __shared__ __attribute__((aligned(1024))) uint8_t smem[kUnits * kUnitBytes];
 
@@ -531,12 +534,12 @@ static void launch_one(const GemmParams &p, unsigned blocks, hipStream_t st) {
         GemmParams a = p;
         a.A2 = nullptr; a.B2 = nullptr; a.K2 = 0; a.sa2 = nullptr; a.sb2 = nullptr;
         a.C = p.tmp; a.c_f32 = 1;
-        hipLaunchKernelGGL((gemm_kernel<EPI_STORE, AFMT>), dim3(blocks), dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL((gemm_kernel<EPI_STORE, AFMT, 1>), dim3(blocks), dim3(kThreads), 0, st, a);
         GemmParams b = p;
         b.A = p.A2; b.B = p.B2; b.K = p.K2; b.sa = p.sa2; b.sb = p.sb2;
         b.A2 = nullptr; b.B2 = nullptr; b.K2 = 0; b.sa2 = nullptr; b.sb2 = nullptr;
         b.add = p.tmp;
-        hipLaunchKernelGGL((gemm_kernel<EPI_STORE, AFMT, true>), dim3(blocks), dim3(kThreads), 0, st, b);
+        hipLaunchKernelGGL((gemm_kernel<EPI_STORE, AFMT, 2>), dim3(blocks), dim3(kThreads), 0, st, b);
     }
 }
 
