@@ -93,3 +93,23 @@ def test_mfma_rate_probe_runs_and_checks_its_arguments():
     assert torch.all(sink == 16 * 16 * 3 * 64.0)
     with pytest.raises(ssg.SsgError):
         ssg.ssg_probe_mfma_rate(ws[:4096], 3)
+
+
+@pytest.mark.parametrize("c_dtype", [ssg.SSG_F32, ssg.SSG_BF16])
+def test_nan_and_inf_codes_propagate_to_their_rows_only(c_dtype):
+    """One NaN code in a row of A (E4M3 0x7F) and one infinity in another (E5M2 0x7C): those output rows are
+    NaN / non-finite, every other row is untouched (also through the bf16 packing of the epilogue)."""
+    rng = np.random.default_rng(5)
+    M, N, K = 272, 320, 256
+    a = _codes(rng, ssg.SSG_E5M2, (M, K))
+    b = _codes(rng, ssg.SSG_E4M3, (N, K))
+    clean = _run(a, ssg.SSG_E5M2, b, 2.0, 0.5, c_dtype)
+    a2 = a.copy()
+    a2[37, 100] = 0x7F          # E5M2 NaN
+    a2[200, 3] = 0x7C           # E5M2 +inf
+    got = _run(a2, ssg.SSG_E5M2, b, 2.0, 0.5, c_dtype)
+    assert np.all(np.isnan(got[37]))
+    assert not np.any(np.isfinite(got[200][fp8.decode(b[:, 3], fp8.E4M3) != 0]))
+    keep = np.ones(M, bool)
+    keep[[37, 200]] = False
+    assert np.array_equal(got[keep], clean[keep])

@@ -88,3 +88,24 @@ def test_delayed_mode_needs_a_state_and_cached_weights_keep_their_history():
     pos = lambda w: int(w[0, 1:2].view(np.int32)[0])          # the ring position is an integer word
     assert pos(after) == pos(before) + 1                      # x advanced
     assert torch.equal(y0, blk.y)                             # same inputs, history = their own ranges
+
+
+def test_recorded_range_ignores_nan_and_keeps_infinity():
+    """The cast that records the range for the history takes it on the raw bf16 patterns: NaN must not
+    enter it (as in the stand-alone range pass), infinity must."""
+    base = synth.make_inputs(64, 64, 96, seed=47)
+    state = torch.empty(ssg.ssg_mlp_scaling_state_bytes(), dtype=torch.uint8, device=gu.DEV)
+    ssg.ssg_mlp_scaling_init(state)
+    blk = tm.Block(base)
+    blk.desc = ssg.make_desc(blk.T, blk.d, blk.f, scale_mode=ssg.SSG_SCALE_DELAYED, scaling_state=state)
+    x = base["x"].clone()
+    x[3, 5] = float("nan")
+    x[7, 9] = -float("nan")
+    big = float(x[torch.isfinite(x.float())].float().abs().max())
+    blk.x = gu.dev(x)
+    blk.fwd()
+    assert _state_words(state)[0, 2] == np.float32(big)
+    x[11, 1] = -float("inf")
+    blk.x = gu.dev(x)
+    blk.fwd()
+    assert _state_words(state)[0, 2] == np.inf
