@@ -28,11 +28,11 @@ if ROOT not in sys.path:
 PEAK_FP8_TFLOPS = 5000.0          # MI355X dense FP8 MFMA peak (published: 5.0 PFLOP/s)
 METRIC = "FP8 Smooth-SwiGLU MLP fwd+bwd TFLOP/s (7B shape), % of FP8 MFMA peak"
 # tag of ssg_profile_read -> kernel symbol as rocprofv3 prints it (template args: epilogue, A format, part of a two-launch sum);
-# the two-product input gradient is two launches (the second adds the first's fp32 result), timed as one record
+# the input gradient is two launches (the second adds the first's fp32 result)
 TAG_NAMES = {0: "gemm_kernel<0, 0, 0>", 1: "gemm_kernel<0, 1, 0>", 2: "gemm_kernel<1, 0, 0>",
-             5: "gemm_kernel<2, 1, 0>", 9: "gemm_kernel<0, 1, 1> + gemm_kernel<0, 1, 2>"}
+             5: "gemm_kernel<2, 1, 0>", 9: "gemm_kernel<0, 1, 1>", 10: "gemm_kernel<0, 1, 2>"}
 TAG_ROLES = {0: "y = h^ w3~^T", 1: "dW3, dW1, dW2", 2: "U, G + SwiGLU + channel maxima", 5: "dH + SwiGLU backward",
-             9: "dX (two products, two launches)"}
+             9: "dX, first product (to fp32 scratch)", 10: "dX, second product + scratch"}
 
 # L2<->memory bytes per launch of the dominant kernel (gemm_kernel<0, 1, 0>: dW3, dW1, dW2) from two
 # rocprofv3 --pmc runs of this command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
@@ -49,7 +49,8 @@ def gemm_flops_by_tag(T, d, f):
         2: (2 * one, 1),      # U and G in one launch
         5: (one, 1),          # dH
         1: (3 * one, 3),      # dW3, dW1, dW2
-        9: (2 * one, 1),      # dX: two products, two launches under one timing record
+        9: (one, 1),          # dX: first product
+        10: (one, 1),         # dX: second product, adds the first
     }
 
 
@@ -244,8 +245,8 @@ def main() -> int:
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     dom_ms, _ = ssg.ssg_profile_read(3 * args.steps)
-    # per-kernel breakdown of all seven GEMM launches: a separate pass, not part of `value`
-    launches_per_step = 7
+    # per-kernel breakdown of all eight GEMM launches: a separate pass, not part of `value`
+    launches_per_step = 8
     bsteps = max(5, args.steps // 5)
     ssg.ssg_profile_select(-1)
     ssg.ssg_profile_enable(launches_per_step * bsteps)

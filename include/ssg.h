@@ -260,7 +260,8 @@ ssg_status ssg_adam_view_state(int64_t n, int32_t step, const void *state, ssg_a
  *                          tag = 2 * epilogue + a_fmt with epilogue 0 = plain store (y, dx, dW),
  *                          1 = fused SwiGLU forward (U, G, channel maxima), 2 = fused SwiGLU backward,
  *                          3 = fused SwiGLU product + E4M3 cast of the inference form;
- *                          +8 for the two-product form of the plain store (dx).
+ *                          9 and 10 are the two launches of the input gradient (first product to fp32
+ *                          scratch; second product plus scratch).
  *                          The two passes of ssg_adam_step are recorded too: tag 32 = range pass,
  *                          33 = update pass. */
 ssg_status ssg_profile_enable(int max_records);

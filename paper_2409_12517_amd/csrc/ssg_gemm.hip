@@ -56,9 +56,9 @@ __device__ unsigned long long g_timeline[kTlLaunches * kTlBlocks * kTlStamps];
 #endif
 
 struct GemmParams {
-    const uint8_t *A, *B, *A2, *B2;
-    int64_t M, N, K, K2;
-    const float *sa, *sb, *sa2, *sb2, *col_scale;
+    const uint8_t *A, *B, *B2;
+    int64_t M, N, K;
+    const float *sa, *sb, *sb2, *col_scale;
     void *C, *C2;
     const uint16_t *U, *G;
     uint32_t *camax_bits, *amax_bits, *amax_bits2;
@@ -522,49 +522,29 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     SSG_STAMP(3);
 }
 
-template <int EPI, int AFMT, bool TWO>
-static void launch_one(const GemmParams &p, unsigned blocks, hipStream_t st) {
-    if constexpr (!TWO) {
-        hipLaunchKernelGGL((gemm_kernel<EPI, AFMT>), dim3(blocks), dim3(kThreads), 0, st, p);
-    } else {
-        // Sum of two products: two launches.  The first stores product 1, scaled, as fp32 in the caller's
-        // scratch; the second adds it to its own scaled result before rounding.  (Inside one kernel the
-        // accumulators would have to be rescaled between the products, which this compiler cannot do on 256
-        // AGPR-resident accumulators without spilling them.)
-        GemmParams a = p;
-        a.A2 = nullptr; a.B2 = nullptr; a.K2 = 0; a.sa2 = nullptr; a.sb2 = nullptr;
-        a.C = p.tmp; a.c_f32 = 1;
-        hipLaunchKernelGGL((gemm_kernel<EPI_STORE, AFMT, 1>), dim3(blocks), dim3(kThreads), 0, st, a);
-        GemmParams b = p;
-        b.A = p.A2; b.B = p.B2; b.K = p.K2; b.sa = p.sa2; b.sb = p.sb2;
-        b.A2 = nullptr; b.B2 = nullptr; b.K2 = 0; b.sa2 = nullptr; b.sb2 = nullptr;
-        b.add = p.tmp;
-        hipLaunchKernelGGL((gemm_kernel<EPI_STORE, AFMT, 2>), dim3(blocks), dim3(kThreads), 0, st, b);
-    }
-}
-
-template <int EPI>
+template <int EPI, int PART>
 static void launch_epi(const GemmParams &p, int a_fmt, unsigned blocks, hipStream_t st) {
-    if (EPI == EPI_STORE && p.A2) {        // two K segments: the input gradient sums two products
-        if (a_fmt == kE4M3) launch_one<EPI_STORE, kE4M3, true>(p, blocks, st);
-        else launch_one<EPI_STORE, kE5M2, true>(p, blocks, st);
-        return;
-    }
-    if (a_fmt == kE4M3) launch_one<EPI, kE4M3, false>(p, blocks, st);
-    else launch_one<EPI, kE5M2, false>(p, blocks, st);
+    if (a_fmt == kE4M3) hipLaunchKernelGGL((gemm_kernel<EPI, kE4M3, PART>), dim3(blocks), dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((gemm_kernel<EPI, kE5M2, PART>), dim3(blocks), dim3(kThreads), 0, st, p);
 }
 
 bool launch_gemm(const GemmArgs &a, hipStream_t st) {
-    if (a.A2 && (a.epilogue != EPI_STORE || !a.tmp)) return false;      // a sum of two products needs the fp32 scratch
+    // A sum of two products (the input gradient) runs as two launches: part 1 leaves its scaled product as fp32
+    // scratch, part 2 adds it to its own before rounding.  (Inside one kernel the accumulators would have to be
+    // rescaled between the products, which this compiler cannot do on 256 AGPR-resident accumulators without
+    // spilling them.)
+    if (a.part != 0 && a.epilogue != EPI_STORE) return false;
+    if ((a.part == 2) != (a.add != nullptr)) return false;
+    if (a.part == 1 && !a.c_f32) return false;
     GemmParams p;
-    p.A = a.A; p.B = a.B; p.A2 = a.A2; p.B2 = a.B2;
-    p.M = a.M; p.N = a.N; p.K = a.K; p.K2 = a.K2;
-    p.sa = a.sa; p.sb = a.sb; p.sa2 = a.sa2; p.sb2 = a.sb2; p.col_scale = a.col_scale;
+    p.A = a.A; p.B = a.B; p.B2 = a.B2;
+    p.M = a.M; p.N = a.N; p.K = a.K;
+    p.sa = a.sa; p.sb = a.sb; p.sb2 = a.sb2; p.col_scale = a.col_scale;
     p.C = a.C; p.C2 = a.C2;
     p.U = (const uint16_t *)a.U; p.G = (const uint16_t *)a.G;
     p.camax_bits = a.camax_bits; p.amax_bits = a.amax_bits; p.amax_bits2 = a.amax_bits2;
     p.c_f32 = a.c_f32;
-    p.tmp = a.tmp; p.add = nullptr;
+    p.add = a.add;
     p.tl_slot = 0;
 #if SSG_GEMM_TIMELINE
     static int tl_launch = 0;
@@ -574,12 +554,17 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st) {
     const int n_per_tile = (a.epilogue == EPI_SWIGLU || a.epilogue == EPI_SWIGLU_Q) ? BN / 2 : BN;
     p.tiles_n = (int)((a.N + n_per_tile - 1) / n_per_tile);
     const unsigned blocks = (unsigned)p.tiles_m * (unsigned)p.tiles_n;
-    profile_before(2 * a.epilogue + a.a_fmt + (a.epilogue == EPI_STORE && a.A2 ? 8 : 0), st);
+    // timing tag: 2 * epilogue + A format; the two halves of a sum get 9 and 10
+    profile_before(a.part ? 8 + a.part : 2 * a.epilogue + a.a_fmt, st);
     switch (a.epilogue) {
-        case EPI_STORE: launch_epi<EPI_STORE>(p, a.a_fmt, blocks, st); break;
-        case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(p, a.a_fmt, blocks, st); break;
-        case EPI_SWIGLU_Q: launch_epi<EPI_SWIGLU_Q>(p, a.a_fmt, blocks, st); break;
-        default: launch_epi<EPI_SWIGLU_BWD>(p, a.a_fmt, blocks, st); break;
+        case EPI_STORE:
+            if (a.part == 1) launch_epi<EPI_STORE, 1>(p, a.a_fmt, blocks, st);
+            else if (a.part == 2) launch_epi<EPI_STORE, 2>(p, a.a_fmt, blocks, st);
+            else launch_epi<EPI_STORE, 0>(p, a.a_fmt, blocks, st);
+            break;
+        case EPI_SWIGLU: launch_epi<EPI_SWIGLU, 0>(p, a.a_fmt, blocks, st); break;
+        case EPI_SWIGLU_Q: launch_epi<EPI_SWIGLU_Q, 0>(p, a.a_fmt, blocks, st); break;
+        default: launch_epi<EPI_SWIGLU_BWD, 0>(p, a.a_fmt, blocks, st); break;
     }
     profile_after(st);
     return true;

@@ -79,13 +79,14 @@ struct GemmArgs {
     int64_t M = 0, N = 0, K = 0;
     const uint8_t *A = nullptr;         // [M, K]
     const uint8_t *B = nullptr;         // [N, K]
-    // second product (EPI_STORE only): C = A B^T / (sa sb) + A2 B2^T / (sa2 sb2), run as two launches through `tmp`
-    const uint8_t *A2 = nullptr;        // [M, K2]
-    const uint8_t *B2 = nullptr;        // [N, K2]   (EPI_SWIGLU: the second weight matrix, same K)
-    int64_t K2 = 0;
-    float *tmp = nullptr;               // optional fp32 [M, N] scratch: lets a sum of two products run as two launches
+    const uint8_t *B2 = nullptr;        // EPI_SWIGLU, EPI_SWIGLU_Q: the second weight matrix [N, K]
+    // EPI_STORE as one half of a sum of two products run as two launches:
+    //   part = 1: C is the fp32 scratch [M, N] that receives this product, scaled (c_f32 = 1)
+    //   part = 2: `add` (that scratch) is added to this product, scaled, before rounding into C
+    int part = 0;
+    const float *add = nullptr;
     // dequantization: alpha = 1 / (sa * sb); null pointer = 1
-    const float *sa = nullptr, *sb = nullptr, *sa2 = nullptr, *sb2 = nullptr;
+    const float *sa = nullptr, *sb = nullptr, *sb2 = nullptr;   // sb2: scale of B2
     const float *col_scale = nullptr;   // optional [N] factor (EPI_STORE, EPI_SWIGLU_BWD)
     void *C = nullptr;                  // EPI_STORE: [M,N];  EPI_SWIGLU: U;  EPI_SWIGLU_BWD: dU
     void *C2 = nullptr;                 // EPI_SWIGLU: G;  EPI_SWIGLU_BWD: dG
@@ -95,7 +96,7 @@ struct GemmArgs {
     uint32_t *amax_bits = nullptr;      // EPI_SWIGLU_BWD: running max |dU| (float bits), kAmaxSlots slots
     uint32_t *amax_bits2 = nullptr;     //                 same for |dG|
 };
-// false (nothing launched): a sum of two products was asked for without the fp32 scratch or with a fused epilogue
+// false (nothing launched): inconsistent arguments (part / add / epilogue)
 bool launch_gemm(const GemmArgs &a, hipStream_t st);
 
 // Benchmark hook: called by launch_gemm before and after the kernel launch (no-ops unless enabled).
