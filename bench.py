@@ -183,7 +183,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="7b", help="name in synth.CONFIGS (default: the headline shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=512)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
     ap.add_argument("--no-adam", action="store_true", help="skip the FP8-moment Adam step reported under 'adam_step'")
     ap.add_argument("--copy-probe", action="store_true",
                     help="first run three 1 GiB device-to-device copies (a kernel of known traffic, used to "
