@@ -88,6 +88,14 @@ ssg_status ssg_quantize(const void *src, ssg_dtype src_dtype, int64_t rows, int6
 ssg_status ssg_gemm_fp8(const uint8_t *A, ssg_fp8_format a_fmt, const uint8_t *B, ssg_fp8_format b_fmt,
                         int64_t M, int64_t N, int64_t K, const float *sa_dev, const float *sb_dev,
                         void *C, ssg_dtype c_dtype, void *stream);
+/* The same contraction with "K-major" operands: a_kmajor = 1 means A is stored as [K,M] (M contiguous),
+ * b_kmajor = 1 that B is stored as [K,N].  This is how the backward contractions read the tensors the
+ * forward quantized row-major -- dY^ [T,d], h^ [T,f], x^ [T,d], dU^ [T,f] for the weight gradients (contraction
+ * over T), w^ [f,d] and w3~ [d,f] for the input gradients -- without transposed copies.  Built combinations:
+ * (0,0), (0,1), (1,1); (1,0) returns SSG_ERR_UNSUPPORTED. */
+ssg_status ssg_gemm_fp8_layout(const uint8_t *A, ssg_fp8_format a_fmt, int a_kmajor, const uint8_t *B,
+                               ssg_fp8_format b_fmt, int b_kmajor, int64_t M, int64_t N, int64_t K,
+                               const float *sa_dev, const float *sb_dev, void *C, ssg_dtype c_dtype, void *stream);
 
 /* SwiGLU product of Section 4.1 from stored bf16 U, G [T,f], in fp32:
  * h = u * (g * (1 / (1 + exp(-g)))).  Debug / test entry: this is the h the
@@ -149,8 +157,7 @@ size_t ssg_mlp_scaling_state_bytes(void);
 ssg_status ssg_mlp_scaling_init(void *scaling_state, void *stream);
 
 /* Sizes of the two caller-allocated device buffers.  `saved` carries what the
- * backward pass needs (quantized operands, their transposed copies, bf16 U and
- * G, the factors); `workspace` is scratch of the backward pass.  0 on a bad
+ * backward pass needs (quantized operands, bf16 U and G, the factors); `workspace` is scratch of the backward pass.  0 on a bad
  * descriptor. */
 size_t ssg_mlp_saved_bytes(const ssg_mlp_desc *desc);
 size_t ssg_mlp_workspace_bytes(const ssg_mlp_desc *desc);
@@ -170,12 +177,13 @@ typedef struct {
     const float *scales;     /* [0]=sx [1]=sw1 [2]=sw2 [3]=sw3 [4]=amax_x [5]=amax_w1 [6]=amax_w2 [7]=amax of s^-1*w3
                                 ([4..6] are written under current scaling only) */
     const float *s, *sinv, *h_camax, *w3_camax;          /* f floats each */
-    const uint8_t *x_q, *x_qT, *w1_q, *w2_q, *w1_qT, *w2_qT, *h_q, *h_qT, *w3_q, *w3_qT;
+    const uint8_t *x_q, *w1_q, *w2_q, *h_q, *w3_q;       /* [T,d], [f,d], [f,d], [T,f], [d,f]: row-major only; the
+                                                            backward reads them K-major, no transposed copies */
     const void *U, *G;                                   /* bf16 [T,f] */
 } ssg_mlp_saved_view;
 typedef struct {
     const float *scales;     /* [0]=sdy [1]=sdu [2]=sdg [3]=amax_dy [4]=amax_du [5]=amax_dg ([3..5]: current scaling only) */
-    const uint8_t *dy_q, *dy_qT, *du_q, *du_qT, *dg_q, *dg_qT;
+    const uint8_t *dy_q, *du_q, *dg_q;                   /* [T,d], [T,f], [T,f] */
     const void *dU, *dG;                                 /* bf16 [T,f] */
 } ssg_mlp_workspace_view;
 ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_mlp_saved_view *out);

@@ -30,7 +30,7 @@ SSG_SCALE_CURRENT, SSG_SCALE_GIVEN, SSG_SCALE_DELAYED = 0, 1, 2
 SSG_ROUND_EXACT_DIV, SSG_ROUND_POW2 = 0, 1
 
 EXPORTS = [
-    "ssg_last_error", "ssg_version", "ssg_amax", "ssg_quantize", "ssg_gemm_fp8", "ssg_swiglu",
+    "ssg_last_error", "ssg_version", "ssg_amax", "ssg_quantize", "ssg_gemm_fp8", "ssg_gemm_fp8_layout", "ssg_swiglu",
     "ssg_smooth_swiglu_quantize", "ssg_fold_w3", "ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes",
     "ssg_mlp_fwd", "ssg_mlp_bwd", "ssg_mlp_view_saved", "ssg_mlp_view_workspace",
     "ssg_mlp_scaling_state_bytes", "ssg_mlp_scaling_init",
@@ -62,12 +62,11 @@ class ssg_adam_state_view(Structure):
 
 class ssg_mlp_saved_view(Structure):
     _fields_ = [(n, c_void_p) for n in (
-        "scales", "s", "sinv", "h_camax", "w3_camax", "x_q", "x_qT", "w1_q", "w2_q", "w1_qT", "w2_qT",
-        "h_q", "h_qT", "w3_q", "w3_qT", "U", "G")]
+        "scales", "s", "sinv", "h_camax", "w3_camax", "x_q", "w1_q", "w2_q", "h_q", "w3_q", "U", "G")]
 
 
 class ssg_mlp_workspace_view(Structure):
-    _fields_ = [(n, c_void_p) for n in ("scales", "dy_q", "dy_qT", "du_q", "du_qT", "dg_q", "dg_qT", "dU", "dG")]
+    _fields_ = [(n, c_void_p) for n in ("scales", "dy_q", "du_q", "dg_q", "dU", "dG")]
 
 
 _lib.ssg_last_error.restype = c_char_p
@@ -77,6 +76,8 @@ _lib.ssg_quantize.argtypes = [c_void_p, c_int, c_int64, c_int64, c_int, c_int, c
                               c_void_p, c_void_p, c_void_p]
 _lib.ssg_gemm_fp8.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int64, c_int64, c_int64, c_void_p, c_void_p,
                               c_void_p, c_int, c_void_p]
+_lib.ssg_gemm_fp8_layout.argtypes = [c_void_p, c_int, c_int, c_void_p, c_int, c_int, c_int64, c_int64, c_int64, c_void_p,
+                                     c_void_p, c_void_p, c_int, c_void_p]
 _lib.ssg_swiglu.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_void_p]
 _lib.ssg_smooth_swiglu_quantize.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int, c_void_p, c_void_p,
                                             c_void_p, c_void_p, c_void_p, c_void_p]
@@ -169,6 +170,11 @@ def ssg_quantize(src, src_dtype, rows, cols, fmt, mode, rnd, dst, dst_t, scale_d
 def ssg_gemm_fp8(A, a_fmt, B, b_fmt, M, N, K, sa_dev, sb_dev, C, c_dtype, stream=None):
     _check(_lib.ssg_gemm_fp8(_ptr(A), a_fmt, _ptr(B), b_fmt, M, N, K, _ptr(sa_dev), _ptr(sb_dev), _ptr(C),
                              c_dtype, _stream(stream)))
+
+
+def ssg_gemm_fp8_layout(A, a_fmt, a_kmajor, B, b_fmt, b_kmajor, M, N, K, sa_dev, sb_dev, C, c_dtype, stream=None):
+    _check(_lib.ssg_gemm_fp8_layout(_ptr(A), a_fmt, a_kmajor, _ptr(B), b_fmt, b_kmajor, M, N, K, _ptr(sa_dev),
+                                    _ptr(sb_dev), _ptr(C), c_dtype, _stream(stream)))
 
 
 def ssg_swiglu(U, G, T, f, h, stream=None):

@@ -60,7 +60,7 @@ bool fmt_ok(int f) { return f == SSG_E4M3 || f == SSG_E5M2; }
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct SavedLayout {
-    size_t scalars, partials, s, sinv, h_camax, w3_camax, x_q, x_qT, w1_q, w2_q, w1_qT, w2_qT, U, G, h_q, h_qT, w3_q, w3_qT, total;
+    size_t scalars, partials, s, sinv, h_camax, w3_camax, x_q, w1_q, w2_q, U, G, h_q, w3_q, total;
 };
 // scalar slots of `saved` (floats; amax slots are accumulated as bit patterns)
 enum { S_SX = 0, S_SW1, S_SW2, S_SW3, S_AMAX_X, S_AMAX_W1, S_AMAX_W2, S_AMAX_W3S, S_HMAX, S_COUNT = 64 };
@@ -75,16 +75,16 @@ SavedLayout saved_layout(const ssg_mlp_desc &d) {
     L.partials = take(3 * ssg::kAmaxSlotWords * 4);
     L.h_camax = take(f * 4); L.w3_camax = take(f * 4);
     L.s = take(f * 4); L.sinv = take(f * 4);
-    L.x_q = take(T * dm); L.x_qT = take(T * dm);
-    L.w1_q = take(f * dm); L.w2_q = take(f * dm); L.w1_qT = take(f * dm); L.w2_qT = take(f * dm);
+    L.x_q = take(T * dm);
+    L.w1_q = take(f * dm); L.w2_q = take(f * dm);
     L.U = take(T * f * 2); L.G = take(T * f * 2);
-    L.h_q = take(T * f); L.h_qT = take(T * f);
-    L.w3_q = take(f * dm); L.w3_qT = take(f * dm);
+    L.h_q = take(T * f);
+    L.w3_q = take(f * dm);
     L.total = o;
     return L;
 }
 
-struct WorkLayout { size_t scalars, partials, dy_q, dy_qT, dU, dG, du_q, du_qT, dg_q, dg_qT, dx_tmp, total; };
+struct WorkLayout { size_t scalars, partials, dy_q, dU, dG, du_q, dg_q, dx_tmp, total; };
 enum { W_SDY = 0, W_SDU, W_SDG, W_AMAX_DY, W_AMAX_DU, W_AMAX_DG, W_COUNT = 64 };
 
 WorkLayout work_layout(const ssg_mlp_desc &d) {
@@ -94,9 +94,9 @@ WorkLayout work_layout(const ssg_mlp_desc &d) {
     auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
     L.scalars = take(W_COUNT * 4);
     L.partials = take(3 * ssg::kAmaxSlotWords * 4);     // slotted running maxima of dY, dU, dG (adjacent to the scalars)
-    L.dy_q = take(T * dm); L.dy_qT = take(T * dm);
+    L.dy_q = take(T * dm);
     L.dU = take(T * f * 2); L.dG = take(T * f * 2);
-    L.du_q = take(T * f); L.du_qT = take(T * f); L.dg_q = take(T * f); L.dg_qT = take(T * f);
+    L.du_q = take(T * f); L.dg_q = take(T * f);
     L.dx_tmp = take(T * dm * 4);                        // fp32 first product of the input gradient
     L.total = o;
     return L;
@@ -453,12 +453,14 @@ ssg_status ssg_quantize(const void *src, ssg_dtype src_dtype, int64_t rows, int6
     return check_launch("ssg_quantize");
 }
 
-ssg_status ssg_gemm_fp8(const uint8_t *A, ssg_fp8_format a_fmt, const uint8_t *B, ssg_fp8_format b_fmt, int64_t M,
-                        int64_t N, int64_t K, const float *sa_dev, const float *sb_dev, void *C,
-                        ssg_dtype c_dtype, void *stream) {
+ssg_status ssg_gemm_fp8_layout(const uint8_t *A, ssg_fp8_format a_fmt, int a_kmajor, const uint8_t *B,
+                               ssg_fp8_format b_fmt, int b_kmajor, int64_t M, int64_t N, int64_t K, const float *sa_dev,
+                               const float *sb_dev, void *C, ssg_dtype c_dtype, void *stream) {
     if (!fmt_ok(a_fmt) || !fmt_ok(b_fmt)) return fail(SSG_ERR_ARG, "ssg_gemm_fp8: bad format");
     if (b_fmt != SSG_E4M3) return fail(SSG_ERR_UNSUPPORTED, "ssg_gemm_fp8: B must be E4M3");
     if (!dtype_ok(c_dtype)) return fail(SSG_ERR_ARG, "ssg_gemm_fp8: bad c_dtype");
+    if ((a_kmajor != 0 && a_kmajor != 1) || (b_kmajor != 0 && b_kmajor != 1)) return fail(SSG_ERR_ARG, "ssg_gemm_fp8: bad layout flag");
+    if (a_kmajor && !b_kmajor) return fail(SSG_ERR_UNSUPPORTED, "ssg_gemm_fp8: A K-major with B K-contiguous is not built");
     if (!extent_ok(M) || !extent_ok(N) || !extent_ok(K))
         return fail(SSG_ERR_SHAPE, "ssg_gemm_fp8: M=%lld N=%lld K=%lld must be positive multiples of 16",
                     (long long)M, (long long)N, (long long)K);
@@ -467,9 +469,16 @@ ssg_status ssg_gemm_fp8(const uint8_t *A, ssg_fp8_format a_fmt, const uint8_t *B
     SSG_REQUIRE_PTR(A); SSG_REQUIRE_PTR(B); SSG_REQUIRE_PTR(C);
     ssg::GemmArgs g;
     g.epilogue = ssg::EPI_STORE; g.a_fmt = a_fmt; g.M = M; g.N = N; g.K = K; g.A = A; g.B = B;
+    g.layout = a_kmajor ? 2 : (b_kmajor ? 1 : 0);
     g.sa = sa_dev; g.sb = sb_dev; g.C = C; g.c_f32 = c_dtype == SSG_F32;
     if (!ssg::launch_gemm(g, (hipStream_t)stream)) return fail(SSG_ERR_ARG, "ssg_gemm_fp8: internal GEMM arguments");
     return check_launch("ssg_gemm_fp8");
+}
+
+ssg_status ssg_gemm_fp8(const uint8_t *A, ssg_fp8_format a_fmt, const uint8_t *B, ssg_fp8_format b_fmt, int64_t M,
+                        int64_t N, int64_t K, const float *sa_dev, const float *sb_dev, void *C,
+                        ssg_dtype c_dtype, void *stream) {
+    return ssg_gemm_fp8_layout(A, a_fmt, 0, B, b_fmt, 0, M, N, K, sa_dev, sb_dev, C, c_dtype, stream);
 }
 
 ssg_status ssg_swiglu(const void *U, const void *G, int64_t T, int64_t f, float *h, void *stream) {
@@ -551,9 +560,9 @@ ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_m
     out->sinv = reinterpret_cast<const float *>(b + L.sinv);
     out->h_camax = reinterpret_cast<const float *>(b + L.h_camax);
     out->w3_camax = reinterpret_cast<const float *>(b + L.w3_camax);
-    out->x_q = b + L.x_q; out->x_qT = b + L.x_qT;
-    out->w1_q = b + L.w1_q; out->w2_q = b + L.w2_q; out->w1_qT = b + L.w1_qT; out->w2_qT = b + L.w2_qT;
-    out->h_q = b + L.h_q; out->h_qT = b + L.h_qT; out->w3_q = b + L.w3_q; out->w3_qT = b + L.w3_qT;
+    out->x_q = b + L.x_q;
+    out->w1_q = b + L.w1_q; out->w2_q = b + L.w2_q;
+    out->h_q = b + L.h_q; out->w3_q = b + L.w3_q;
     out->U = b + L.U; out->G = b + L.G;
     return SSG_OK;
 }
@@ -565,8 +574,8 @@ ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspac
     const WorkLayout L = work_layout(*desc);
     const uint8_t *b = static_cast<const uint8_t *>(workspace);
     out->scales = reinterpret_cast<const float *>(b + L.scalars);
-    out->dy_q = b + L.dy_q; out->dy_qT = b + L.dy_qT;
-    out->du_q = b + L.du_q; out->du_qT = b + L.du_qT; out->dg_q = b + L.dg_q; out->dg_qT = b + L.dg_qT;
+    out->dy_q = b + L.dy_q;
+    out->du_q = b + L.du_q; out->dg_q = b + L.dg_q;
     out->dU = b + L.dU; out->dG = b + L.dG;
     return SSG_OK;
 }
@@ -609,8 +618,8 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     c.kind = ssg::SRC_BF16; c.fmt = ssg::kE4M3; c.pow2 = pow2;
     c.amax_slots = ssg::kAmaxSlots;
     auto quantize_input = [&](const void *src, int64_t rows, int64_t cols, uint32_t *part, int k, float *amax_out,
-                              float *scale_out, uint8_t *dst, uint8_t *dst_t) {
-        c.src = src; c.rows = rows; c.cols = cols; c.scale_out = scale_out; c.dst = dst; c.dst_t = dst_t;
+                              float *scale_out, uint8_t *dst) {
+        c.src = src; c.rows = rows; c.cols = cols; c.scale_out = scale_out; c.dst = dst;
         if (delayed) {
             c.amax = nullptr; c.amax_out = nullptr; c.scale_in = state_scale(k); c.record = state_slots(k);
         } else {
@@ -619,10 +628,10 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
         }
         ssg::launch_cast(c, st);
     };
-    quantize_input(x, T, dm, part_x, 0, sc + S_AMAX_X, sc + S_SX, b + L.x_q, b + L.x_qT);
+    quantize_input(x, T, dm, part_x, 0, sc + S_AMAX_X, sc + S_SX, b + L.x_q);
     if (!cached) {
-        quantize_input(W1, f, dm, part_w1, 1, sc + S_AMAX_W1, sc + S_SW1, b + L.w1_q, b + L.w1_qT);
-        quantize_input(W2, f, dm, part_w2, 2, sc + S_AMAX_W2, sc + S_SW2, b + L.w2_q, b + L.w2_qT);
+        quantize_input(W1, f, dm, part_w1, 1, sc + S_AMAX_W1, sc + S_SW1, b + L.w1_q);
+        quantize_input(W2, f, dm, part_w2, 2, sc + S_AMAX_W2, sc + S_SW2, b + L.w2_q);
         // per-channel range of w3, needed for the range of s^-1 * w3 (constant between weight updates)
         ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
     }
@@ -641,14 +650,14 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     // a6: h^ = cast(s_i * h), recomputing h from the stored bf16 U, G
     ssg::CastArgs hq;
     hq.src = b + L.U; hq.src2 = b + L.G; hq.kind = ssg::SRC_SWIGLU; hq.rows = T; hq.cols = f; hq.fmt = ssg::kE4M3;
-    hq.col_scale = s; hq.dst = b + L.h_q; hq.dst_t = b + L.h_qT;
+    hq.col_scale = s; hq.dst = b + L.h_q;
     ssg::launch_cast(hq, st);
 
     // a7: w3~ = Q(s^-1 * w3)
     ssg::CastArgs wq;
     wq.src = W3; wq.kind = ssg::SRC_BF16; wq.rows = dm; wq.cols = f; wq.fmt = ssg::kE4M3; wq.pow2 = pow2;
     wq.col_scale = sinv; wq.amax = sc + S_AMAX_W3S; wq.scale_out = sc + S_SW3;
-    wq.dst = b + L.w3_q; wq.dst_t = b + L.w3_qT;
+    wq.dst = b + L.w3_q;
     ssg::launch_cast(wq, st);
 
     // a8: last linear layer.  Smooth: only the scale of w3~ is left; plain: s_i = sigma_h for all i
@@ -705,7 +714,7 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     // a9: upstream gradient to E5M2 (Section 6.2), with its transposed copy
     ssg::CastArgs c;
     c.src = dy; c.kind = ssg::SRC_BF16; c.rows = T; c.cols = dm; c.fmt = ssg::kE5M2; c.pow2 = pow2;
-    c.amax_slots = ssg::kAmaxSlots; c.scale_out = wsc + W_SDY; c.dst = wk + Wl.dy_q; c.dst_t = wk + Wl.dy_qT;
+    c.amax_slots = ssg::kAmaxSlots; c.scale_out = wsc + W_SDY; c.dst = wk + Wl.dy_q;
     if (delayed) {
         c.scale_in = state_scale(3); c.record = state_dy_slots;
     } else {
@@ -718,16 +727,15 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     // a10: dH = s_i * dY^ w3~ / (sdy sw3), then through the SwiGLU product
     ssg::GemmArgs g;
     g.epilogue = ssg::EPI_SWIGLU_BWD; g.a_fmt = ssg::kE5M2; g.M = T; g.N = f; g.K = dm;
-    g.A = wk + Wl.dy_q; g.B = sv + L.w3_qT; g.sa = wsc + W_SDY; g.sb = sc + S_SW3;
+    g.A = wk + Wl.dy_q; g.B = sv + L.w3_q; g.layout = 1; g.sa = wsc + W_SDY; g.sb = sc + S_SW3;   // B = w3~ as stored, [d,f] = [K,N]
     // plain block: dH = acc / (sdy sw3), no channel factor
     g.col_scale = desc->smooth ? s : nullptr;
     g.U = sv + L.U; g.G = sv + L.G; g.C = wk + Wl.dU; g.C2 = wk + Wl.dG; g.amax_bits = part_du; g.amax_bits2 = part_dg;
     if (!ssg::launch_gemm(g, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
 
     // a11: two tensors, two E5M2 scales (their ranges came out of the epilogue above either way)
-    auto cast_grad = [&](const void *src, float *amax_slots, float *amax_out, float *scale_out, int k, uint8_t *dst,
-                         uint8_t *dst_t) {
-        c.kind = ssg::SRC_BF16; c.rows = T; c.cols = f; c.src = src; c.scale_out = scale_out; c.dst = dst; c.dst_t = dst_t;
+    auto cast_grad = [&](const void *src, float *amax_slots, float *amax_out, float *scale_out, int k, uint8_t *dst) {
+        c.kind = ssg::SRC_BF16; c.rows = T; c.cols = f; c.src = src; c.scale_out = scale_out; c.dst = dst;
         if (delayed) { c.amax = nullptr; c.amax_out = nullptr; c.scale_in = state_scale(k); }
         else { c.amax = amax_slots; c.amax_out = amax_out; c.scale_in = nullptr; }
         ssg::launch_cast(c, st);
@@ -735,25 +743,28 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     // a12: dW3[j,i] = sinv_i * sum_t dY^[t,j] h^[t,i] / sdy   (plain: / (sdy * sigma_h))
     ssg::GemmArgs g3;
     g3.epilogue = ssg::EPI_STORE; g3.a_fmt = ssg::kE5M2; g3.M = dm; g3.N = f; g3.K = T;
-    g3.A = wk + Wl.dy_qT; g3.B = sv + L.h_qT; g3.sa = wsc + W_SDY; g3.sb = desc->smooth ? nullptr : s;
+    g3.layout = 2;                                                                     // dY^ [T,d] = [K,M], h^ [T,f] = [K,N]
+    g3.A = wk + Wl.dy_q; g3.B = sv + L.h_q; g3.sa = wsc + W_SDY; g3.sb = desc->smooth ? nullptr : s;
     g3.col_scale = desc->smooth ? sinv : nullptr; g3.C = dW3; g3.c_f32 = dw_f32;
     // a13: dX = dU^ w1^ / (sdu sw1) + dG^ w2^ / (sdg sw2): two launches, the first product through fp32 scratch
     float *dx_tmp = reinterpret_cast<float *>(wk + Wl.dx_tmp);
     ssg::GemmArgs g4a, g4b;
     g4a.epilogue = ssg::EPI_STORE; g4a.a_fmt = ssg::kE5M2; g4a.M = T; g4a.N = dm; g4a.K = f; g4a.part = 1;
-    g4a.A = wk + Wl.du_q; g4a.B = sv + L.w1_qT; g4a.sa = wsc + W_SDU; g4a.sb = sc + S_SW1; g4a.C = dx_tmp; g4a.c_f32 = 1;
+    g4a.layout = 1;                                                                    // w1^ [f,d] = [K,N]
+    g4a.A = wk + Wl.du_q; g4a.B = sv + L.w1_q; g4a.sa = wsc + W_SDU; g4a.sb = sc + S_SW1; g4a.C = dx_tmp; g4a.c_f32 = 1;
     g4b = g4a; g4b.part = 2;
-    g4b.A = wk + Wl.dg_q; g4b.B = sv + L.w2_qT; g4b.sa = wsc + W_SDG; g4b.sb = sc + S_SW2; g4b.add = dx_tmp;
+    g4b.A = wk + Wl.dg_q; g4b.B = sv + L.w2_q; g4b.sa = wsc + W_SDG; g4b.sb = sc + S_SW2; g4b.add = dx_tmp;
     g4b.C = dx; g4b.c_f32 = desc->y_dtype == SSG_F32;
     // a14: dW1 = dU^T x^ / (sdu sx), dW2 = dG^T x^ / (sdg sx)
     ssg::GemmArgs g5a, g5b;
     g5a.epilogue = ssg::EPI_STORE; g5a.a_fmt = ssg::kE5M2; g5a.M = f; g5a.N = dm; g5a.K = T;
-    g5a.A = wk + Wl.du_qT; g5a.B = sv + L.x_qT; g5a.sa = wsc + W_SDU; g5a.sb = sc + S_SX; g5a.C = dW1; g5a.c_f32 = dw_f32;
-    g5b = g5a; g5b.A = wk + Wl.dg_qT; g5b.sa = wsc + W_SDG; g5b.C = dW2;
+    g5a.layout = 2;                                                                    // dU^ [T,f] = [K,M], x^ [T,d] = [K,N]
+    g5a.A = wk + Wl.du_q; g5a.B = sv + L.x_q; g5a.sa = wsc + W_SDU; g5a.sb = sc + S_SX; g5a.C = dW1; g5a.c_f32 = dw_f32;
+    g5b = g5a; g5b.A = wk + Wl.dg_q; g5b.sa = wsc + W_SDG; g5b.C = dW2;
 #define SSG_GEMM(g) do { if (!ssg::launch_gemm(g, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__); } while (0)
     // (running each cast right before the GEMMs that read its output, or dW3 first, measured the same within 0.3 %)
-    cast_grad(wk + Wl.dU, reinterpret_cast<float *>(part_du), wsc + W_AMAX_DU, wsc + W_SDU, 4, wk + Wl.du_q, wk + Wl.du_qT);
-    cast_grad(wk + Wl.dG, reinterpret_cast<float *>(part_dg), wsc + W_AMAX_DG, wsc + W_SDG, 5, wk + Wl.dg_q, wk + Wl.dg_qT);
+    cast_grad(wk + Wl.dU, reinterpret_cast<float *>(part_du), wsc + W_AMAX_DU, wsc + W_SDU, 4, wk + Wl.du_q);
+    cast_grad(wk + Wl.dG, reinterpret_cast<float *>(part_dg), wsc + W_AMAX_DG, wsc + W_SDG, 5, wk + Wl.dg_q);
     SSG_GEMM(g3); SSG_GEMM(g4a); SSG_GEMM(g4b); SSG_GEMM(g5a); SSG_GEMM(g5b);
 #undef SSG_GEMM
     if (state) {

@@ -147,9 +147,15 @@ constexpr int kThreads = 256;
 // its scaled product as fp32 scratch; the same code as 0, a separate symbol so that profiles tell it from the
 // weight-gradient GEMMs), 2 = second half (the fp32 matrix p.add [M, N] is added to the scaled result before it
 // is rounded and stored).  0 = an ordinary GEMM.
-template <int EPI, int AFMT, int PART = 0>
+// LAY names how the operands lie in memory: 0 = both with the contraction index contiguous (A [M,K], B [N,K]);
+// 1 = B "K-major" (stored [K,N], N contiguous); 2 = both K-major (A stored [K,M]).  A K-major tile is streamed
+// into LDS as 128 rows of K x 256 bytes and its MFMA fragments are read with the transposing LDS load, so the
+// backward contractions read the forward's quantized tensors as they are: no transposed copies exist.
+template <int EPI, int AFMT, int PART = 0, int LAY = 0>
 __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     constexpr bool ADD = PART == 2;
+    constexpr bool AKM = LAY == 2, BKM = LAY >= 1;
+    static_assert(!(BKM && (EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_Q)), "the dual-B forms take K-contiguous operands");
     constexpr bool kDual = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_Q;     // B tile = 128 rows of W1 + 128 rows of W2
     __shared__ __attribute__((aligned(1024))) uint8_t smem[kUnits * kUnitBytes];
 
@@ -162,23 +168,37 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     const int64_t n0 = (int64_t)tile_n * (kDual ? BN / 2 : BN);
     SSG_STAMP(0);
 
-    // DMA slots: a unit is 32 instructions of 8 rows x 128 B, 8 per wave (rows (8w+j)*8 + l/8)
+    // DMA slots: a unit is 32 instructions of 1 KB, 8 per wave.  K-contiguous operand: an instruction is 8 rows x
+    // 128 B (rows (8w+j)*8 + l/8).  K-major operand: 4 rows of K x 256 B (K rows (8w+j)*4 + l/16); the sixteen
+    // 16-byte chunks of a row are XOR-permuted by kmaj_swz(k) so that the transposing reads, which touch eight
+    // consecutive K rows of one chunk column for each of the two K groups, spread over all banks.
     const int lrow = l >> 3;
     const int chunk_even = (l & 7) ^ swz(lrow), chunk_odd = (l & 7) ^ swz(8 + lrow);
+    auto kmaj_swz = [](int k) { return (k & 7) | (((k >> 5) & 1) << 3); };
     uint32_t a_lane[8], b_lane[8];
     const uint8_t *b_src = p.B;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int row = (w * 8 + j) * 8 + lrow;
         const int ck = ((j & 1) ? chunk_odd : chunk_even) * 16;
-        int64_t gm = m0 + row;
-        gm = gm < p.M ? gm : p.M - 1;
-        a_lane[j] = (uint32_t)(gm * p.K) + ck;
-        int64_t gn;
-        if (kDual) gn = n0 + (row & 127);
-        else gn = n0 + row;
-        gn = gn < p.N ? gn : p.N - 1;
-        b_lane[j] = (uint32_t)(gn * p.K) + ck;
+        const int kr = (w * 8 + j) * 4 + (l >> 4);                     // K-major: K row of this lane's chunk
+        const int ckm = ((l & 15) ^ kmaj_swz(kr)) * 16;                 //          and the chunk it fetches
+        if (AKM) {
+            a_lane[j] = (uint32_t)((int64_t)kr * p.M + m0) + ckm;
+        } else {
+            int64_t gm = m0 + row;
+            gm = gm < p.M ? gm : p.M - 1;
+            a_lane[j] = (uint32_t)(gm * p.K) + ck;
+        }
+        if (BKM) {
+            b_lane[j] = (uint32_t)((int64_t)kr * p.N + n0) + ckm;
+        } else {
+            int64_t gn;
+            if (kDual) gn = n0 + (row & 127);
+            else gn = n0 + row;
+            gn = gn < p.N ? gn : p.N - 1;
+            b_lane[j] = (uint32_t)(gn * p.K) + ck;
+        }
     }
     if (kDual && w >= 2) b_src = p.B2;      // waves 2, 3 fill tile rows 128..255
     const uint32_t lds_w = (uint32_t)(w * 8) * 1024u;
@@ -191,6 +211,19 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
 #pragma unroll
         for (int e = 0; e < 2; ++e)
             frag_off[kh][e] = (uint32_t)((l & 31) * BK + (((kh * 4 + (l >> 5) * 2 + e) ^ swz(l & 31)) << 4));
+    // K-major operand: lane offsets of the transposing reads.  In every group of 16 lanes the even lanes supply
+    // the 8-byte words whose byte j goes to output lane j, the odd lanes those for output lane 8+j; lane p of a
+    // group therefore points at K row p/2 (of eight) and at half p%2 of the 16-byte chunk that holds the group's
+    // 16 rows of the 32-row block.  Four such reads (K rows +0, +8, +16, +24) make one fragment.
+    uint32_t tr_a[4], tr_b[4];
+    {
+        const int g16 = l >> 4, kg = g16 >> 1, g1 = g16 & 1, t = (l & 15) >> 1, e = l & 1;
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            tr_a[rb] = (uint32_t)((kg * 32 + t) * 256 + (((wm * 8 + rb * 2 + g1) ^ (t | (kg << 3))) << 4) + e * 8);
+            tr_b[rb] = (uint32_t)((kg * 32 + t) * 256 + (((wn * 8 + rb * 2 + g1) ^ (t | (kg << 3))) << 4) + e * 8);
+        }
+    }
     const uint32_t a_wave_base = (uint32_t)(wm * 128) * BK;
     const uint32_t b_wave_base = (uint32_t)(kDual ? wn * 64 : wn * 128) * BK;
     auto b_block_off = [](int nb) -> uint32_t {      // SWIGLU: blocks 0, 1 from the W1 rows, 2, 3 from the W2 rows
@@ -219,8 +252,17 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
             const bool is_b = (u & 1) != 0;
             const uint8_t *base = is_b ? b_src : p.A;
             const uint8_t *zero = reinterpret_cast<const uint8_t *>(&g_zero_chunk);
+            const bool kmajor = is_b ? BKM : AKM;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
+                if (kmajor) {
+                    const int kr = (w * 8 + j) * 4 + (l >> 4);
+                    const int64_t col = (is_b ? n0 : m0) + (((l & 15) ^ kmaj_swz(kr)) * 16);
+                    const int64_t ld = is_b ? p.N : p.M;
+                    const bool ok = kbase + kr < Kseg && col < ld;      // extents are multiples of 16: a chunk is all in or out
+                    dma16(ok ? base + (kbase + kr) * ld + col : zero, dst + j * 1024);
+                    continue;
+                }
                 const int row = (w * 8 + j) * 8 + lrow;
                 const int ck = ((j & 1) ? chunk_odd : chunk_even) * 16;
                 int64_t g = (is_b ? n0 + (kDual ? (row & 127) : row) : m0 + row);
@@ -237,6 +279,18 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         auto load_frag = [&](int set, uint32_t sa, uint32_t sb, int kh, int i) {
             constexpr int kOrder[8] = {4, 0, 5, 6, 7, 1, 2, 3};
             const int g = kOrder[i];
+            if ((g < 4 && AKM) || (g >= 4 && BKM)) {
+                typedef int v2i_t __attribute__((ext_vector_type(2)));
+                typedef __attribute__((address_space(3))) v2i_t *lds_v2i_ptr;
+                const uint8_t *base = smem + (g < 4 ? sa * kUnitBytes + tr_a[g] : sb * kUnitBytes + tr_b[g - 4]) + kh * 64 * 256;
+                const v2i_t q0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(base));
+                const v2i_t q1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(base + 8 * 256));
+                const v2i_t q2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(base + 16 * 256));
+                const v2i_t q3 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(base + 24 * 256));
+                const v8i f = v8i{q0.x, q0.y, q1.x, q1.y, q2.x, q2.y, q3.x, q3.y};
+                if (g < 4) fa[set][g] = f; else fb[set][g - 4] = f;
+                return;
+            }
             const uint32_t ub = g < 4 ? sa * kUnitBytes + a_wave_base : sb * kUnitBytes + b_wave_base;   // uniform
             const uint32_t imm = g < 4 ? (uint32_t)(g * 32 * BK) : b_block_off(g - 4);
             const uint4 lo = *reinterpret_cast<const uint4 *>(smem + (frag_off[kh][0] + ub) + imm);
@@ -275,11 +329,14 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         // Steady state: when every K step is whole, the steps whose new units exist run a body without
         // any per-instruction check: wave-uniform source pointers, lane offsets from registers.  The
         // last two steps, and every step of a ragged shape, take the general body.
-        const int kfast = (p.K % BK) == 0 ? (nk > 2 ? nk - 2 : 0) : 0;
+        // (a K-major operand also needs its 256 tile columns to exist: the fast body does no column check)
+        const bool whole = (p.K % BK) == 0 && (!AKM || m0 + BM <= p.M) && (!BKM || n0 + BN <= p.N);
+        const int kfast = whole ? (nk > 2 ? nk - 2 : 0) : 0;
         uint32_t sa = 0, sb = 1, sp = 4;             // ring slots of units 2k, 2k+1 and 2k+4
         auto next_slot = [](uint32_t s) { const uint32_t t = s + 2; return t >= (uint32_t)kUnits ? t - kUnits : t; };
         // wave-uniform sources of the units issued during step k (K step k+2): running pointers in scalar registers
-        const uint8_t *ua = p.A + 2 * BK, *ub = b_src + 2 * BK;
+        const int64_t a_step = AKM ? (int64_t)BK * p.M : BK, b_step = BKM ? (int64_t)BK * p.N : BK;   // bytes per K step
+        const uint8_t *ua = p.A + 2 * a_step, *ub = b_src + 2 * b_step;
         for (int k = 0; k < kfast; ++k) {
             const uint32_t sa_n = next_slot(sa), sb_n = next_slot(sb);
             const uint32_t d4 = smem_base + sp * kUnitBytes + lds_w;
@@ -303,7 +360,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                 __builtin_amdgcn_sched_barrier(0);
             }
             sp = sb; sa = sa_n; sb = sb_n;
-            ua += BK; ub += BK;
+            ua += a_step; ub += b_step;
         }
         for (int k = kfast; k < nk; ++k) {
             const uint32_t sa_n = next_slot(sa), sb_n = next_slot(sb);
@@ -522,10 +579,10 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     SSG_STAMP(3);
 }
 
-template <int EPI, int PART>
+template <int EPI, int PART, int LAY>
 static void launch_epi(const GemmParams &p, int a_fmt, unsigned blocks, hipStream_t st) {
-    if (a_fmt == kE4M3) hipLaunchKernelGGL((gemm_kernel<EPI, kE4M3, PART>), dim3(blocks), dim3(kThreads), 0, st, p);
-    else hipLaunchKernelGGL((gemm_kernel<EPI, kE5M2, PART>), dim3(blocks), dim3(kThreads), 0, st, p);
+    if (a_fmt == kE4M3) hipLaunchKernelGGL((gemm_kernel<EPI, kE4M3, PART, LAY>), dim3(blocks), dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((gemm_kernel<EPI, kE5M2, PART, LAY>), dim3(blocks), dim3(kThreads), 0, st, p);
 }
 
 bool launch_gemm(const GemmArgs &a, hipStream_t st) {
@@ -534,6 +591,10 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st) {
     // rescaled between the products, which this compiler cannot do on 256 AGPR-resident accumulators without
     // spilling them.)
     if (a.part != 0 && a.epilogue != EPI_STORE) return false;
+    if (a.layout < 0 || a.layout > 2) return false;
+    if (a.layout != 0 && a.epilogue != EPI_STORE && a.epilogue != EPI_SWIGLU_BWD) return false;
+    if (a.epilogue == EPI_SWIGLU_BWD && a.layout == 2) return false;
+    if (a.part != 0 && a.layout == 2) return false;
     if ((a.part == 2) != (a.add != nullptr)) return false;
     if (a.part == 1 && !a.c_f32) return false;
     GemmParams p;
@@ -558,13 +619,24 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st) {
     profile_before(a.part ? 8 + a.part : 2 * a.epilogue + a.a_fmt, st);
     switch (a.epilogue) {
         case EPI_STORE:
-            if (a.part == 1) launch_epi<EPI_STORE, 1>(p, a.a_fmt, blocks, st);
-            else if (a.part == 2) launch_epi<EPI_STORE, 2>(p, a.a_fmt, blocks, st);
-            else launch_epi<EPI_STORE, 0>(p, a.a_fmt, blocks, st);
+            if (a.part == 1) {
+                if (a.layout == 1) launch_epi<EPI_STORE, 1, 1>(p, a.a_fmt, blocks, st);
+                else launch_epi<EPI_STORE, 1, 0>(p, a.a_fmt, blocks, st);
+            } else if (a.part == 2) {
+                if (a.layout == 1) launch_epi<EPI_STORE, 2, 1>(p, a.a_fmt, blocks, st);
+                else launch_epi<EPI_STORE, 2, 0>(p, a.a_fmt, blocks, st);
+            } else {
+                if (a.layout == 2) launch_epi<EPI_STORE, 0, 2>(p, a.a_fmt, blocks, st);
+                else if (a.layout == 1) launch_epi<EPI_STORE, 0, 1>(p, a.a_fmt, blocks, st);
+                else launch_epi<EPI_STORE, 0, 0>(p, a.a_fmt, blocks, st);
+            }
             break;
-        case EPI_SWIGLU: launch_epi<EPI_SWIGLU, 0>(p, a.a_fmt, blocks, st); break;
-        case EPI_SWIGLU_Q: launch_epi<EPI_SWIGLU_Q, 0>(p, a.a_fmt, blocks, st); break;
-        default: launch_epi<EPI_SWIGLU_BWD, 0>(p, a.a_fmt, blocks, st); break;
+        case EPI_SWIGLU: launch_epi<EPI_SWIGLU, 0, 0>(p, a.a_fmt, blocks, st); break;
+        case EPI_SWIGLU_Q: launch_epi<EPI_SWIGLU_Q, 0, 0>(p, a.a_fmt, blocks, st); break;
+        default:
+            if (a.layout == 1) launch_epi<EPI_SWIGLU_BWD, 0, 1>(p, a.a_fmt, blocks, st);
+            else launch_epi<EPI_SWIGLU_BWD, 0, 0>(p, a.a_fmt, blocks, st);
+            break;
     }
     profile_after(st);
     return true;

@@ -77,8 +77,9 @@ struct GemmArgs {
     int epilogue = EPI_STORE;
     int a_fmt = 0;                      // kE4M3 / kE5M2 (B is always E4M3)
     int64_t M = 0, N = 0, K = 0;
-    const uint8_t *A = nullptr;         // [M, K]
-    const uint8_t *B = nullptr;         // [N, K]
+    const uint8_t *A = nullptr;         // [M, K]   (layout 2: stored K-major, [K, M])
+    const uint8_t *B = nullptr;         // [N, K]   (layout 1, 2: stored K-major, [K, N])
+    int layout = 0;                     // 0 = both K-contiguous; 1 = B K-major; 2 = A and B K-major (EPI_STORE, EPI_SWIGLU_BWD)
     const uint8_t *B2 = nullptr;        // EPI_SWIGLU, EPI_SWIGLU_Q: the second weight matrix [N, K]
     // EPI_STORE as one half of a sum of two products run as two launches:
     //   part = 1: C is the fp32 scratch [M, N] that receives this product, scaled (c_f32 = 1)

@@ -297,10 +297,15 @@ static void launch_cast_l(const Loader &ld, const CastArgs &a, hipStream_t st) {
     hipLaunchKernelGGL((cast_kernel<Loader, FMT, CS, TR>), grid, dim3(256), 0, st, ld, a.rows, a.cols, \
                        a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst, a.dst_t)
     if constexpr (std::is_same<Loader, LoadBf16>::value) {
-        if (a.record && !cs && tr) {
-            hipLaunchKernelGGL((cast_kernel<Loader, FMT, false, true, true>), grid, dim3(256), 0, st, ld, a.rows, a.cols,
-                               a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst,
-                               a.dst_t, a.record);
+        if (a.record && !cs) {
+            if (tr)
+                hipLaunchKernelGGL((cast_kernel<Loader, FMT, false, true, true>), grid, dim3(256), 0, st, ld, a.rows, a.cols,
+                                   a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst,
+                                   a.dst_t, a.record);
+            else
+                hipLaunchKernelGGL((cast_kernel<Loader, FMT, false, false, true>), grid, dim3(256), 0, st, ld, a.rows, a.cols,
+                                   a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst,
+                                   a.dst_t, a.record);
             return;
         }
     }

@@ -49,7 +49,6 @@ def run_and_check(name, backward=True, n_samples=192):
     xq_ref, sx_ref, _ = quant.quantize_per_tensor(synth.bf16_to_f32_numpy(inp["x"]), fp8.E4M3)
     x_q = blk.sv("x_q", (T, d), torch.uint8)
     assert sc[0] == sx_ref and np.array_equal(gu.u8(x_q), xq_ref)
-    assert torch.equal(blk.sv("x_qT", (d, T), torch.uint8), x_q.t())
     # weights: scale in full (amax is cheap), codes on sampled rows
     for k, nm, slot in (("W1", "w1_q", 1), ("W2", "w2_q", 2)):
         w = inp[k]
@@ -59,7 +58,6 @@ def run_and_check(name, backward=True, n_samples=192):
         ref = quant.cast_with_scale(synth.bf16_to_f32_numpy(w[rows]), s_ref, fp8.E4M3)
         wq = blk.sv(nm, (f, d), torch.uint8)
         assert np.array_equal(gu.u8(wq[rows.to(gu.DEV)]), ref)
-        assert torch.equal(blk.sv(nm + "T", (d, f), torch.uint8), wq.t())
     w1_q, w2_q = blk.sv("w1_q", (f, d), torch.uint8), blk.sv("w2_q", (f, d), torch.uint8)
     U, G = blk.sv("U", (T, f), torch.bfloat16), blk.sv("G", (T, f), torch.bfloat16)
     # (ii) sampled U, G
@@ -78,7 +76,6 @@ def run_and_check(name, backward=True, n_samples=192):
     assert np.array_equal(s, s_ref) and np.array_equal(gu.f32(blk.sv("sinv", (f,), torch.float32)), sinv_ref)
     h_q = blk.sv("h_q", (T, f), torch.uint8)
     assert bool(((h_q & 0x7F).amax(dim=0) == 0x7E).all())            # every channel fills the format
-    assert torch.equal(blk.sv("h_qT", (f, T), torch.uint8), h_q.t())
     cols = torch.from_numpy(rng.integers(0, f, 48))
     hq_ref = quant.cast_with_scale(gu.f32(h[:, cols.to(gu.DEV)]), s_ref[cols.numpy()][None, :], fp8.E4M3)
     assert np.array_equal(gu.u8(h_q[:, cols.to(gu.DEV)]), hq_ref)
@@ -96,7 +93,6 @@ def run_and_check(name, backward=True, n_samples=192):
     assert sc[3] == sw3_ref
     w3s = (w3[:, cols.numpy()] * sinv_ref[cols.numpy()][None, :]).astype(np.float32)
     assert np.array_equal(gu.u8(w3_q[:, cols.to(gu.DEV)]), quant.cast_with_scale(w3s, sw3_ref, fp8.E4M3))
-    assert torch.equal(blk.sv("w3_qT", (f, d), torch.uint8), w3_q.t())
     del w3
     # sampled y
     sampled_gemm_check(h_q, fp8.E4M3, w3_q, blk.y, 1.0 / float(sc[3]), n_samples, rng, "Y", True)
@@ -107,10 +103,9 @@ def run_and_check(name, backward=True, n_samples=192):
     dyq_ref, sdy_ref, _ = quant.quantize_per_tensor(synth.bf16_to_f32_numpy(inp["dY"]), fp8.E5M2)
     dy_q = blk.wv("dy_q", (T, d), torch.uint8)
     assert wsc[0] == sdy_ref and np.array_equal(gu.u8(dy_q), dyq_ref)
-    dy_qT = blk.wv("dy_qT", (d, T), torch.uint8)
-    assert torch.equal(dy_qT, dy_q.t())
+    dy_qT = dy_q.t()          # the backward reads the row-major tensors K-major: views, not copies
     # sampled dH -> dU, dG through the oracle's SwiGLU derivative
-    w3_qT = blk.sv("w3_qT", (f, d), torch.uint8)
+    w3_qT = w3_q.t()
     dU, dG = blk.wv("dU", (T, f), torch.bfloat16), blk.wv("dG", (T, f), torch.bfloat16)
     mi = torch.from_numpy(rng.integers(0, T, n_samples)); ni = torch.from_numpy(rng.integers(0, f, n_samples))
     acc = (fp8.decode(gu.u8(dy_q[mi.to(gu.DEV)]), fp8.E5M2) * fp8.decode(gu.u8(w3_qT[ni.to(gu.DEV)]), fp8.E4M3)).sum(axis=1)
@@ -127,17 +122,16 @@ def run_and_check(name, backward=True, n_samples=192):
         rows = torch.from_numpy(rng.integers(0, T, 32)).to(gu.DEV)
         q = blk.wv(nm, (T, f), torch.uint8)
         assert np.array_equal(gu.u8(q[rows]), quant.cast_with_scale(gu.f32(src[rows]), np.float32(wsc[slot_s]), fp8.E5M2))
-        assert torch.equal(blk.wv(nm + "T", (f, T), torch.uint8), q.t())
     du_q, dg_q = blk.wv("du_q", (T, f), torch.uint8), blk.wv("dg_q", (T, f), torch.uint8)
-    sampled_gemm_check(du_q, fp8.E5M2, blk.sv("w1_qT", (d, f), torch.uint8), blk.dx,
+    sampled_gemm_check(du_q, fp8.E5M2, w1_q.t(), blk.dx,
                        1.0 / (float(wsc[1]) * float(sc[1])), n_samples, rng, "dX", True,
-                       A2=dg_q, B2=blk.sv("w2_qT", (d, f), torch.uint8), scale2=1.0 / (float(wsc[2]) * float(sc[2])))
-    x_qT = blk.sv("x_qT", (d, T), torch.uint8)
-    sampled_gemm_check(blk.wv("du_qT", (f, T), torch.uint8), fp8.E5M2, x_qT, blk.dW1,
+                       A2=dg_q, B2=w2_q.t(), scale2=1.0 / (float(wsc[2]) * float(sc[2])))
+    x_qT = x_q.t()
+    sampled_gemm_check(du_q.t(), fp8.E5M2, x_qT, blk.dW1,
                        1.0 / (float(wsc[1]) * float(sc[0])), n_samples, rng, "dW1", False)
-    sampled_gemm_check(blk.wv("dg_qT", (f, T), torch.uint8), fp8.E5M2, x_qT, blk.dW2,
+    sampled_gemm_check(dg_q.t(), fp8.E5M2, x_qT, blk.dW2,
                        1.0 / (float(wsc[2]) * float(sc[0])), n_samples, rng, "dW2", False)
-    sampled_gemm_check(dy_qT, fp8.E5M2, blk.sv("h_qT", (f, T), torch.uint8), blk.dW3,
+    sampled_gemm_check(dy_qT, fp8.E5M2, h_q.t(), blk.dW3,
                        1.0 / float(wsc[0]), n_samples, rng, "dW3", False, col_factor=sinv_ref)
     return blk, inp
 

@@ -113,3 +113,35 @@ def test_nan_and_inf_codes_propagate_to_their_rows_only(c_dtype):
     keep = np.ones(M, bool)
     keep[[37, 200]] = False
     assert np.array_equal(got[keep], clean[keep])
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 256, 128), (256, 512, 384), (272, 336, 208), (48, 32, 80), (1024, 768, 1040)])
+@pytest.mark.parametrize("layout", [(0, 1), (1, 1)])
+@pytest.mark.parametrize("a_fmt", [ssg.SSG_E4M3, ssg.SSG_E5M2])
+def test_kmajor_operands_match_the_contiguous_form(M, N, K, layout, a_fmt):
+    """K-major operands (stored [K,M] / [K,N], read through the transposing LDS load) must give the bytes of
+    the K-contiguous form on the same logical operands, for whole tiles, ragged tiles and ragged K -- and the
+    K-contiguous form is the one checked against the oracle above."""
+    rng = np.random.default_rng(M + N + K)
+    a = _codes(rng, a_fmt, (M, K))
+    b = _codes(rng, ssg.SSG_E4M3, (N, K))
+    want = _run(a, a_fmt, b, 3.0, 0.25, ssg.SSG_F32)
+    ak, bk = layout
+    A = gu.dev(torch.from_numpy(np.ascontiguousarray(a.T) if ak else a))
+    B = gu.dev(torch.from_numpy(np.ascontiguousarray(b.T) if bk else b))
+    sa = torch.tensor([3.0], dtype=torch.float32, device=gu.DEV)
+    sb = torch.tensor([0.25], dtype=torch.float32, device=gu.DEV)
+    for c_dtype, tdt in ((ssg.SSG_F32, torch.float32), (ssg.SSG_BF16, torch.bfloat16)):
+        C = torch.empty(M, N, dtype=tdt, device=gu.DEV)
+        ssg.ssg_gemm_fp8_layout(A, a_fmt, ak, B, ssg.SSG_E4M3, bk, M, N, K, sa, sb, C, c_dtype)
+        torch.cuda.synchronize()
+        ref = want if c_dtype == ssg.SSG_F32 else torch.from_numpy(want).to(torch.bfloat16).float().numpy()
+        assert np.array_equal(gu.f32(C), ref)
+
+
+def test_kmajor_unsupported_combination_is_refused():
+    t = torch.zeros(256 * 256, dtype=torch.uint8, device=gu.DEV)
+    c = torch.zeros(256, 256, device=gu.DEV)
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_gemm_fp8_layout(t, ssg.SSG_E4M3, 1, t, ssg.SSG_E4M3, 0, 256, 256, 256, None, None, c, ssg.SSG_F32)
+    assert e.value.status == ssg.SSG_ERR_UNSUPPORTED

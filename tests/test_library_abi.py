@@ -32,8 +32,10 @@ def test_sizes_and_descriptor_validation():
     d = ssg.make_desc(256, 256, 688)
     saved, work = ssg.ssg_mlp_saved_bytes(d), ssg.ssg_mlp_workspace_bytes(d)
     T, dm, f = 256, 256, 688
-    assert saved >= 2 * T * dm + 4 * f * dm + 4 * T * f + 2 * T * f + 2 * f * dm
-    assert work >= 2 * T * dm + 4 * T * f + 4 * T * f
+    # saved: x^, w1^, w2^, w3~ and h^ codes (row-major only), bf16 U and G
+    assert saved >= T * dm + 3 * f * dm + T * f + 4 * T * f
+    # workspace: dY^, dU^, dG^ codes, bf16 dU and dG, the fp32 first product of dX
+    assert work >= T * dm + 2 * T * f + 4 * T * f + 4 * T * dm
     assert saved % 256 == 0 and work % 256 == 0
     assert ssg.ssg_mlp_saved_bytes(ssg.make_desc(250, 256, 688)) == 0        # T not a multiple of 16
     assert "multiples of 16" in ssg.ssg_last_error()
