@@ -27,18 +27,19 @@ if ROOT not in sys.path:
 
 PEAK_FP8_TFLOPS = 5000.0          # MI355X dense FP8 MFMA peak (published: 5.0 PFLOP/s)
 METRIC = "FP8 Smooth-SwiGLU MLP fwd+bwd TFLOP/s (7B shape), % of FP8 MFMA peak"
-# tag of ssg_profile_read -> kernel symbol as rocprofv3 prints it (template args: epilogue, A format, part of a two-launch sum);
+# tag of ssg_profile_read -> kernel symbol as rocprofv3 prints it (template args: epilogue, A format, part of a two-launch sum, operand layout: 0 = both K-contiguous,
+# 1 = B K-major, 2 = A and B K-major);
 # the input gradient is two launches (the second adds the first's fp32 result)
-TAG_NAMES = {0: "gemm_kernel<0, 0, 0>", 1: "gemm_kernel<0, 1, 0>", 2: "gemm_kernel<1, 0, 0>",
-             5: "gemm_kernel<2, 1, 0>", 9: "gemm_kernel<0, 1, 1>", 10: "gemm_kernel<0, 1, 2>"}
+TAG_NAMES = {0: "gemm_kernel<0, 0, 0, 0>", 1: "gemm_kernel<0, 1, 0, 2>", 2: "gemm_kernel<1, 0, 0, 0>",
+             5: "gemm_kernel<2, 1, 0, 1>", 9: "gemm_kernel<0, 1, 1, 1>", 10: "gemm_kernel<0, 1, 2, 1>"}
 TAG_ROLES = {0: "y = h^ w3~^T", 1: "dW3, dW1, dW2", 2: "U, G + SwiGLU + channel maxima", 5: "dH + SwiGLU backward",
              9: "dX, first product (to fp32 scratch)", 10: "dX, second product + scratch"}
 
-# L2<->memory bytes per launch of the dominant kernel (gemm_kernel<0, 1, 0>: dW3, dW1, dW2) from two
+# L2<->memory bytes per launch of the dominant kernel (gemm_kernel<0, 1, 0, 2>: dW3, dW1, dW2) from two
 # rocprofv3 --pmc runs of this command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
 # reads for a 1 GiB copy (factors 2.000 and 1.000); see profiles/bench_7b_hbm_traffic.txt.  Algorithmic
 # bytes of that launch: 61.9 MB of FP8 operands read + 180.4 MB of fp32 written.
-MEASURED_TRAFFIC_BYTES = {"gemm_kernel<0, 1, 0>": 329.4e6 + 191.6e6}
+MEASURED_TRAFFIC_BYTES = {"gemm_kernel<0, 1, 0, 2>": 329.4e6 + 191.6e6}
 
 
 def gemm_flops_by_tag(T, d, f):

@@ -170,11 +170,17 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
 
     // DMA slots: a unit is 32 instructions of 1 KB, 8 per wave.  K-contiguous operand: an instruction is 8 rows x
     // 128 B (rows (8w+j)*8 + l/8).  K-major operand: 4 rows of K x 256 B (K rows (8w+j)*4 + l/16); the sixteen
-    // 16-byte chunks of a row are XOR-permuted by kmaj_swz(k) so that the transposing reads, which touch eight
-    // consecutive K rows of one chunk column for each of the two K groups, spread over all banks.
+    // 16-byte chunks of a row are permuted so that a transposing read is free of bank conflicts: chunk c of K row k
+    // sits at position c ^ (k & 7) ^ (((c & 1) ^ (k >> 5 & 1)) << 3).  The 32 lanes of one K group read eight
+    // consecutive K rows of two adjacent chunks: the XOR with k & 7 spreads the rows over the eight positions of a
+    // half row, the chunk's own low bit picks the half, so the 32 words cover all 64 banks exactly once.
     const int lrow = l >> 3;
     const int chunk_even = (l & 7) ^ swz(lrow), chunk_odd = (l & 7) ^ swz(8 + lrow);
-    auto kmaj_swz = [](int k) { return (k & 7) | (((k >> 5) & 1) << 3); };
+    // the chunk that belongs at position `pos` of K row k (the map is its own inverse in the low three bits)
+    auto kmaj_chunk = [](int k, int pos) {
+        const int low = (pos ^ k) & 7;
+        return low | ((((pos >> 3) ^ (k >> 5) ^ low) & 1) << 3);
+    };
     uint32_t a_lane[8], b_lane[8];
     const uint8_t *b_src = p.B;
 #pragma unroll
@@ -182,7 +188,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         const int row = (w * 8 + j) * 8 + lrow;
         const int ck = ((j & 1) ? chunk_odd : chunk_even) * 16;
         const int kr = (w * 8 + j) * 4 + (l >> 4);                     // K-major: K row of this lane's chunk
-        const int ckm = ((l & 15) ^ kmaj_swz(kr)) * 16;                 //          and the chunk it fetches
+        const int ckm = kmaj_chunk(kr, l & 15) * 16;                    //          and the chunk it fetches
         if (AKM) {
             a_lane[j] = (uint32_t)((int64_t)kr * p.M + m0) + ckm;
         } else {
@@ -220,8 +226,12 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         const int g16 = l >> 4, kg = g16 >> 1, g1 = g16 & 1, t = (l & 15) >> 1, e = l & 1;
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) {
-            tr_a[rb] = (uint32_t)((kg * 32 + t) * 256 + (((wm * 8 + rb * 2 + g1) ^ (t | (kg << 3))) << 4) + e * 8);
-            tr_b[rb] = (uint32_t)((kg * 32 + t) * 256 + (((wn * 8 + rb * 2 + g1) ^ (t | (kg << 3))) << 4) + e * 8);
+            // position of chunk c in K row k = kg * 32 + t (+ multiples of 8 and 64, which do not enter)
+            const int ca = wm * 8 + rb * 2 + g1, cb = wn * 8 + rb * 2 + g1;
+            const int pa = ((ca ^ t) & 7) | ((((ca >> 3) ^ kg ^ ca) & 1) << 3);
+            const int pb = ((cb ^ t) & 7) | ((((cb >> 3) ^ kg ^ cb) & 1) << 3);
+            tr_a[rb] = (uint32_t)((kg * 32 + t) * 256 + (pa << 4) + e * 8);
+            tr_b[rb] = (uint32_t)((kg * 32 + t) * 256 + (pb << 4) + e * 8);
         }
     }
     const uint32_t a_wave_base = (uint32_t)(wm * 128) * BK;
@@ -257,7 +267,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
             for (int j = 0; j < 8; ++j) {
                 if (kmajor) {
                     const int kr = (w * 8 + j) * 4 + (l >> 4);
-                    const int64_t col = (is_b ? n0 : m0) + (((l & 15) ^ kmaj_swz(kr)) * 16);
+                    const int64_t col = (is_b ? n0 : m0) + kmaj_chunk(kr, l & 15) * 16;
                     const int64_t ld = is_b ? p.N : p.M;
                     const bool ok = kbase + kr < Kseg && col < ld;      // extents are multiples of 16: a chunk is all in or out
                     dma16(ok ? base + (kbase + kr) * ld + col : zero, dst + j * 1024);
