@@ -184,7 +184,8 @@ typedef struct {
 typedef struct {
     const float *scales;     /* [0]=sdy [1]=sdu [2]=sdg [3]=amax_dy [4]=amax_du [5]=amax_dg ([3..5]: current scaling only) */
     const uint8_t *dy_q, *du_q, *dg_q;                   /* [T,d], [T,f], [T,f] */
-    const void *dU, *dG;                                 /* bf16 [T,f] */
+    const void *dU, *dG;                                 /* bf16 [T,f]; not written under SSG_SCALE_DELAYED, where
+                                                            the dH epilogue emits the E5M2 codes directly */
 } ssg_mlp_workspace_view;
 ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_mlp_saved_view *out);
 ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspace, ssg_mlp_workspace_view *out);

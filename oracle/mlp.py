@@ -193,14 +193,16 @@ class Backward:
 
 
 def backward(fw: Forward, dY, *, dx_dtype: str = "bf16", dw_dtype: str = "f32",
-             stored_dU_dG=None, scales=None) -> Backward:
+             stored_dU_dG=None, scales=None, stored_codes=None) -> Backward:
     """Gradients of sum(Y * dY) with respect to x, W1, W2, W3.
 
     ``stored_dU_dG`` = (dU, dG), bf16-valued arrays: continue from step 10 with
     these stored activations' gradients instead of the ones step 9 produced.
     Tests use it to check the later steps on identical inputs when an earlier
     step differed from another implementation by a bf16 rounding.
-    ``scales`` may give the per-tensor scales of "dy", "du", "dg" (delayed scaling)."""
+    ``scales`` may give the per-tensor scales of "dy", "du", "dg" (delayed scaling).
+    ``stored_codes`` = (du_q, dg_q): continue from step 11 with these E5M2 codes (their scales
+    must be in ``scales``), for implementations that never store the bf16 gradients."""
     bw = Backward()
     given = scales or {}
     bw.amax = {}
@@ -237,6 +239,8 @@ def backward(fw: Forward, dY, *, dx_dtype: str = "bf16", dw_dtype: str = "f32",
     # 10. two tensors, two E5M2 scales
     bw.du_q, bw.sdu, bw.amax["du"] = quant.quantize_per_tensor(bw.dU, fp8.E5M2, scale=given.get("du"))
     bw.dg_q, bw.sdg, bw.amax["dg"] = quant.quantize_per_tensor(bw.dG, fp8.E5M2, scale=given.get("dg"))
+    if stored_codes is not None:
+        bw.du_q, bw.dg_q = (np.asarray(v, np.uint8) for v in stored_codes)
     sdu, sdg = np.float64(bw.sdu), np.float64(bw.sdg)
     sx, sw1, sw2 = np.float64(fw.sx), np.float64(fw.sw1), np.float64(fw.sw2)
     # 11. input gradient: two contractions over the channel index

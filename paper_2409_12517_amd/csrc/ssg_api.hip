@@ -731,13 +731,20 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     // plain block: dH = acc / (sdy sw3), no channel factor
     g.col_scale = desc->smooth ? s : nullptr;
     g.U = sv + L.U; g.G = sv + L.G; g.C = wk + Wl.dU; g.C2 = wk + Wl.dG; g.amax_bits = part_du; g.amax_bits2 = part_dg;
+    if (delayed) {
+        // the scales of dU, dG are known beforehand: the epilogue writes their E5M2 codes directly (a11 is fused
+        // away; bf16 dU, dG are not stored) and still folds their ranges for the history
+        g.epilogue = ssg::EPI_SWIGLU_BWD_Q;
+        g.C = wk + Wl.du_q; g.C2 = wk + Wl.dg_q;
+        g.q_scale = state_scale(4); g.q_scale2 = state_scale(5); g.q_scale_out = wsc + W_SDU; g.q_scale_out2 = wsc + W_SDG;
+    }
     if (!ssg::launch_gemm(g, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
 
     // a11: two tensors, two E5M2 scales (their ranges came out of the epilogue above either way)
-    auto cast_grad = [&](const void *src, float *amax_slots, float *amax_out, float *scale_out, int k, uint8_t *dst) {
+    auto cast_grad = [&](const void *src, float *amax_slots, float *amax_out, float *scale_out, uint8_t *dst) {
+        if (delayed) return;             // done in the epilogue above
         c.kind = ssg::SRC_BF16; c.rows = T; c.cols = f; c.src = src; c.scale_out = scale_out; c.dst = dst;
-        if (delayed) { c.amax = nullptr; c.amax_out = nullptr; c.scale_in = state_scale(k); }
-        else { c.amax = amax_slots; c.amax_out = amax_out; c.scale_in = nullptr; }
+        c.amax = amax_slots; c.amax_out = amax_out; c.scale_in = nullptr;
         ssg::launch_cast(c, st);
     };
     // a12: dW3[j,i] = sinv_i * sum_t dY^[t,j] h^[t,i] / sdy   (plain: / (sdy * sigma_h))
@@ -763,8 +770,8 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     g5b = g5a; g5b.A = wk + Wl.dg_q; g5b.sa = wsc + W_SDG; g5b.C = dW2;
 #define SSG_GEMM(g) do { if (!ssg::launch_gemm(g, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__); } while (0)
     // (running each cast right before the GEMMs that read its output, or dW3 first, measured the same within 0.3 %)
-    cast_grad(wk + Wl.dU, reinterpret_cast<float *>(part_du), wsc + W_AMAX_DU, wsc + W_SDU, 4, wk + Wl.du_q);
-    cast_grad(wk + Wl.dG, reinterpret_cast<float *>(part_dg), wsc + W_AMAX_DG, wsc + W_SDG, 5, wk + Wl.dg_q);
+    cast_grad(wk + Wl.dU, reinterpret_cast<float *>(part_du), wsc + W_AMAX_DU, wsc + W_SDU, wk + Wl.du_q);
+    cast_grad(wk + Wl.dG, reinterpret_cast<float *>(part_dg), wsc + W_AMAX_DG, wsc + W_SDG, wk + Wl.dg_q);
     SSG_GEMM(g3); SSG_GEMM(g4a); SSG_GEMM(g4b); SSG_GEMM(g5a); SSG_GEMM(g5b);
 #undef SSG_GEMM
     if (state) {

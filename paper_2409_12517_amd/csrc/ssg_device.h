@@ -69,6 +69,31 @@ __device__ __forceinline__ uint32_t satcast_pk4(float a, float b, float c, float
     return satcast_pk2<FMT>(a, b) | (satcast_pk2<FMT>(c, d) << 16);
 }
 
+// The same for eight values in ALU-bound epilogues: one NaN test for all eight (x - x is 0 for every finite x and
+// NaN for NaN and infinities, and NaN is sticky through the sum), and the per-element NaN patch only when it fires.
+template <int FMT>
+__device__ __forceinline__ uint2 satcast_pk8(const float (&v)[8]) {
+    float probe = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) probe += v[k] - v[k];
+    if (__builtin_expect(probe != probe, 0))
+        return make_uint2(satcast_pk4<FMT>(v[0], v[1], v[2], v[3]), satcast_pk4<FMT>(v[4], v[5], v[6], v[7]));
+    constexpr float fmax = Fp8Traits<FMT>::fmax;
+    uint32_t w[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const float a = __builtin_amdgcn_fmed3f(v[4 * h], -fmax, fmax), b = __builtin_amdgcn_fmed3f(v[4 * h + 1], -fmax, fmax);
+        const float c = __builtin_amdgcn_fmed3f(v[4 * h + 2], -fmax, fmax), d = __builtin_amdgcn_fmed3f(v[4 * h + 3], -fmax, fmax);
+        if (FMT == kE4M3)
+            w[h] = ((uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false) & 0xffffu) |
+                   ((uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(c, d, 0, false) << 16);
+        else
+            w[h] = ((uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(a, b, 0, false) & 0xffffu) |
+                   ((uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(c, d, 0, false) << 16);
+    }
+    return make_uint2(w[0], w[1]);
+}
+
 // SwiGLU neuron of Section 4.1 in fp32: u * Swish(g), Swish(g) = g * sigma(g).
 // Every operation is a single rounded fp32 operation in a fixed order so that
 // the GEMM epilogue and the stand-alone pass produce identical bits.

@@ -24,6 +24,7 @@
 //   SWIGLU_BWD  acc -> dH (times the channel factor s_i), reads bf16 U, G, stores
 //               bf16 dU, dG and folds their amax.
 //   SWIGLU_Q    as SWIGLU, but stores only the E4M3 cast of u * Swish(g) (inference form).
+//   SWIGLU_BWD_Q as SWIGLU_BWD, but dU, dG leave as E5M2 codes under given scales (delayed scaling).
 #include "ssg_device.h"
 #include "ssg_internal.h"
 
@@ -67,6 +68,8 @@ struct GemmParams {
     int tl_slot;
     float *tmp;          // fp32 [M, N] scratch for the two-launch form of a sum of two products (may be null)
     const float *add;    // gemm_kernel<.., ADD>: fp32 [M, N] added before the store
+    const float *q_scale, *q_scale2;        // EPI_SWIGLU_BWD_Q: scales of dU, dG
+    float *q_scale_out, *q_scale_out2;      //                   where the scales used are recorded
 };
 
 // An LDS row holds the 128 bytes (eight 16-byte chunks, one full cache line) of one matrix row for one
@@ -155,6 +158,7 @@ template <int EPI, int AFMT, int PART = 0, int LAY = 0>
 __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     constexpr bool ADD = PART == 2;
     constexpr bool AKM = LAY == 2, BKM = LAY >= 1;
+    constexpr bool kBwd = EPI == EPI_SWIGLU_BWD || EPI == EPI_SWIGLU_BWD_Q;     // dH -> dU, dG through the SwiGLU derivative
     static_assert(!(BKM && (EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_Q)), "the dual-B forms take K-contiguous operands");
     constexpr bool kDual = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_Q;     // B tile = 128 rows of W1 + 128 rows of W2
     __shared__ __attribute__((aligned(1024))) uint8_t smem[kUnits * kUnitBytes];
@@ -433,7 +437,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         }
     };
 
-    if (EPI == EPI_STORE || EPI == EPI_SWIGLU_BWD) {
+    if (EPI == EPI_STORE || kBwd) {
         // lane -> (row of the slab in 8 passes of 4 rows, 8 columns c8 of the wave's 128)
         const int c8 = (l & 15) * 8;
         const int64_t col = n0 + wn * 128 + c8;
@@ -449,9 +453,14 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         // running |.| maxima of the stored dU, dG as floats: rounding to bf16 is monotone, so the
         // maximum of the rounded values is the rounded maximum (taken once, at the end); fmaxf drops NaN
         float du_maxf = 0.0f, dg_maxf = 0.0f;
+        float q_su = 1.0f, q_sg = 1.0f;
+        if (EPI == EPI_SWIGLU_BWD_Q) {
+            q_su = *p.q_scale; q_sg = *p.q_scale2;
+            if (blockIdx.x == 0 && tid == 0) { *p.q_scale_out = q_su; *p.q_scale_out2 = q_sg; }
+        }
         uint4 ru[2][8], rg[2][8];
         auto fetch_ug = [&](int mb) {                  // the slab's stored U, G (or addend): rows in 8 passes of 4
-            if (EPI != EPI_SWIGLU_BWD && !ADD) return;
+            if (!kBwd && !ADD) return;
 #pragma unroll
             for (int pass = 0; pass < 8; ++pass) {
                 const int64_t row = m0 + wm * 128 + mb * 32 + pass * 4 + (l >> 4);
@@ -506,14 +515,29 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                         du_maxf = fmaxf(du_maxf, fabsf(du[k]));
                         dg_maxf = fmaxf(dg_maxf, fabsf(dg[k]));
                     }
-                    *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = pack_bf16x8(du);
-                    *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C2) + at) = pack_bf16x8(dg);
+                    const uint4 qu = pack_bf16x8(du), qg = pack_bf16x8(dg);
+                    if (EPI == EPI_SWIGLU_BWD_Q) {
+                        // delayed scaling: the scales are known beforehand, so the bf16 values (formed only to
+                        // round as the stored-tensor path does) go straight to E5M2 codes
+                        unpack_bf16x8(qu, du);
+                        unpack_bf16x8(qg, dg);
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            du[k] = __fmul_rn(du[k], q_su);
+                            dg[k] = __fmul_rn(dg[k], q_sg);
+                        }
+                        *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(p.C) + at) = satcast_pk8<kE5M2>(du);
+                        *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(p.C2) + at) = satcast_pk8<kE5M2>(dg);
+                    } else {
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = qu;
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C2) + at) = qg;
+                    }
                 }
             }
         }
         // bf16 bits of the rounded maxima (an infinite maximum, 0x7f80, is kept; NaN never enters)
         uint32_t du_max = pack_bf16x2(du_maxf, 0.0f) & 0x7fffu, dg_max = pack_bf16x2(dg_maxf, 0.0f) & 0x7fffu;
-        if (EPI == EPI_SWIGLU_BWD) {
+        if (kBwd) {
             du_max = wave_max_u32(du_max);
             dg_max = wave_max_u32(dg_max);
             uint32_t *red = reinterpret_cast<uint32_t *>(smem + 4 * 32 * kPitch * 4);   // past the staging patches
@@ -557,8 +581,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                     float h[8];
 #pragma unroll
                     for (int k = 0; k < 8; ++k) h[k] = swiglu_f32(u[k], g[k]);
-                    *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(p.C) + at) =
-                        make_uint2(satcast_pk4<kE4M3>(h[0], h[1], h[2], h[3]), satcast_pk4<kE4M3>(h[4], h[5], h[6], h[7]));
+                    *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(p.C) + at) = satcast_pk8<kE4M3>(h);
                     continue;
                 }
                 const uint4 qu = pack_bf16x8(u), qg = pack_bf16x8(g);
@@ -602,8 +625,10 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st) {
     // spilling them.)
     if (a.part != 0 && a.epilogue != EPI_STORE) return false;
     if (a.layout < 0 || a.layout > 2) return false;
-    if (a.layout != 0 && a.epilogue != EPI_STORE && a.epilogue != EPI_SWIGLU_BWD) return false;
-    if (a.epilogue == EPI_SWIGLU_BWD && a.layout == 2) return false;
+    const bool bwd = a.epilogue == EPI_SWIGLU_BWD || a.epilogue == EPI_SWIGLU_BWD_Q;
+    if (a.layout != 0 && a.epilogue != EPI_STORE && !bwd) return false;
+    if (bwd && a.layout == 2) return false;
+    if (a.epilogue == EPI_SWIGLU_BWD_Q && (!a.q_scale || !a.q_scale2 || !a.q_scale_out || !a.q_scale_out2)) return false;
     if (a.part != 0 && a.layout == 2) return false;
     if ((a.part == 2) != (a.add != nullptr)) return false;
     if (a.part == 1 && !a.c_f32) return false;
@@ -616,6 +641,7 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st) {
     p.camax_bits = a.camax_bits; p.amax_bits = a.amax_bits; p.amax_bits2 = a.amax_bits2;
     p.c_f32 = a.c_f32;
     p.add = a.add;
+    p.q_scale = a.q_scale; p.q_scale2 = a.q_scale2; p.q_scale_out = a.q_scale_out; p.q_scale_out2 = a.q_scale_out2;
     p.tl_slot = 0;
 #if SSG_GEMM_TIMELINE
     static int tl_launch = 0;
@@ -626,7 +652,7 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st) {
     p.tiles_n = (int)((a.N + n_per_tile - 1) / n_per_tile);
     const unsigned blocks = (unsigned)p.tiles_m * (unsigned)p.tiles_n;
     // timing tag: 2 * epilogue + A format; the two halves of a sum get 9 and 10
-    profile_before(a.part ? 8 + a.part : 2 * a.epilogue + a.a_fmt, st);
+    profile_before(a.part ? 8 + a.part : 2 * (a.epilogue == EPI_SWIGLU_BWD_Q ? (int)EPI_SWIGLU_BWD : a.epilogue) + a.a_fmt, st);
     switch (a.epilogue) {
         case EPI_STORE:
             if (a.part == 1) {
@@ -643,6 +669,10 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st) {
             break;
         case EPI_SWIGLU: launch_epi<EPI_SWIGLU, 0, 0>(p, a.a_fmt, blocks, st); break;
         case EPI_SWIGLU_Q: launch_epi<EPI_SWIGLU_Q, 0, 0>(p, a.a_fmt, blocks, st); break;
+        case EPI_SWIGLU_BWD_Q:
+            if (a.layout == 1) launch_epi<EPI_SWIGLU_BWD_Q, 0, 1>(p, a.a_fmt, blocks, st);
+            else launch_epi<EPI_SWIGLU_BWD_Q, 0, 0>(p, a.a_fmt, blocks, st);
+            break;
         default:
             if (a.layout == 1) launch_epi<EPI_SWIGLU_BWD, 0, 1>(p, a.a_fmt, blocks, st);
             else launch_epi<EPI_SWIGLU_BWD, 0, 0>(p, a.a_fmt, blocks, st);

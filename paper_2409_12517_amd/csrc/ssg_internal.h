@@ -70,7 +70,9 @@ enum Epilogue {
     EPI_STORE = 0,        // C = acc * alpha [* col_scale[n]]
     EPI_SWIGLU = 1,       // dual B: U, G bf16 stores + per-channel max of |h|
     EPI_SWIGLU_BWD = 2,   // acc -> dH; loads U, G; stores dU, dG bf16 + their amax
-    EPI_SWIGLU_Q = 3      // dual B as EPI_SWIGLU, but stores only the E4M3 cast of u * Swish(g) (C: bytes [M, N])
+    EPI_SWIGLU_Q = 3,     // dual B as EPI_SWIGLU, but stores only the E4M3 cast of u * Swish(g) (C: bytes [M, N])
+    EPI_SWIGLU_BWD_Q = 4  // as EPI_SWIGLU_BWD, but dU, dG leave as E5M2 codes under given scales (C, C2: bytes [M, N]):
+                          // code = satcast(fl32(bf16(dU) * q_scale)); the scales are copied to q_scale_out / q_scale_out2
 };
 
 struct GemmArgs {
@@ -96,6 +98,8 @@ struct GemmArgs {
     uint32_t *camax_bits = nullptr;     // EPI_SWIGLU: [N] running max |h| (float bits)
     uint32_t *amax_bits = nullptr;      // EPI_SWIGLU_BWD: running max |dU| (float bits), kAmaxSlots slots
     uint32_t *amax_bits2 = nullptr;     //                 same for |dG|
+    const float *q_scale = nullptr, *q_scale2 = nullptr;          // EPI_SWIGLU_BWD_Q: scales of dU, dG (device)
+    float *q_scale_out = nullptr, *q_scale_out2 = nullptr;        //                   where the scales used are recorded
 };
 // false (nothing launched): inconsistent arguments (part / add / epilogue)
 bool launch_gemm(const GemmArgs &a, hipStream_t st);

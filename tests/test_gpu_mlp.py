@@ -128,15 +128,36 @@ def check_backward(blk: Block, npi, ref_fw, fw_gpu, smooth=1, scales=None):
     dy_q = gu.u8(blk.wv("dy_q", (T, d), torch.uint8))
     assert wsc[0] == cont.sdy and np.array_equal(dy_q, cont.dy_q)
     assert delayed or wsc[3] == quant.amax(npi["dY"])
-    # stage 2: dU, dG on identical inputs (one GEMM plus the SwiGLU derivative)
-    dU = gu.f32(blk.wv("dU", (T, f), torch.bfloat16)); dG = gu.f32(blk.wv("dG", (T, f), torch.bfloat16))
-    gu.assert_close_gemm(dU, cont.dU, True, "dU"); gu.assert_close_gemm(dG, cont.dG, True, "dG")
-    # stage 3: quantization of the GPU's own dU, dG, bit-exact
-    cont2 = mlp.backward(fw_gpu, npi["dY"], dx_dtype=ydt, dw_dtype=wdt, stored_dU_dG=(dU, dG), scales=scales)
-    assert wsc[1] == cont2.sdu and wsc[2] == cont2.sdg
-    assert delayed or (wsc[4] == quant.amax(dU) and wsc[5] == quant.amax(dG))
-    assert np.array_equal(gu.u8(blk.wv("du_q", (T, f), torch.uint8)), cont2.du_q)
-    assert np.array_equal(gu.u8(blk.wv("dg_q", (T, f), torch.uint8)), cont2.dg_q)
+    if delayed:
+        # Under delayed scaling the dH epilogue emits the E5M2 codes of dU, dG directly (no bf16 tensors exist).
+        # The code is decided from fp32 values accumulated in the matrix core's order, so what is checked is the
+        # value: decode(code) / scale must be a correct E5M2 rounding (half an ulp = 2^-3 relative; half the
+        # smallest subnormal absolute; clipped at the format maximum) of a value within the GEMM bar of the
+        # oracle's bf16 dU, dG -- and the outright decisions must agree almost everywhere.
+        table = fp8.decode_table(fp8.E5M2).astype(np.float64)
+        codes = {}
+        for nm, ref_v, ref_q, sc_given in (("du_q", cont.dU, cont.du_q, float(scales["du"])), ("dg_q", cont.dG, cont.dg_q, float(scales["dg"]))):
+            q = gu.u8(blk.wv(nm, (T, f), torch.uint8))
+            codes[nm] = q
+            got = table[q] / sc_given
+            lim = 57344.0 / sc_given
+            want = np.clip(ref_v, -lim, lim)
+            tol = 2e-3 * np.abs(ref_v).max() + gu.bf16_ulp(ref_v) + 2.0 ** -3 * np.abs(want) * (1 + 1e-6) + 2.0 ** -17 / sc_given
+            assert np.all(np.abs(got - want) <= tol), nm
+            assert (q != ref_q).mean() < 2e-2, (nm, (q != ref_q).mean())
+        assert wsc[1] == np.float32(scales["du"]) and wsc[2] == np.float32(scales["dg"])
+        cont2 = mlp.backward(fw_gpu, npi["dY"], dx_dtype=ydt, dw_dtype=wdt, scales=scales,
+                             stored_codes=(codes["du_q"], codes["dg_q"]))
+    else:
+        # stage 2: dU, dG on identical inputs (one GEMM plus the SwiGLU derivative)
+        dU = gu.f32(blk.wv("dU", (T, f), torch.bfloat16)); dG = gu.f32(blk.wv("dG", (T, f), torch.bfloat16))
+        gu.assert_close_gemm(dU, cont.dU, True, "dU"); gu.assert_close_gemm(dG, cont.dG, True, "dG")
+        # stage 3: quantization of the GPU's own dU, dG, bit-exact
+        cont2 = mlp.backward(fw_gpu, npi["dY"], dx_dtype=ydt, dw_dtype=wdt, stored_dU_dG=(dU, dG), scales=scales)
+        assert wsc[1] == cont2.sdu and wsc[2] == cont2.sdg
+        assert wsc[4] == quant.amax(dU) and wsc[5] == quant.amax(dG)
+        assert np.array_equal(gu.u8(blk.wv("du_q", (T, f), torch.uint8)), cont2.du_q)
+        assert np.array_equal(gu.u8(blk.wv("dg_q", (T, f), torch.uint8)), cont2.dg_q)
     # stage 4: the four gradient GEMMs on identical inputs
     gu.assert_close_gemm(gu.f32(blk.dx), cont2.dX, bf_y, "dX")
     gu.assert_close_gemm(gu.f32(blk.dW1), cont2.dW1, bf_w, "dW1")
