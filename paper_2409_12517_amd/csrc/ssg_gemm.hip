@@ -481,6 +481,28 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         for (int mb = 0; mb < 4; ++mb) {
             if (mb + 1 < 4) fetch_ug(mb + 1);          // one slab ahead: the loads fly while this slab is worked
             stage_slab(mb);
+            if (EPI == EPI_STORE && !ADD && p.c_f32) {
+                // fp32 output: one 16-byte store per lane and pass, consecutive lanes on consecutive 16 bytes, so
+                // every store instruction writes two whole 512-byte row segments
+                const int c4 = (l & 31) * 4;
+                const int64_t col4 = n0 + wn * 128 + c4;
+                float f4[4] = {alpha, alpha, alpha, alpha};
+                if (p.col_scale && col4 < p.N) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) f4[k] = __fmul_rn(alpha, p.col_scale[col4 + k]);
+                }
+#pragma unroll
+                for (int pass = 0; pass < 16; ++pass) {
+                    const int r = pass * 2 + (l >> 5);
+                    const int64_t row = m0 + wm * 128 + mb * 32 + r;
+                    const float4 a = *reinterpret_cast<const float4 *>(stg + r * kPitch + c4);
+                    if (col4 >= p.N || row >= p.M) continue;
+                    float *out = reinterpret_cast<float *>(p.C) + (size_t)row * (size_t)p.N + (size_t)col4;
+                    *reinterpret_cast<float4 *>(out) =
+                        make_float4(__fmul_rn(a.x, f4[0]), __fmul_rn(a.y, f4[1]), __fmul_rn(a.z, f4[2]), __fmul_rn(a.w, f4[3]));
+                }
+                continue;
+            }
 #pragma unroll
             for (int pass = 0; pass < 8; ++pass) {
                 const int r = pass * 4 + (l >> 4);
