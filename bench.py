@@ -39,7 +39,7 @@ TAG_ROLES = {0: "y = h^ w3~^T", 1: "dW3, dW1, dW2", 2: "U, G + SwiGLU + channel 
 # rocprofv3 --pmc runs of this command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
 # reads for a 1 GiB copy (factors 2.000 and 1.000); see profiles/bench_7b_hbm_traffic.txt.  Algorithmic
 # bytes of that launch: 61.9 MB of FP8 operands read + 180.4 MB of fp32 written.
-MEASURED_TRAFFIC_BYTES = {"gemm_kernel<0, 1, 0, 2>": 329.9e6 + 191.6e6}
+MEASURED_TRAFFIC_BYTES = {"gemm_kernel<0, 1, 0, 2>": 318.3e6 + 180.4e6}
 
 
 def gemm_flops_by_tag(T, d, f):
