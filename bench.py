@@ -399,8 +399,8 @@ def main() -> int:
                                            "ms_per_step": dt_dc * 1e3 / args.steps,
                                            "note": "delayed scaling and Q(w1), Q(w2) reused: a later micro-batch of a "
                                                    "training step under the paper's recipe; not the headline"},
-        "config": {"workload": f"{cfg.name}: Llama2-7B MLP fwd+bwd, T={T} d_model={d} d_ffn={f}, Smooth-SwiGLU, "
-                               "current scaling, W1/W2 quantized every step",
+        "config": {"workload": f"{cfg.name}: {'Llama2-7B ' if (d, f) == (4096, 11008) else ''}SwiGLU MLP fwd+bwd, T={T} d_model={d} "
+                               f"d_ffn={f}, Smooth-SwiGLU, current scaling, W1/W2 quantized every step",
                    "T": T, "d_model": d, "d_ffn": f, "seed": cfg.seed},
         "roofline": roofline,
     }
