@@ -132,7 +132,7 @@ typedef struct {
     int32_t y_dtype;         /* ssg_dtype of y and dx */
     int32_t dw_dtype;        /* ssg_dtype of dW1, dW2, dW3 */
     int32_t weights_cached;  /* 1 = W1, W2, W3 are unchanged since an earlier ssg_mlp_fwd that used this same `saved`
-                                buffer: keep its Q(w1), Q(w2), their transposes and scales and W3's per-channel
+                                buffer: keep its Q(w1), Q(w2), their scales and W3's per-channel
                                 ranges instead of recomputing them (quantize once per optimizer step, run many
                                 micro-batches).  0 = quantize the weights in this call. */
     int32_t scale_mode;      /* SSG_SCALE_CURRENT, or SSG_SCALE_DELAYED (needs scaling_state): the per-tensor scales of

@@ -605,8 +605,8 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     ssg::launch_reset(scb, per_call, part, (size_t)((L.h_camax - L.partials) / 4) + (size_t)f,
                       reinterpret_cast<uint32_t *>(w3_camax), cached ? 0 : (size_t)f, st);
 
-    // a1 + a2: per-tensor range (Section 2), then Q (Eq. 2) with the transposed copy the backward
-    // contractions read.  Range and cast of one tensor run back to back so that the second read of
+    // a1 + a2: per-tensor range (Section 2), then Q (Eq. 2); row-major only: the backward contractions
+    // read these tensors K-major.  Range and cast of one tensor run back to back so that the second read of
     // the tensor can still be served from the memory-side cache.
     // Delayed scaling (Section 2): the scale comes from the history in the caller's state and the
     // cast itself records the range it sees, so the stand-alone range pass disappears.
@@ -711,7 +711,7 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     auto state_scale = [&](int k) { return reinterpret_cast<float *>(state + (size_t)k * ssg::kScalingStride); };
     uint32_t *state_dy_slots = state ? state + ssg::kScalingHeaderWords + 3 * ssg::kAmaxSlotWords : nullptr;
 
-    // a9: upstream gradient to E5M2 (Section 6.2), with its transposed copy
+    // a9: upstream gradient to E5M2 (Section 6.2)
     ssg::CastArgs c;
     c.src = dy; c.kind = ssg::SRC_BF16; c.rows = T; c.cols = dm; c.fmt = ssg::kE5M2; c.pow2 = pow2;
     c.amax_slots = ssg::kAmaxSlots; c.scale_out = wsc + W_SDY; c.dst = wk + Wl.dy_q;
