@@ -154,6 +154,10 @@ def mfma_ceiling(ssg, torch, saved_view_bytes, stream):
     """Sustained rate of a register-only MFMA loop (no memory traffic): on one repeated FP8 code, and on
     FP8 codes taken from this workload's quantized x and W1.  The clock under a dense MFMA load follows
     the power the operand data draws, so the second figure is the ceiling a GEMM on this data can approach."""
+    import ctypes
+    probe = ctypes.CDLL(os.path.join(ROOT, "paper_2409_12517_amd", "libssg_probe.so"))     # bench-only library
+    probe.ssg_probe_mfma_rate.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
+                                          ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
     dev = saved_view_bytes[0].device
     ws = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
     out = {}
@@ -167,7 +171,10 @@ def mfma_ceiling(ssg, torch, saved_view_bytes, stream):
         for _ in range(2):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
-            flops = ssg.ssg_probe_mfma_rate(ws, 16000, stream)
+            flops = ctypes.c_double(0.0)
+            rc = probe.ssg_probe_mfma_rate(ws.data_ptr(), ws.numel(), 16000, ctypes.byref(flops), stream.cuda_stream)
+            assert rc == 0, f"ssg_probe_mfma_rate returned {rc}"
+            flops = flops.value
             e1.record(stream)
             e1.synchronize()
             best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)

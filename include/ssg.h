@@ -18,9 +18,17 @@
  *     device memory and keeps no state between calls.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  *     only enqueue work and return; nothing is synchronised.
- *   - A negative return value means no kernel was launched; ssg_last_error()
- *     then returns a description (thread-local, valid until the next call on
- *     that thread).
+ *   - Errors: SSG_ERR_ARG, SSG_ERR_SHAPE, SSG_ERR_WORKSPACE and SSG_ERR_UNSUPPORTED
+ *     are found before anything is enqueued (every argument, buffer size and
+ *     internal launch configuration is checked first), and so is a HIP error that
+ *     was already pending when the call was made (SSG_ERR_HIP, nothing launched;
+ *     the pending error is consumed).  SSG_ERR_HIP after that means one of the
+ *     call's own launches failed: the outputs are then undefined.
+ *     ssg_last_error() returns a description (thread-local, valid until the next
+ *     call on that thread).
+ *   - Buffers whose size the library computes (`saved`, `workspace`, `prepared`)
+ *     are passed with their size in bytes; a buffer smaller than the matching
+ *     *_bytes() query returns SSG_ERR_WORKSPACE.
  *   - Matrix extents that are contracted or vector-accessed (every rows/cols,
  *     T, d, f, M, N, K below) must be positive multiples of 16, otherwise
  *     SSG_ERR_SHAPE; ssg_amax / ssg_quantize accept an extent of 0 as "nothing
@@ -43,7 +51,7 @@ typedef enum {
     SSG_OK = 0,
     SSG_ERR_ARG = -1,          /* null pointer, bad enum, misaligned pointer */
     SSG_ERR_SHAPE = -2,        /* extent not a positive multiple of 16, or too large */
-    SSG_ERR_WORKSPACE = -3,
+    SSG_ERR_WORKSPACE = -3,    /* a caller-allocated buffer is smaller than its *_bytes() query */
     SSG_ERR_HIP = -4,          /* a launch reported an error (text in ssg_last_error) */
     SSG_ERR_UNSUPPORTED = -5
 } ssg_status;
@@ -140,9 +148,21 @@ typedef struct {
                                 scaling", what the runs of Section 6.2 used), so no stand-alone range pass runs;
                                 values beyond the remembered range saturate.  The per-channel factors of
                                 Smooth-SwiGLU and the scale of the folded w3 stay current. */
-    int32_t reserved[2];     /* must be 0 */
+    int32_t h_scale_mode;    /* plain block (smooth = 0) only: SSG_SCALE_CURRENT = the scale of h comes from its own
+                                range; SSG_SCALE_GIVEN = *h_scale is used as it is (a scale from earlier iterations,
+                                Section 2): values beyond the range it allows saturate (Section 3).  Must be
+                                SSG_SCALE_CURRENT when smooth = 1. */
+    int32_t keep_bf16_grads; /* SSG_SCALE_DELAYED only (no effect otherwise): 1 = ssg_mlp_bwd also stores the bf16 dU, dG
+                                that the fused epilogue rounds and casts from (for inspection; under current scaling
+                                they are always stored).  0 = only their E5M2 codes are written. */
     void *scaling_state;     /* device, ssg_mlp_scaling_state_bytes() bytes, or NULL.  When given, every call
                                 (current or delayed) enters the ranges it saw into the history. */
+    const float *h_scale;    /* device, one float: the given scale of h (h_scale_mode = SSG_SCALE_GIVEN), else NULL */
+    uint64_t *h_counters;    /* device, two 64-bit words, or NULL.  When given, ssg_mlp_fwd clears them and the cast of
+                                the SwiGLU product counts into [0] the elements that overflow E4M3 under their scale
+                                (scaled magnitude beyond 464 = 448 plus half the spacing of the top binade: only the
+                                clamp of the saturating cast keeps them finite) and into [1] the nonzero elements
+                                whose code is +-0 (underflow) -- the two failure modes of Section 3. */
 } ssg_mlp_desc;
 
 /* Amax history of delayed scaling.  One state per block instance, kept by the caller across steps,
@@ -162,20 +182,23 @@ ssg_status ssg_mlp_scaling_init(void *scaling_state, void *stream);
 size_t ssg_mlp_saved_bytes(const ssg_mlp_desc *desc);
 size_t ssg_mlp_workspace_bytes(const ssg_mlp_desc *desc);
 
-/* Forward: y = block(x).  x [T,d], W1, W2 [f,d], W3 [d,f] bf16; y [T,d] of y_dtype. */
+/* Forward: y = block(x).  x [T,d], W1, W2 [f,d], W3 [d,f] bf16; y [T,d] of y_dtype.
+ * saved: out, saved_bytes >= ssg_mlp_saved_bytes(desc), else SSG_ERR_WORKSPACE. */
 ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, const void *W2,
-                       const void *W3, void *y, void *saved, void *stream);
+                       const void *W3, void *y, void *saved, size_t saved_bytes, void *stream);
 
 /* Backward of sum(y * dy) with the straight-through estimator through every Q
  * and s_i held constant: dy [T,d] bf16 is quantized to E5M2; dx [T,d] y_dtype;
- * dW1, dW2 [f,d], dW3 [d,f] of dw_dtype. */
-ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *saved, void *dx,
-                       void *dW1, void *dW2, void *dW3, void *workspace, void *stream);
+ * dW1, dW2 [f,d], dW3 [d,f] of dw_dtype.  saved: as the forward call with the same desc left it;
+ * workspace: scratch, workspace_bytes >= ssg_mlp_workspace_bytes(desc); either buffer too small:
+ * SSG_ERR_WORKSPACE. */
+ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *saved, size_t saved_bytes, void *dx,
+                       void *dW1, void *dW2, void *dW3, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Pointers into `saved` / `workspace` for tests and reports (host struct of device pointers). */
 typedef struct {
     const float *scales;     /* [0]=sx [1]=sw1 [2]=sw2 [3]=sw3 [4]=amax_x [5]=amax_w1 [6]=amax_w2 [7]=amax of s^-1*w3
-                                ([4..6] are written under current scaling only) */
+                                [8]=amax of h (plain block only) ([4..6] are written under current scaling only) */
     const float *s, *sinv, *h_camax, *w3_camax;          /* f floats each */
     const uint8_t *x_q, *w1_q, *w2_q, *h_q, *w3_q;       /* [T,d], [f,d], [f,d], [T,f], [d,f]: row-major only; the
                                                             backward reads them K-major, no transposed copies */
@@ -184,8 +207,9 @@ typedef struct {
 typedef struct {
     const float *scales;     /* [0]=sdy [1]=sdu [2]=sdg [3]=amax_dy [4]=amax_du [5]=amax_dg ([3..5]: current scaling only) */
     const uint8_t *dy_q, *du_q, *dg_q;                   /* [T,d], [T,f], [T,f] */
-    const void *dU, *dG;                                 /* bf16 [T,f]; not written under SSG_SCALE_DELAYED, where
-                                                            the dH epilogue emits the E5M2 codes directly */
+    const void *dU, *dG;                                 /* bf16 [T,f]; under SSG_SCALE_DELAYED the dH epilogue emits the
+                                                            E5M2 codes directly and these are written only when
+                                                            desc.keep_bf16_grads = 1 */
 } ssg_mlp_workspace_view;
 ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_mlp_saved_view *out);
 ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspace, ssg_mlp_workspace_view *out);
@@ -200,8 +224,8 @@ ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspac
  * y = h^ w3~^T / sigma_w3.
  * desc: the block's T, d, f, rnd, y_dtype (smooth must be 1, scale_mode current; T may differ from call
  * to call with the same `prepared`).  prepared / workspace: device, caller-owned, sizes from the two
- * queries.  W1, W2 [f,d], W3 [d,f], x [T,d] bf16; s, sinv [f] fp32; y [T,d] y_dtype.  Asynchronous,
- * nothing allocated; a negative status means nothing was launched. */
+ * queries, passed with their sizes in bytes.  W1, W2 [f,d], W3 [d,f], x [T,d] bf16; s, sinv [f] fp32;
+ * y [T,d] y_dtype.  Asynchronous, nothing allocated. */
 typedef struct {
     const float *weight_scales;   /* [0]=scale of w1~ [1]=scale of w2^ [2]=scale of w3~ [4..6] their ranges */
     const uint8_t *w1_q, *w2_q;   /* [f,d] */
@@ -212,9 +236,9 @@ typedef struct {
 size_t ssg_infer_prepared_bytes(const ssg_mlp_desc *desc);
 size_t ssg_infer_workspace_bytes(const ssg_mlp_desc *desc);
 ssg_status ssg_infer_prepare(const ssg_mlp_desc *desc, const void *W1, const void *W2, const void *W3, const float *s,
-                             const float *sinv, void *prepared, void *stream);
-ssg_status ssg_infer_fwd(const ssg_mlp_desc *desc, const void *x, const void *prepared, void *y, void *workspace,
-                         void *stream);
+                             const float *sinv, void *prepared, size_t prepared_bytes, void *stream);
+ssg_status ssg_infer_fwd(const ssg_mlp_desc *desc, const void *x, const void *prepared, size_t prepared_bytes, void *y,
+                         void *workspace, size_t workspace_bytes, void *stream);
 ssg_status ssg_infer_view(const ssg_mlp_desc *desc, const void *prepared, const void *workspace, ssg_infer_view_t *out);
 
 /* ---- Adam with both moments in FP8 (Section 5) -------------------------------
@@ -236,8 +260,7 @@ ssg_status ssg_infer_view(const ssg_mlp_desc *desc, const void *prepared, const 
  * in order (the parity of `step` selects which scalar set is read and which is written).
  * grad: [n] device, grad_dtype SSG_F32 or SSG_BF16.  w: [n] fp32 device, updated in place.
  * w_bf16: optional [n] bf16 device copy of the new weights (NULL to skip).  n: multiple of 16,
- * below 2^40.  All calls are asynchronous on `stream` and allocate nothing; a negative status
- * means nothing was launched. */
+ * below 2^40.  All calls are asynchronous on `stream` and allocate nothing. */
 typedef struct {
     int64_t n;
     float lr, beta1, beta2, eps, weight_decay;
@@ -278,17 +301,6 @@ ssg_status ssg_profile_enable(int max_records);
  * region); tag < 0 = every launch (the default).  Survives ssg_profile_enable. */
 ssg_status ssg_profile_select(int tag);
 int ssg_profile_read(float *ms, int *tags, int cap);
-
-/* ---- matrix-core ceiling probe (optional diagnostic) ---------------------------
- * Launches a register-only loop of v_mfma_f32_32x32x64_f8f6f4 (256 workgroups of 4 waves, 16
- * accumulator blocks per wave, no memory traffic inside the loop): `iters` passes of 16 MFMAs per
- * wave.  The A/B fragments are the first 64 KiB of `workspace` (device; the caller fills them,
- * e.g. with one repeated FP8 code or with random codes -- the sustained clock, and so the rate,
- * depends on the data); a 256 KiB checksum is written after them.  `workspace_bytes` >= 320 KiB.
- * *flops (host, may be NULL) receives the flop count of the launch; the caller times it.
- * The measured rate is the ceiling the GEMMs of this library can approach on such data; it prices
- * them beside the published dense FP8 peak.  Asynchronous; errors as for the other entry points. */
-ssg_status ssg_probe_mfma_rate(void *workspace, size_t workspace_bytes, int iters, double *flops, void *stream);
 
 #ifdef __cplusplus
 }

@@ -192,35 +192,13 @@ class Backward:
     amax: Optional[dict] = None              # ranges of dy, du, dg seen in this call
 
 
-def backward(fw: Forward, dY, *, dx_dtype: str = "bf16", dw_dtype: str = "f32",
-             stored_dU_dG=None, scales=None, stored_codes=None) -> Backward:
-    """Gradients of sum(Y * dY) with respect to x, W1, W2, W3.
-
-    ``stored_dU_dG`` = (dU, dG), bf16-valued arrays: continue from step 10 with
-    these stored activations' gradients instead of the ones step 9 produced.
-    Tests use it to check the later steps on identical inputs when an earlier
-    step differed from another implementation by a bf16 rounding.
-    ``scales`` may give the per-tensor scales of "dy", "du", "dg" (delayed scaling).
-    ``stored_codes`` = (du_q, dg_q): continue from step 11 with these E5M2 codes (their scales
-    must be in ``scales``), for implementations that never store the bf16 gradients."""
+def backward_grad_h(fw: Forward, dY, *, scales=None) -> Backward:
+    """Steps 7-9 of the quantized backward pass: the upstream gradient to E5M2, the gradient at h (one
+    contraction over the model dimension, times the channel factor), and through the SwiGLU product to
+    bf16 dU, dG.  ``scales`` may give the per-tensor scale of "dy" (delayed scaling)."""
     bw = Backward()
     given = scales or {}
     bw.amax = {}
-    if not fw.quantized:
-        dY64 = np.asarray(dY, np.float64)
-        if fw.smooth:
-            # Y = (h*s) @ (W3*sinv)^T with s constant
-            bw.dH = (dY64 @ (fw.W3 * fw.sinv[None, :])) * fw.s[None, :]
-            bw.dW3 = (dY64.T @ (fw.h * fw.s[None, :])) * fw.sinv[None, :]
-        else:
-            bw.dH = dY64 @ fw.W3
-            bw.dW3 = dY64.T @ fw.h
-        bw.dU, bw.dG = swiglu.swiglu_grads(fw.U, fw.G, bw.dH)
-        bw.dX = bw.dU @ fw.W1 + bw.dG @ fw.W2
-        bw.dW1 = bw.dU.T @ fw.x
-        bw.dW2 = bw.dG.T @ fw.x
-        return bw
-
     # 7. upstream gradient to E5M2
     bw.dy_q, bw.sdy, bw.amax["dy"] = quant.quantize_per_tensor(dY, fp8.E5M2, scale=given.get("dy"))
     sdy, sw3 = np.float64(bw.sdy), np.float64(fw.sw3)
@@ -234,13 +212,18 @@ def backward(fw: Forward, dY, *, dx_dtype: str = "bf16", dw_dtype: str = "f32",
     # 9. through the SwiGLU product, from the stored bf16 U and G
     dU, dG = swiglu.swiglu_grads(fw.U, fw.G, bw.dH)
     bw.dU, bw.dG = round_bf16(dU), round_bf16(dG)
-    if stored_dU_dG is not None:
-        bw.dU, bw.dG = (np.asarray(v, np.float64) for v in stored_dU_dG)
+    return bw
+
+
+def backward_operand_grads(fw: Forward, bw: Backward, *, dx_dtype: str = "bf16", dw_dtype: str = "f32",
+                           scales=None) -> Backward:
+    """Steps 10-12: quantize the bf16 dU, dG held in ``bw`` (two tensors, two E5M2 scales; ``scales`` may
+    give "du", "dg"), then the input gradient and the three weight gradients.  Fills and returns ``bw``."""
+    given = scales or {}
+    sdy = np.float64(bw.sdy)
     # 10. two tensors, two E5M2 scales
     bw.du_q, bw.sdu, bw.amax["du"] = quant.quantize_per_tensor(bw.dU, fp8.E5M2, scale=given.get("du"))
     bw.dg_q, bw.sdg, bw.amax["dg"] = quant.quantize_per_tensor(bw.dG, fp8.E5M2, scale=given.get("dg"))
-    if stored_codes is not None:
-        bw.du_q, bw.dg_q = (np.asarray(v, np.uint8) for v in stored_codes)
     sdu, sdg = np.float64(bw.sdu), np.float64(bw.sdg)
     sx, sw1, sw2 = np.float64(fw.sx), np.float64(fw.sw1), np.float64(fw.sw2)
     # 11. input gradient: two contractions over the channel index
@@ -260,3 +243,28 @@ def backward(fw: Forward, dY, *, dx_dtype: str = "bf16", dw_dtype: str = "f32",
     else:
         bw.dW3 = _round_out(acc3 / (sdy * np.float64(fw.sh)), dw_dtype)
     return bw
+
+
+def backward(fw: Forward, dY, *, dx_dtype: str = "bf16", dw_dtype: str = "f32", scales=None) -> Backward:
+    """Gradients of sum(Y * dY) with respect to x, W1, W2, W3.
+
+    ``scales`` may give the per-tensor scales of "dy", "du", "dg" (delayed scaling).  The quantized pass
+    is the two halves above run one after the other."""
+    if not fw.quantized:
+        bw = Backward()
+        bw.amax = {}
+        dY64 = np.asarray(dY, np.float64)
+        if fw.smooth:
+            # Y = (h*s) @ (W3*sinv)^T with s constant
+            bw.dH = (dY64 @ (fw.W3 * fw.sinv[None, :])) * fw.s[None, :]
+            bw.dW3 = (dY64.T @ (fw.h * fw.s[None, :])) * fw.sinv[None, :]
+        else:
+            bw.dH = dY64 @ fw.W3
+            bw.dW3 = dY64.T @ fw.h
+        bw.dU, bw.dG = swiglu.swiglu_grads(fw.U, fw.G, bw.dH)
+        bw.dX = bw.dU @ fw.W1 + bw.dG @ fw.W2
+        bw.dW1 = bw.dU.T @ fw.x
+        bw.dW2 = bw.dG.T @ fw.x
+        return bw
+    bw = backward_grad_h(fw, dY, scales=scales)
+    return backward_operand_grads(fw, bw, dx_dtype=dx_dtype, dw_dtype=dw_dtype, scales=scales)

@@ -36,14 +36,15 @@ EXPORTS = [
     "ssg_mlp_scaling_state_bytes", "ssg_mlp_scaling_init",
     "ssg_infer_prepared_bytes", "ssg_infer_workspace_bytes", "ssg_infer_prepare", "ssg_infer_fwd", "ssg_infer_view",
     "ssg_adam_state_bytes", "ssg_adam_init", "ssg_adam_step", "ssg_adam_view_state",
-    "ssg_profile_enable", "ssg_profile_select", "ssg_profile_read", "ssg_probe_mfma_rate",
+    "ssg_profile_enable", "ssg_profile_select", "ssg_profile_read",
 ]
 
 
 class ssg_mlp_desc(Structure):
     _fields_ = [("T", c_int64), ("d", c_int64), ("f", c_int64), ("smooth", c_int32), ("rnd", c_int32),
                 ("y_dtype", c_int32), ("dw_dtype", c_int32), ("weights_cached", c_int32), ("scale_mode", c_int32),
-                ("reserved", c_int32 * 2), ("scaling_state", c_void_p)]
+                ("h_scale_mode", c_int32), ("keep_bf16_grads", c_int32), ("scaling_state", c_void_p), ("h_scale", c_void_p),
+                ("h_counters", c_void_p)]
 
 
 class ssg_infer_view_t(Structure):
@@ -87,8 +88,8 @@ _lib.ssg_mlp_saved_bytes.argtypes = [POINTER(ssg_mlp_desc)]
 _lib.ssg_mlp_saved_bytes.restype = c_size_t
 _lib.ssg_mlp_workspace_bytes.argtypes = [POINTER(ssg_mlp_desc)]
 _lib.ssg_mlp_workspace_bytes.restype = c_size_t
-_lib.ssg_mlp_fwd.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 7
-_lib.ssg_mlp_bwd.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 8
+_lib.ssg_mlp_fwd.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 6 + [c_size_t, c_void_p]
+_lib.ssg_mlp_bwd.argtypes = [POINTER(ssg_mlp_desc), c_void_p, c_void_p, c_size_t] + [c_void_p] * 5 + [c_size_t, c_void_p]
 _lib.ssg_mlp_view_saved.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_saved_view)]
 _lib.ssg_mlp_view_workspace.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_workspace_view)]
 _lib.ssg_profile_enable.argtypes = [c_int]
@@ -101,15 +102,14 @@ _lib.ssg_infer_prepared_bytes.argtypes = [POINTER(ssg_mlp_desc)]
 _lib.ssg_infer_prepared_bytes.restype = c_size_t
 _lib.ssg_infer_workspace_bytes.argtypes = [POINTER(ssg_mlp_desc)]
 _lib.ssg_infer_workspace_bytes.restype = c_size_t
-_lib.ssg_infer_prepare.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 7
-_lib.ssg_infer_fwd.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 5
+_lib.ssg_infer_prepare.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 6 + [c_size_t, c_void_p]
+_lib.ssg_infer_fwd.argtypes = [POINTER(ssg_mlp_desc), c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_size_t, c_void_p]
 _lib.ssg_infer_view.argtypes = [POINTER(ssg_mlp_desc), c_void_p, c_void_p, POINTER(ssg_infer_view_t)]
 _lib.ssg_adam_state_bytes.argtypes = [c_int64]
 _lib.ssg_adam_state_bytes.restype = c_size_t
 _lib.ssg_adam_init.argtypes = [c_int64, c_void_p, c_void_p]
 _lib.ssg_adam_step.argtypes = [POINTER(ssg_adam_desc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
 _lib.ssg_adam_view_state.argtypes = [c_int64, c_int32, c_void_p, POINTER(ssg_adam_state_view)]
-_lib.ssg_probe_mfma_rate.argtypes = [c_void_p, c_size_t, c_int, POINTER(ctypes.c_double), c_void_p]
 for _n in EXPORTS[2:]:
     if not _n.endswith("_bytes"):          # the size queries return size_t, everything else a status
         getattr(_lib, _n).restype = c_int
@@ -150,12 +150,24 @@ def _stream(stream):
     return stream if isinstance(stream, int) else stream.cuda_stream
 
 
+def _nbytes(t, given=None) -> int:
+    """Size in bytes of a caller-allocated buffer: as given, else that of the tensor backing it."""
+    if given is not None:
+        return int(given)
+    if t is None or isinstance(t, int):
+        return 0
+    return t.numel() * t.element_size()
+
+
 def make_desc(T: int, d: int, f: int, smooth: int = 1, rnd: int = SSG_ROUND_EXACT_DIV,
               y_dtype: int = SSG_BF16, dw_dtype: int = SSG_F32, weights_cached: int = 0,
-              scale_mode: int = SSG_SCALE_CURRENT, scaling_state=None) -> ssg_mlp_desc:
-    """`scaling_state`: a device byte tensor of ssg_mlp_scaling_state_bytes() bytes (kept alive by the caller)."""
-    return ssg_mlp_desc(T, d, f, smooth, rnd, y_dtype, dw_dtype, weights_cached, scale_mode, (c_int32 * 2)(0, 0),
-                        _ptr(scaling_state))
+              scale_mode: int = SSG_SCALE_CURRENT, scaling_state=None, h_scale=None, h_counters=None,
+              keep_bf16_grads: int = 0) -> ssg_mlp_desc:
+    """`scaling_state`: a device byte tensor of ssg_mlp_scaling_state_bytes() bytes; `h_scale`: a device float
+    (plain block, given scale of h); `h_counters`: two device int64 words.  All kept alive by the caller."""
+    return ssg_mlp_desc(T, d, f, smooth, rnd, y_dtype, dw_dtype, weights_cached, scale_mode,
+                        SSG_SCALE_GIVEN if h_scale is not None else SSG_SCALE_CURRENT, keep_bf16_grads,
+                        _ptr(scaling_state), _ptr(h_scale), _ptr(h_counters))
 
 
 def ssg_amax(src, src_dtype, n, amax_dev, stream=None):
@@ -199,14 +211,16 @@ def ssg_mlp_workspace_bytes(desc: ssg_mlp_desc) -> int:
     return _lib.ssg_mlp_workspace_bytes(ctypes.byref(desc))
 
 
-def ssg_mlp_fwd(desc, x, W1, W2, W3, y, saved, stream=None):
+def ssg_mlp_fwd(desc, x, W1, W2, W3, y, saved, stream=None, saved_bytes=None):
+    """`saved` (and `workspace`, `prepared` below) are device tensors whose size in bytes is passed along; give
+    the *_bytes argument to state a size explicitly (needed when the buffer is a raw pointer)."""
     _check(_lib.ssg_mlp_fwd(ctypes.byref(desc), _ptr(x), _ptr(W1), _ptr(W2), _ptr(W3), _ptr(y), _ptr(saved),
-                            _stream(stream)))
+                            _nbytes(saved, saved_bytes), _stream(stream)))
 
 
-def ssg_mlp_bwd(desc, dy, saved, dx, dW1, dW2, dW3, workspace, stream=None):
-    _check(_lib.ssg_mlp_bwd(ctypes.byref(desc), _ptr(dy), _ptr(saved), _ptr(dx), _ptr(dW1), _ptr(dW2), _ptr(dW3),
-                            _ptr(workspace), _stream(stream)))
+def ssg_mlp_bwd(desc, dy, saved, dx, dW1, dW2, dW3, workspace, stream=None, saved_bytes=None, workspace_bytes=None):
+    _check(_lib.ssg_mlp_bwd(ctypes.byref(desc), _ptr(dy), _ptr(saved), _nbytes(saved, saved_bytes), _ptr(dx), _ptr(dW1),
+                            _ptr(dW2), _ptr(dW3), _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream)))
 
 
 def ssg_mlp_view_saved(desc, saved) -> ssg_mlp_saved_view:
@@ -255,13 +269,14 @@ def ssg_infer_workspace_bytes(desc) -> int:
     return int(_lib.ssg_infer_workspace_bytes(ctypes.byref(desc)))
 
 
-def ssg_infer_prepare(desc, W1, W2, W3, s, sinv, prepared, stream=None) -> None:
+def ssg_infer_prepare(desc, W1, W2, W3, s, sinv, prepared, stream=None, prepared_bytes=None) -> None:
     _check(_lib.ssg_infer_prepare(ctypes.byref(desc), _ptr(W1), _ptr(W2), _ptr(W3), _ptr(s), _ptr(sinv),
-                                  _ptr(prepared), _stream(stream)))
+                                  _ptr(prepared), _nbytes(prepared, prepared_bytes), _stream(stream)))
 
 
-def ssg_infer_fwd(desc, x, prepared, y, workspace, stream=None) -> None:
-    _check(_lib.ssg_infer_fwd(ctypes.byref(desc), _ptr(x), _ptr(prepared), _ptr(y), _ptr(workspace), _stream(stream)))
+def ssg_infer_fwd(desc, x, prepared, y, workspace, stream=None, prepared_bytes=None, workspace_bytes=None) -> None:
+    _check(_lib.ssg_infer_fwd(ctypes.byref(desc), _ptr(x), _ptr(prepared), _nbytes(prepared, prepared_bytes), _ptr(y),
+                              _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream)))
 
 
 def ssg_infer_view(desc, prepared, workspace) -> ssg_infer_view_t:
@@ -294,15 +309,6 @@ def ssg_adam_view_state(n: int, step: int, state) -> ssg_adam_state_view:
     v = ssg_adam_state_view()
     _check(_lib.ssg_adam_view_state(n, step, _ptr(state), ctypes.byref(v)))
     return v
-
-
-def ssg_probe_mfma_rate(workspace, iters: int, stream=None) -> float:
-    """Launches the register-only MFMA loop on the operand bytes at the start of `workspace`
-    (a device byte tensor of at least 320 KiB); returns the flop count of the launch."""
-    flops = ctypes.c_double(0.0)
-    _check(_lib.ssg_probe_mfma_rate(_ptr(workspace), workspace.numel() * workspace.element_size(), iters,
-                                    ctypes.byref(flops), _stream(stream)))
-    return flops.value
 
 
 def view_tensor(saved, base_ptr: int, field_ptr: int, shape, dtype):

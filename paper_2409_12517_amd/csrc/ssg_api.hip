@@ -35,6 +35,16 @@ ssg_status check_launch(const char *what) {
     return SSG_OK;
 }
 
+// An error some earlier HIP call of the process left behind would otherwise be reported as this entry
+// point's own launch failure: it is read (which clears it) and reported before anything is enqueued.
+ssg_status check_entry(const char *what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail(SSG_ERR_HIP, "%s: a HIP error was already pending on entry (%s); nothing was launched", what,
+                    hipGetErrorString(e));
+    return SSG_OK;
+}
+
 #define SSG_REQUIRE_PTR(p)                                                                     \
     do {                                                                                       \
         if ((p) == nullptr) return fail(SSG_ERR_ARG, "%s: %s is NULL", __func__, #p);          \
@@ -119,8 +129,16 @@ ssg_status check_desc(const ssg_mlp_desc *d, const char *who) {
         return fail(SSG_ERR_ARG, "%s: SSG_SCALE_DELAYED needs scaling_state", who);
     if (d->scaling_state != nullptr && !aligned16(d->scaling_state))
         return fail(SSG_ERR_ARG, "%s: scaling_state is not 16-byte aligned", who);
-    for (int i = 0; i < 2; ++i)
-        if (d->reserved[i] != 0) return fail(SSG_ERR_ARG, "%s: reserved fields must be 0", who);
+    if (d->h_scale_mode != SSG_SCALE_CURRENT && d->h_scale_mode != SSG_SCALE_GIVEN)
+        return fail(SSG_ERR_ARG, "%s: h_scale_mode must be SSG_SCALE_CURRENT or SSG_SCALE_GIVEN", who);
+    if (d->h_scale_mode == SSG_SCALE_GIVEN) {
+        if (d->smooth) return fail(SSG_ERR_ARG, "%s: a given scale of h applies to the plain block only (smooth = 0)", who);
+        if (d->h_scale == nullptr || (reinterpret_cast<uintptr_t>(d->h_scale) & 3u))
+            return fail(SSG_ERR_ARG, "%s: h_scale_mode = SSG_SCALE_GIVEN needs h_scale (device, 4-byte aligned)", who);
+    }
+    if (d->h_counters != nullptr && (reinterpret_cast<uintptr_t>(d->h_counters) & 7u))
+        return fail(SSG_ERR_ARG, "%s: h_counters is not 8-byte aligned", who);
+    if (d->keep_bf16_grads != 0 && d->keep_bf16_grads != 1) return fail(SSG_ERR_ARG, "%s: keep_bf16_grads must be 0 or 1", who);
     return SSG_OK;
 }
 
@@ -242,7 +260,7 @@ size_t ssg_infer_workspace_bytes(const ssg_mlp_desc *desc) {
 }
 
 ssg_status ssg_infer_prepare(const ssg_mlp_desc *desc, const void *W1, const void *W2, const void *W3, const float *s,
-                             const float *sinv, void *prepared, void *stream) {
+                             const float *sinv, void *prepared, size_t prepared_bytes, void *stream) {
     ssg_status rc = check_infer_desc(desc, "ssg_infer_prepare");
     if (rc != SSG_OK) return rc;
     SSG_REQUIRE_PTR(W1); SSG_REQUIRE_PTR(W2); SSG_REQUIRE_PTR(W3); SSG_REQUIRE_PTR(s); SSG_REQUIRE_PTR(sinv);
@@ -251,6 +269,9 @@ ssg_status ssg_infer_prepare(const ssg_mlp_desc *desc, const void *W1, const voi
     const int64_t dm = desc->d, f = desc->f;
     const int pow2 = desc->rnd == SSG_ROUND_POW2;
     const InferPrepared L = infer_prepared_layout(dm, f);
+    if (prepared_bytes < L.total)
+        return fail(SSG_ERR_WORKSPACE, "ssg_infer_prepare: prepared holds %zu bytes, %zu needed", prepared_bytes, L.total);
+    if ((rc = check_entry("ssg_infer_prepare")) != SSG_OK) return rc;
     uint8_t *b = static_cast<uint8_t *>(prepared);
     float *sc = reinterpret_cast<float *>(b + L.scalars);
     uint32_t *slots = reinterpret_cast<uint32_t *>(b + L.slots);
@@ -275,20 +296,31 @@ ssg_status ssg_infer_prepare(const ssg_mlp_desc *desc, const void *W1, const voi
     return check_launch("ssg_infer_prepare");
 }
 
-ssg_status ssg_infer_fwd(const ssg_mlp_desc *desc, const void *x, const void *prepared, void *y, void *workspace,
-                         void *stream) {
-    ssg_status rc = check_infer_desc(desc, "ssg_infer_fwd");
-    if (rc != SSG_OK) return rc;
-    SSG_REQUIRE_PTR(x); SSG_REQUIRE_PTR(prepared); SSG_REQUIRE_PTR(y); SSG_REQUIRE_PTR(workspace);
-    hipStream_t st = (hipStream_t)stream;
+namespace {
+// The forward of the folded form on a workspace that holds infer_work_layout(T, d, f).total bytes; shared by
+// ssg_infer_fwd.
+ssg_status infer_forward(const char *who, const ssg_mlp_desc *desc, const void *x, const void *prepared, void *y,
+                         uint8_t *wk, hipStream_t st) {
     const int64_t T = desc->T, dm = desc->d, f = desc->f;
     const InferPrepared P = infer_prepared_layout(dm, f);
     const InferWork Wl = infer_work_layout(T, dm, f);
     const uint8_t *pb = static_cast<const uint8_t *>(prepared);
     const float *psc = reinterpret_cast<const float *>(pb + P.scalars);
-    uint8_t *wk = static_cast<uint8_t *>(workspace);
     float *wsc = reinterpret_cast<float *>(wk + Wl.scalars);
     uint32_t *slots = reinterpret_cast<uint32_t *>(wk + Wl.slots);
+    // both inner products, the SwiGLU product and its cast in one kernel: h^ = cast((s_i u_i) Swish(g_i))
+    ssg::GemmArgs g;
+    g.epilogue = ssg::EPI_SWIGLU_Q; g.a_fmt = ssg::kE4M3; g.M = T; g.N = f; g.K = dm;
+    g.A = wk + Wl.x_q; g.B = pb + P.w1_q; g.B2 = pb + P.w2_q; g.sa = wsc + 0; g.sb = psc + 0; g.sb2 = psc + 1;
+    g.C = wk + Wl.h_q;
+    // y = h^ w3~^T / sigma_w3
+    ssg::GemmArgs g2;
+    g2.epilogue = ssg::EPI_STORE; g2.a_fmt = ssg::kE4M3; g2.M = T; g2.N = dm; g2.K = f;
+    g2.A = wk + Wl.h_q; g2.B = pb + P.w3_q; g2.sb = psc + 2; g2.C = y; g2.c_f32 = desc->y_dtype == SSG_F32;
+    if (!ssg::gemm_args_ok(g) || !ssg::gemm_args_ok(g2)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", who);
+    ssg_status rc = check_entry(who);
+    if (rc != SSG_OK) return rc;
+    // the range slots start at zero (a fill kernel, not a memset: the call may be under graph capture)
     ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(wk), (Wl.x_q - Wl.scalars) / 4, 0u, st);
     // x^ = Q(x)
     ssg::launch_amax(x, ssg::SRC_BF16, (size_t)(T * dm), slots, ssg::kAmaxSlots, st);
@@ -297,18 +329,25 @@ ssg_status ssg_infer_fwd(const ssg_mlp_desc *desc, const void *x, const void *pr
     c.amax = reinterpret_cast<float *>(slots); c.amax_slots = ssg::kAmaxSlots; c.amax_out = wsc + 1; c.scale_out = wsc + 0;
     c.dst = wk + Wl.x_q;
     ssg::launch_cast(c, st);
-    // both inner products, the SwiGLU product and its cast in one kernel: h^ = cast((s_i u_i) Swish(g_i))
-    ssg::GemmArgs g;
-    g.epilogue = ssg::EPI_SWIGLU_Q; g.a_fmt = ssg::kE4M3; g.M = T; g.N = f; g.K = dm;
-    g.A = wk + Wl.x_q; g.B = pb + P.w1_q; g.B2 = pb + P.w2_q; g.sa = wsc + 0; g.sb = psc + 0; g.sb2 = psc + 1;
-    g.C = wk + Wl.h_q;
-    if (!ssg::launch_gemm(g, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
-    // y = h^ w3~^T / sigma_w3
-    ssg::GemmArgs g2;
-    g2.epilogue = ssg::EPI_STORE; g2.a_fmt = ssg::kE4M3; g2.M = T; g2.N = dm; g2.K = f;
-    g2.A = wk + Wl.h_q; g2.B = pb + P.w3_q; g2.sb = psc + 2; g2.C = y; g2.c_f32 = desc->y_dtype == SSG_F32;
-    if (!ssg::launch_gemm(g2, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
-    return check_launch("ssg_infer_fwd");
+    ssg::launch_gemm(g, st);
+    ssg::launch_gemm(g2, st);
+    return check_launch(who);
+}
+
+}  // namespace
+
+ssg_status ssg_infer_fwd(const ssg_mlp_desc *desc, const void *x, const void *prepared, size_t prepared_bytes, void *y,
+                         void *workspace, size_t workspace_bytes, void *stream) {
+    ssg_status rc = check_infer_desc(desc, "ssg_infer_fwd");
+    if (rc != SSG_OK) return rc;
+    SSG_REQUIRE_PTR(x); SSG_REQUIRE_PTR(prepared); SSG_REQUIRE_PTR(y); SSG_REQUIRE_PTR(workspace);
+    const size_t need_p = infer_prepared_layout(desc->d, desc->f).total;
+    const size_t need_w = infer_work_layout(desc->T, desc->d, desc->f).total;
+    if (prepared_bytes < need_p)
+        return fail(SSG_ERR_WORKSPACE, "ssg_infer_fwd: prepared holds %zu bytes, %zu needed", prepared_bytes, need_p);
+    if (workspace_bytes < need_w)
+        return fail(SSG_ERR_WORKSPACE, "ssg_infer_fwd: workspace holds %zu bytes, %zu needed", workspace_bytes, need_w);
+    return infer_forward("ssg_infer_fwd", desc, x, prepared, y, static_cast<uint8_t *>(workspace), (hipStream_t)stream);
 }
 
 ssg_status ssg_infer_view(const ssg_mlp_desc *desc, const void *prepared, const void *workspace, ssg_infer_view_t *out) {
@@ -387,18 +426,6 @@ ssg_status ssg_adam_view_state(int64_t n, int32_t step, const void *state, ssg_a
     return SSG_OK;
 }
 
-ssg_status ssg_probe_mfma_rate(void *workspace, size_t workspace_bytes, int iters, double *flops, void *stream) {
-    SSG_REQUIRE_PTR(workspace);
-    const size_t need = ssg::mfma_rate_operand_bytes() + ssg::mfma_rate_sink_bytes();
-    if (workspace_bytes < need)
-        return fail(SSG_ERR_WORKSPACE, "ssg_probe_mfma_rate: workspace of %zu bytes, %zu needed", workspace_bytes, need);
-    if (iters <= 0 || iters > (1 << 24)) return fail(SSG_ERR_ARG, "ssg_probe_mfma_rate: iters %d out of range", iters);
-    if (flops) *flops = ssg::mfma_rate_flops(iters);
-    ssg::launch_mfma_rate(workspace, static_cast<uint8_t *>(workspace) + ssg::mfma_rate_operand_bytes(), iters,
-                          static_cast<hipStream_t>(stream));
-    return check_launch("ssg_probe_mfma_rate");
-}
-
 const char *ssg_last_error(void) { return g_err; }
 const char *ssg_version(void) { return "ssg 0.1 (gfx950)"; }
 
@@ -471,7 +498,10 @@ ssg_status ssg_gemm_fp8_layout(const uint8_t *A, ssg_fp8_format a_fmt, int a_kma
     g.epilogue = ssg::EPI_STORE; g.a_fmt = a_fmt; g.M = M; g.N = N; g.K = K; g.A = A; g.B = B;
     g.layout = a_kmajor ? 2 : (b_kmajor ? 1 : 0);
     g.sa = sa_dev; g.sb = sb_dev; g.C = C; g.c_f32 = c_dtype == SSG_F32;
-    if (!ssg::launch_gemm(g, (hipStream_t)stream)) return fail(SSG_ERR_ARG, "ssg_gemm_fp8: internal GEMM arguments");
+    if (!ssg::gemm_args_ok(g)) return fail(SSG_ERR_ARG, "ssg_gemm_fp8: internal GEMM arguments");
+    ssg_status rc = check_entry("ssg_gemm_fp8");
+    if (rc != SSG_OK) return rc;
+    ssg::launch_gemm(g, (hipStream_t)stream);
     return check_launch("ssg_gemm_fp8");
 }
 
@@ -506,7 +536,7 @@ ssg_status ssg_smooth_swiglu_quantize(const void *U, const void *G, int64_t T, i
     ssg::launch_fill_u32(hmax, 4, 0u, st);
     ssg::launch_col_amax(U, G, ssg::SRC_SWIGLU, T, f, reinterpret_cast<uint32_t *>(camax), st);
     // camax also stands in for the per-channel range of w3 (its product only feeds the sink)
-    ssg::launch_channel_factors(camax, camax, f, smooth, s, sinv, sink, hmax, st);
+    ssg::launch_channel_factors(camax, camax, f, smooth, s, sinv, sink, hmax, nullptr, st);
     ssg::CastArgs a;
     a.src = U; a.src2 = G; a.kind = ssg::SRC_SWIGLU; a.rows = T; a.cols = f; a.fmt = ssg::kE4M3;
     a.col_scale = s; a.dst = h_q; a.dst_t = h_qT;
@@ -581,7 +611,7 @@ ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspac
 }
 
 ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, const void *W2, const void *W3,
-                       void *y, void *saved, void *stream) {
+                       void *y, void *saved, size_t saved_bytes, void *stream) {
     ssg_status rc = check_desc(desc, "ssg_mlp_fwd");
     if (rc != SSG_OK) return rc;
     SSG_REQUIRE_PTR(x); SSG_REQUIRE_PTR(W1); SSG_REQUIRE_PTR(W2); SSG_REQUIRE_PTR(W3);
@@ -590,11 +620,29 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     const int64_t T = desc->T, dm = desc->d, f = desc->f;
     const int pow2 = desc->rnd == SSG_ROUND_POW2;
     const SavedLayout L = saved_layout(*desc);
+    if (saved_bytes < L.total)
+        return fail(SSG_ERR_WORKSPACE, "ssg_mlp_fwd: saved holds %zu bytes, %zu needed (ssg_mlp_saved_bytes)", saved_bytes, L.total);
     uint8_t *b = static_cast<uint8_t *>(saved);
     float *sc = reinterpret_cast<float *>(b + L.scalars);
     uint32_t *scb = reinterpret_cast<uint32_t *>(sc);
     float *h_camax = reinterpret_cast<float *>(b + L.h_camax), *w3_camax = reinterpret_cast<float *>(b + L.w3_camax);
     float *s = reinterpret_cast<float *>(b + L.s), *sinv = reinterpret_cast<float *>(b + L.sinv);
+
+    // every GEMM argument set is built and checked before the first launch
+    // a3 + a4 + first half of a5: both inner products of Eq. 2, bf16 U and G, per-channel max |h|
+    ssg::GemmArgs g;
+    g.epilogue = ssg::EPI_SWIGLU; g.a_fmt = ssg::kE4M3; g.M = T; g.N = f; g.K = dm;
+    g.A = b + L.x_q; g.B = b + L.w1_q; g.B2 = b + L.w2_q;
+    g.sa = sc + S_SX; g.sb = sc + S_SW1; g.sb2 = sc + S_SW2;
+    g.C = b + L.U; g.C2 = b + L.G; g.camax_bits = reinterpret_cast<uint32_t *>(h_camax);
+    // a8: last linear layer.  Smooth: only the scale of w3~ is left; plain: s_i = sigma_h for all i
+    ssg::GemmArgs g2;
+    g2.epilogue = ssg::EPI_STORE; g2.a_fmt = ssg::kE4M3; g2.M = T; g2.N = dm; g2.K = f;
+    g2.A = b + L.h_q; g2.B = b + L.w3_q;
+    g2.sa = desc->smooth ? nullptr : s; g2.sb = sc + S_SW3;
+    g2.C = y; g2.c_f32 = desc->y_dtype == SSG_F32;
+    if (!ssg::gemm_args_ok(g) || !ssg::gemm_args_ok(g2)) return fail(SSG_ERR_ARG, "ssg_mlp_fwd: internal GEMM arguments");
+    if ((rc = check_entry("ssg_mlp_fwd")) != SSG_OK) return rc;
 
     const bool cached = desc->weights_cached != 0;
     // zero the running maxima of this call; with cached weights the slots that belong to W1, W2 and
@@ -604,6 +652,7 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     uint32_t *part_x = part, *part_w1 = part + ssg::kAmaxSlotWords, *part_w2 = part + 2 * ssg::kAmaxSlotWords;
     ssg::launch_reset(scb, per_call, part, (size_t)((L.h_camax - L.partials) / 4) + (size_t)f,
                       reinterpret_cast<uint32_t *>(w3_camax), cached ? 0 : (size_t)f, st);
+    if (desc->h_counters) ssg::launch_fill_u32(reinterpret_cast<uint32_t *>(desc->h_counters), 4, 0u, st);
 
     // a1 + a2: per-tensor range (Section 2), then Q (Eq. 2); row-major only: the backward contractions
     // read these tensors K-major.  Range and cast of one tensor run back to back so that the second read of
@@ -636,21 +685,18 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
         ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
     }
 
-    // a3 + a4 + first half of a5: both inner products of Eq. 2, bf16 U and G, per-channel max |h|
-    ssg::GemmArgs g;
-    g.epilogue = ssg::EPI_SWIGLU; g.a_fmt = ssg::kE4M3; g.M = T; g.N = f; g.K = dm;
-    g.A = b + L.x_q; g.B = b + L.w1_q; g.B2 = b + L.w2_q;
-    g.sa = sc + S_SX; g.sb = sc + S_SW1; g.sb2 = sc + S_SW2;
-    g.C = b + L.U; g.C2 = b + L.G; g.camax_bits = reinterpret_cast<uint32_t *>(h_camax);
-    if (!ssg::launch_gemm(g, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
+    ssg::launch_gemm(g, st);
 
-    // a5: factors s_i, s_i^-1 and the range of s^-1 * w3 (from the per-channel range of w3)
-    ssg::launch_channel_factors(h_camax, w3_camax, f, desc->smooth, s, sinv, scb + S_AMAX_W3S, scb + S_HMAX, st);
+    // a5: factors s_i, s_i^-1 and the range of s^-1 * w3 (from the per-channel range of w3); plain block:
+    // one scale for all of h, from its own range or as the caller gives it
+    ssg::launch_channel_factors(h_camax, w3_camax, f, desc->smooth, s, sinv, scb + S_AMAX_W3S, scb + S_HMAX,
+                                desc->h_scale_mode == SSG_SCALE_GIVEN ? desc->h_scale : nullptr, st);
 
     // a6: h^ = cast(s_i * h), recomputing h from the stored bf16 U, G
     ssg::CastArgs hq;
     hq.src = b + L.U; hq.src2 = b + L.G; hq.kind = ssg::SRC_SWIGLU; hq.rows = T; hq.cols = f; hq.fmt = ssg::kE4M3;
     hq.col_scale = s; hq.dst = b + L.h_q;
+    hq.counters = reinterpret_cast<unsigned long long *>(desc->h_counters);
     ssg::launch_cast(hq, st);
 
     // a7: w3~ = Q(s^-1 * w3)
@@ -660,13 +706,7 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     wq.dst = b + L.w3_q;
     ssg::launch_cast(wq, st);
 
-    // a8: last linear layer.  Smooth: only the scale of w3~ is left; plain: s_i = sigma_h for all i
-    ssg::GemmArgs g2;
-    g2.epilogue = ssg::EPI_STORE; g2.a_fmt = ssg::kE4M3; g2.M = T; g2.N = dm; g2.K = f;
-    g2.A = b + L.h_q; g2.B = b + L.w3_q;
-    g2.sa = desc->smooth ? nullptr : s; g2.sb = sc + S_SW3;
-    g2.C = y; g2.c_f32 = desc->y_dtype == SSG_F32;
-    if (!ssg::launch_gemm(g2, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
+    ssg::launch_gemm(g2, st);
 
     if (state) {
         // enter this call's ranges into the history; the scales written here serve the next call
@@ -683,8 +723,8 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     return check_launch("ssg_mlp_fwd");
 }
 
-ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *saved, void *dx, void *dW1, void *dW2,
-                       void *dW3, void *workspace, void *stream) {
+ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *saved, size_t saved_bytes, void *dx,
+                       void *dW1, void *dW2, void *dW3, void *workspace, size_t workspace_bytes, void *stream) {
     ssg_status rc = check_desc(desc, "ssg_mlp_bwd");
     if (rc != SSG_OK) return rc;
     SSG_REQUIRE_PTR(dy); SSG_REQUIRE_PTR(saved); SSG_REQUIRE_PTR(dx);
@@ -694,6 +734,11 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     const int pow2 = desc->rnd == SSG_ROUND_POW2;
     const SavedLayout L = saved_layout(*desc);
     const WorkLayout Wl = work_layout(*desc);
+    if (saved_bytes < L.total)
+        return fail(SSG_ERR_WORKSPACE, "ssg_mlp_bwd: saved holds %zu bytes, %zu needed (ssg_mlp_saved_bytes)", saved_bytes, L.total);
+    if (workspace_bytes < Wl.total)
+        return fail(SSG_ERR_WORKSPACE, "ssg_mlp_bwd: workspace holds %zu bytes, %zu needed (ssg_mlp_workspace_bytes)",
+                    workspace_bytes, Wl.total);
     const uint8_t *sv = static_cast<const uint8_t *>(saved);
     uint8_t *wk = static_cast<uint8_t *>(workspace);
     const float *sc = reinterpret_cast<const float *>(sv + L.scalars);
@@ -704,26 +749,13 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
 
     uint32_t *wpart = reinterpret_cast<uint32_t *>(wk + Wl.partials);
     uint32_t *part_dy = wpart, *part_du = wpart + ssg::kAmaxSlotWords, *part_dg = wpart + 2 * ssg::kAmaxSlotWords;
-    ssg::launch_fill_u32(wscb, (Wl.partials - Wl.scalars) / 4 + 3 * ssg::kAmaxSlotWords, 0u, st);
 
     const bool delayed = desc->scale_mode == SSG_SCALE_DELAYED;
     uint32_t *state = static_cast<uint32_t *>(desc->scaling_state);
     auto state_scale = [&](int k) { return reinterpret_cast<float *>(state + (size_t)k * ssg::kScalingStride); };
     uint32_t *state_dy_slots = state ? state + ssg::kScalingHeaderWords + 3 * ssg::kAmaxSlotWords : nullptr;
 
-    // a9: upstream gradient to E5M2 (Section 6.2)
-    ssg::CastArgs c;
-    c.src = dy; c.kind = ssg::SRC_BF16; c.rows = T; c.cols = dm; c.fmt = ssg::kE5M2; c.pow2 = pow2;
-    c.amax_slots = ssg::kAmaxSlots; c.scale_out = wsc + W_SDY; c.dst = wk + Wl.dy_q;
-    if (delayed) {
-        c.scale_in = state_scale(3); c.record = state_dy_slots;
-    } else {
-        ssg::launch_amax(dy, ssg::SRC_BF16, (size_t)(T * dm), part_dy, ssg::kAmaxSlots, st);
-        c.amax = reinterpret_cast<float *>(part_dy); c.amax_out = wsc + W_AMAX_DY;
-    }
-    ssg::launch_cast(c, st);
-    c.record = nullptr;
-
+    // every GEMM argument set is built and checked before the first launch
     // a10: dH = s_i * dY^ w3~ / (sdy sw3), then through the SwiGLU product
     ssg::GemmArgs g;
     g.epilogue = ssg::EPI_SWIGLU_BWD; g.a_fmt = ssg::kE5M2; g.M = T; g.N = f; g.K = dm;
@@ -737,16 +769,8 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
         g.epilogue = ssg::EPI_SWIGLU_BWD_Q;
         g.C = wk + Wl.du_q; g.C2 = wk + Wl.dg_q;
         g.q_scale = state_scale(4); g.q_scale2 = state_scale(5); g.q_scale_out = wsc + W_SDU; g.q_scale_out2 = wsc + W_SDG;
+        if (desc->keep_bf16_grads) { g.keep_u = wk + Wl.dU; g.keep_g = wk + Wl.dG; }
     }
-    if (!ssg::launch_gemm(g, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__);
-
-    // a11: two tensors, two E5M2 scales (their ranges came out of the epilogue above either way)
-    auto cast_grad = [&](const void *src, float *amax_slots, float *amax_out, float *scale_out, uint8_t *dst) {
-        if (delayed) return;             // done in the epilogue above
-        c.kind = ssg::SRC_BF16; c.rows = T; c.cols = f; c.src = src; c.scale_out = scale_out; c.dst = dst;
-        c.amax = amax_slots; c.amax_out = amax_out; c.scale_in = nullptr;
-        ssg::launch_cast(c, st);
-    };
     // a12: dW3[j,i] = sinv_i * sum_t dY^[t,j] h^[t,i] / sdy   (plain: / (sdy * sigma_h))
     ssg::GemmArgs g3;
     g3.epilogue = ssg::EPI_STORE; g3.a_fmt = ssg::kE5M2; g3.M = dm; g3.N = f; g3.K = T;
@@ -768,12 +792,42 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     g5a.layout = 2;                                                                    // dU^ [T,f] = [K,M], x^ [T,d] = [K,N]
     g5a.A = wk + Wl.du_q; g5a.B = sv + L.x_q; g5a.sa = wsc + W_SDU; g5a.sb = sc + S_SX; g5a.C = dW1; g5a.c_f32 = dw_f32;
     g5b = g5a; g5b.A = wk + Wl.dg_q; g5b.sa = wsc + W_SDG; g5b.C = dW2;
-#define SSG_GEMM(g) do { if (!ssg::launch_gemm(g, st)) return fail(SSG_ERR_ARG, "%s: internal GEMM arguments", __func__); } while (0)
+    for (const ssg::GemmArgs *a : {&g, &g3, &g4a, &g4b, &g5a, &g5b})
+        if (!ssg::gemm_args_ok(*a)) return fail(SSG_ERR_ARG, "ssg_mlp_bwd: internal GEMM arguments");
+    if ((rc = check_entry("ssg_mlp_bwd")) != SSG_OK) return rc;
+
+    ssg::launch_fill_u32(wscb, (Wl.partials - Wl.scalars) / 4 + 3 * ssg::kAmaxSlotWords, 0u, st);
+
+    // a9: upstream gradient to E5M2 (Section 6.2)
+    ssg::CastArgs c;
+    c.src = dy; c.kind = ssg::SRC_BF16; c.rows = T; c.cols = dm; c.fmt = ssg::kE5M2; c.pow2 = pow2;
+    c.amax_slots = ssg::kAmaxSlots; c.scale_out = wsc + W_SDY; c.dst = wk + Wl.dy_q;
+    if (delayed) {
+        c.scale_in = state_scale(3); c.record = state_dy_slots;
+    } else {
+        ssg::launch_amax(dy, ssg::SRC_BF16, (size_t)(T * dm), part_dy, ssg::kAmaxSlots, st);
+        c.amax = reinterpret_cast<float *>(part_dy); c.amax_out = wsc + W_AMAX_DY;
+    }
+    ssg::launch_cast(c, st);
+    c.record = nullptr;
+
+    ssg::launch_gemm(g, st);
+
+    // a11: two tensors, two E5M2 scales (their ranges came out of the epilogue above either way)
+    auto cast_grad = [&](const void *src, float *amax_slots, float *amax_out, float *scale_out, uint8_t *dst) {
+        if (delayed) return;             // done in the epilogue above
+        c.kind = ssg::SRC_BF16; c.rows = T; c.cols = f; c.src = src; c.scale_out = scale_out; c.dst = dst;
+        c.amax = amax_slots; c.amax_out = amax_out; c.scale_in = nullptr;
+        ssg::launch_cast(c, st);
+    };
     // (running each cast right before the GEMMs that read its output, or dW3 first, measured the same within 0.3 %)
     cast_grad(wk + Wl.dU, reinterpret_cast<float *>(part_du), wsc + W_AMAX_DU, wsc + W_SDU, wk + Wl.du_q);
     cast_grad(wk + Wl.dG, reinterpret_cast<float *>(part_dg), wsc + W_AMAX_DG, wsc + W_SDG, wk + Wl.dg_q);
-    SSG_GEMM(g3); SSG_GEMM(g4a); SSG_GEMM(g4b); SSG_GEMM(g5a); SSG_GEMM(g5b);
-#undef SSG_GEMM
+    ssg::launch_gemm(g3, st);
+    ssg::launch_gemm(g4a, st);
+    ssg::launch_gemm(g4b, st);
+    ssg::launch_gemm(g5a, st);
+    ssg::launch_gemm(g5b, st);
     if (state) {
         ssg::ScalingUpdate u;
         u.pow2 = pow2; u.count = 3;

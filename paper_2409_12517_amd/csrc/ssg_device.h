@@ -11,8 +11,10 @@ constexpr int kE4M3 = 0;
 constexpr int kE5M2 = 1;
 
 template <int FMT> struct Fp8Traits;
-template <> struct Fp8Traits<kE4M3> { static constexpr float fmax = 448.0f; };
-template <> struct Fp8Traits<kE5M2> { static constexpr float fmax = 57344.0f; };
+// overflow_above = fmax plus half the spacing of the top binade: a magnitude beyond it is kept finite only by
+// the clamp of the saturating cast (a value between fmax and it rounds to fmax by itself)
+template <> struct Fp8Traits<kE4M3> { static constexpr float fmax = 448.0f, overflow_above = 464.0f; };
+template <> struct Fp8Traits<kE5M2> { static constexpr float fmax = 57344.0f, overflow_above = 61440.0f; };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 

@@ -35,26 +35,11 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef __attribute__((address_space(1))) const void *global_void_ptr;
 
-#ifndef SSG_GEMM_EXPERIMENT
-#define SSG_GEMM_EXPERIMENT 0   /* timing experiments only (results are wrong): 1 = no DMA after the prologue, 2 = no LDS reads */
-#endif
 constexpr int BM = 256, BN = 256, BK = 128;
 constexpr int kUnitBytes = BM * BK;               // one operand tile of one K step: 256 rows x 128 B = 32 KB
 constexpr int kUnits = 5;                         // ring of operand tiles in LDS: all 160 KB
 
 __device__ uint4 g_zero_chunk = {0u, 0u, 0u, 0u}; // source of the zero fill of a ragged K tail
-
-#ifndef SSG_GEMM_TIMELINE
-#define SSG_GEMM_TIMELINE 0     /* 1: every workgroup stamps its phases (100 MHz clock) into a debug buffer */
-#endif
-#if SSG_GEMM_TIMELINE
-constexpr int kTlLaunches = 8, kTlBlocks = 4096, kTlStamps = 4;
-__device__ unsigned long long g_timeline[kTlLaunches * kTlBlocks * kTlStamps];
-#define SSG_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < kTlBlocks) \
-    g_timeline[((size_t)p.tl_slot * kTlBlocks + blockIdx.x) * kTlStamps + (i)] = wall_clock64(); } while (0)
-#else
-#define SSG_STAMP(i) do { } while (0)
-#endif
 
 struct GemmParams {
     const uint8_t *A, *B, *B2;
@@ -65,11 +50,11 @@ struct GemmParams {
     uint32_t *camax_bits, *amax_bits, *amax_bits2;
     int c_f32;
     int tiles_m, tiles_n;
-    int tl_slot;
     float *tmp;          // fp32 [M, N] scratch for the two-launch form of a sum of two products (may be null)
     const float *add;    // gemm_kernel<.., ADD>: fp32 [M, N] added before the store
     const float *q_scale, *q_scale2;        // EPI_SWIGLU_BWD_Q: scales of dU, dG
     float *q_scale_out, *q_scale_out2;      //                   where the scales used are recorded
+    uint16_t *keep_u, *keep_g;              //                   optional: the bf16 dU, dG the codes were cast from
 };
 
 // An LDS row holds the 128 bytes (eight 16-byte chunks, one full cache line) of one matrix row for one
@@ -85,7 +70,7 @@ __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 __device__ __forceinline__ void dma16(const uint8_t *g, uint32_t lds_addr) {
 #if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(lds_addr), "v"(g) : "memory");
+                 :: "s"(lds_addr), "v"(g) : "memory", "m0");
 #else
     (void)g; (void)lds_addr;
 #endif
@@ -95,7 +80,7 @@ __device__ __forceinline__ void dma16(const uint8_t *g, uint32_t lds_addr) {
 __device__ __forceinline__ void dma16_s(const uint8_t *base_uniform, uint32_t lane_off, uint32_t lds_addr) {
 #if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(lane_off), "s"(base_uniform) : "memory");
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base_uniform) : "memory", "m0");
 #else
     (void)base_uniform; (void)lane_off; (void)lds_addr;
 #endif
@@ -106,11 +91,22 @@ __device__ __forceinline__ v16f mfma(const v8i &a, const v8i &b, const v16f &c) 
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, AFMT, 0, 0, 0, 0, 0);
 }
 
-__device__ __forceinline__ float inv_scale_product(const float *sa, const float *sb) {
-    float p = 1.0f;
-    if (sa) p = *sa;
-    if (sb) p = __fmul_rn(p, *sb);
-    return __fdiv_rn(1.0f, p);
+// The dequantization factor 1 / (sa * sb).  The product of two binary32 scales can leave the binary32 range
+// (the scale of a gradient tensor with a tiny range reaches 1e38) and its reciprocal can fall among the
+// subnormals, so it is formed in binary64 and handed out as a normal binary32 factor `a` (rounded once) times
+// an exact power of two `post`, which is 1 except in those extreme cases.
+struct Dequant { float a, post; };
+__device__ __forceinline__ Dequant inv_scale_product(const float *sa, const float *sb) {
+    double p = 1.0;
+    if (sa) p = (double)*sa;
+    if (sb) p *= (double)*sb;
+    const double r = 1.0 / p;
+    Dequant d;
+    d.post = 1.0f;
+    if (r < 0x1p-100) d.post = 0x1p-96f;
+    else if (r > 0x1p100) d.post = 0x1p96f;
+    d.a = (float)(r / (double)d.post);
+    return d;
 }
 
 // Workgroup -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its
@@ -170,7 +166,6 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     map_tile(p, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM;
     const int64_t n0 = (int64_t)tile_n * (kDual ? BN / 2 : BN);
-    SSG_STAMP(0);
 
     // DMA slots: a unit is 32 instructions of 1 KB, 8 per wave.  K-contiguous operand: an instruction is 8 rows x
     // 128 B (rows (8w+j)*8 + l/8).  K-major operand: 4 rows of K x 256 B (K rows (8w+j)*4 + l/16); the sixteen
@@ -336,8 +331,7 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        SSG_STAMP(1);
-#pragma unroll
+    #pragma unroll
         for (int g = 0; g < 8; ++g) load_frag(0, 0, 1, 0, g);
 
         // Steady state: when every K step is whole, the steps whose new units exist run a body without
@@ -358,19 +352,19 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
 #pragma unroll
             for (int g = 0; g < 8; ++g) {
                 mfma2(0, g);
-                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frag(1, sa, sb, 1, g);
-                if (!(SSG_GEMM_EXPERIMENT & 1)) dma16_s(ua, a_lane[g], d4 + g * 1024);
+                load_frag(1, sa, sb, 1, g);
+                dma16_s(ua, a_lane[g], d4 + g * 1024);
                 __builtin_amdgcn_sched_barrier(0);
             }
             asm volatile("s_waitcnt vmcnt(8)" ::: "memory");       // all but unit 2k+4 have landed
             wait_lds();
-            if (!(SSG_GEMM_EXPERIMENT & 4)) __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int g = 0; g < 8; ++g) {
                 mfma2(1, g);
-                if (!(SSG_GEMM_EXPERIMENT & 2)) load_frag(0, sa_n, sb_n, 0, g);
-                if (!(SSG_GEMM_EXPERIMENT & 1)) dma16_s(ub, b_lane[g], d5 + g * 1024);
+                load_frag(0, sa_n, sb_n, 0, g);
+                dma16_s(ub, b_lane[g], d5 + g * 1024);
                 __builtin_amdgcn_sched_barrier(0);
             }
             sp = sb; sa = sa_n; sb = sb_n;
@@ -403,7 +397,6 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
-    SSG_STAMP(2);
 
     // ---- epilogue: per-wave LDS patch, one 32 x 128 slab (mb) at a time
     constexpr int kPitch = 136;                        // floats; 4 rows apart lands on the other 32 banks
@@ -442,7 +435,9 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         const int c8 = (l & 15) * 8;
         const int64_t col = n0 + wn * 128 + c8;
         const bool col_ok = col < p.N;
-        const float alpha = inv_scale_product(p.sa, p.sb);
+        const Dequant dq = inv_scale_product(p.sa, p.sb);
+        const float alpha = dq.a;
+        const bool post = dq.post != 1.0f;               // wave-uniform, false except for extreme scales
         float f[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) f[k] = alpha;
@@ -498,8 +493,9 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                     const float4 a = *reinterpret_cast<const float4 *>(stg + r * kPitch + c4);
                     if (col4 >= p.N || row >= p.M) continue;
                     float *out = reinterpret_cast<float *>(p.C) + (size_t)row * (size_t)p.N + (size_t)col4;
-                    *reinterpret_cast<float4 *>(out) =
-                        make_float4(__fmul_rn(a.x, f4[0]), __fmul_rn(a.y, f4[1]), __fmul_rn(a.z, f4[2]), __fmul_rn(a.w, f4[3]));
+                    float4 o = make_float4(__fmul_rn(a.x, f4[0]), __fmul_rn(a.y, f4[1]), __fmul_rn(a.z, f4[2]), __fmul_rn(a.w, f4[3]));
+                    if (post) o = make_float4(o.x * dq.post, o.y * dq.post, o.z * dq.post, o.w * dq.post);
+                    *reinterpret_cast<float4 *>(out) = o;
                 }
                 continue;
             }
@@ -513,6 +509,10 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                 const size_t at = (size_t)row * (size_t)p.N + (size_t)col;
 #pragma unroll
                 for (int k = 0; k < 8; ++k) v[k] = __fmul_rn(v[k], f[k]);
+                if (post) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] *= dq.post;
+                }
                 if (ADD) {
                     const uint4 a0 = ru[mb & 1][pass], a1 = rg[mb & 1][pass];
                     const uint32_t aw[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
@@ -550,6 +550,10 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                         }
                         *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(p.C) + at) = satcast_pk8<kE5M2>(du);
                         *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(p.C2) + at) = satcast_pk8<kE5M2>(dg);
+                        if (p.keep_u) {
+                            *reinterpret_cast<uint4 *>(p.keep_u + at) = qu;
+                            *reinterpret_cast<uint4 *>(p.keep_g + at) = qg;
+                        }
                     } else {
                         *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = qu;
                         *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C2) + at) = qg;
@@ -577,8 +581,9 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
         const int c8 = (l & 7) * 8;
         const int64_t col = n0 + wn * 64 + c8;
         const bool col_ok = col < p.N;
-        const float alpha_u = inv_scale_product(p.sa, p.sb);
-        const float alpha_g = inv_scale_product(p.sa, p.sb2);
+        const Dequant dq_u = inv_scale_product(p.sa, p.sb), dq_g = inv_scale_product(p.sa, p.sb2);
+        const float alpha_u = dq_u.a, alpha_g = dq_g.a;
+        const bool post = dq_u.post != 1.0f || dq_g.post != 1.0f;
         float hmaxf[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};   // fmaxf drops NaN
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
@@ -596,6 +601,10 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                 for (int k = 0; k < 8; ++k) {
                     u[k] = __fmul_rn(u[k], alpha_u);
                     g[k] = __fmul_rn(g[k], alpha_g);
+                }
+                if (post) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) { u[k] *= dq_u.post; g[k] *= dq_g.post; }
                 }
                 if (EPI == EPI_SWIGLU_Q) {
                     // inference: the factor s_i is already inside u (folded into w1), so the product is cast as
@@ -631,7 +640,6 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
                 if (hmax[k]) atomicMax(&p.camax_bits[col + k], hmax[k]);
         }
     }
-    SSG_STAMP(3);
 }
 
 template <int EPI, int PART, int LAY>
@@ -640,11 +648,12 @@ static void launch_epi(const GemmParams &p, int a_fmt, unsigned blocks, hipStrea
     else hipLaunchKernelGGL((gemm_kernel<EPI, kE5M2, PART, LAY>), dim3(blocks), dim3(kThreads), 0, st, p);
 }
 
-bool launch_gemm(const GemmArgs &a, hipStream_t st) {
-    // A sum of two products (the input gradient) runs as two launches: part 1 leaves its scaled product as fp32
-    // scratch, part 2 adds it to its own before rounding.  (Inside one kernel the accumulators would have to be
-    // rescaled between the products, which this compiler cannot do on 256 AGPR-resident accumulators without
-    // spilling them.)
+bool gemm_args_ok(const GemmArgs &a) {
+    if (a.epilogue < EPI_STORE || a.epilogue > EPI_SWIGLU_BWD_Q) return false;
+    if (!a.A || !a.B || !a.C || a.M <= 0 || a.N <= 0 || a.K <= 0) return false;
+    const bool dual = a.epilogue == EPI_SWIGLU || a.epilogue == EPI_SWIGLU_Q;
+    if (dual && !a.B2) return false;
+    if (a.epilogue == EPI_SWIGLU && (!a.C2 || !a.camax_bits)) return false;
     if (a.part != 0 && a.epilogue != EPI_STORE) return false;
     if (a.layout < 0 || a.layout > 2) return false;
     const bool bwd = a.epilogue == EPI_SWIGLU_BWD || a.epilogue == EPI_SWIGLU_BWD_Q;
@@ -654,6 +663,17 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st) {
     if (a.part != 0 && a.layout == 2) return false;
     if ((a.part == 2) != (a.add != nullptr)) return false;
     if (a.part == 1 && !a.c_f32) return false;
+    if ((a.keep_u != nullptr) != (a.keep_g != nullptr) || (a.keep_u && a.epilogue != EPI_SWIGLU_BWD_Q)) return false;
+    if (bwd && (!a.U || !a.G || !a.C2 || !a.amax_bits || !a.amax_bits2)) return false;
+    return true;
+}
+
+bool launch_gemm(const GemmArgs &a, hipStream_t st) {
+    // A sum of two products (the input gradient) runs as two launches: part 1 leaves its scaled product as fp32
+    // scratch, part 2 adds it to its own before rounding.  (Inside one kernel the accumulators would have to be
+    // rescaled between the products, which this compiler cannot do on 256 AGPR-resident accumulators without
+    // spilling them.)
+    if (!gemm_args_ok(a)) return false;
     GemmParams p;
     p.A = a.A; p.B = a.B; p.B2 = a.B2;
     p.M = a.M; p.N = a.N; p.K = a.K;
@@ -664,11 +684,7 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st) {
     p.c_f32 = a.c_f32;
     p.add = a.add;
     p.q_scale = a.q_scale; p.q_scale2 = a.q_scale2; p.q_scale_out = a.q_scale_out; p.q_scale_out2 = a.q_scale_out2;
-    p.tl_slot = 0;
-#if SSG_GEMM_TIMELINE
-    static int tl_launch = 0;
-    p.tl_slot = tl_launch++ % kTlLaunches;
-#endif
+    p.keep_u = (uint16_t *)a.keep_u; p.keep_g = (uint16_t *)a.keep_g;
     p.tiles_m = (int)((a.M + BM - 1) / BM);
     const int n_per_tile = (a.epilogue == EPI_SWIGLU || a.epilogue == EPI_SWIGLU_Q) ? BN / 2 : BN;
     p.tiles_n = (int)((a.N + n_per_tile - 1) / n_per_tile);
@@ -705,9 +721,3 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st) {
 }
 
 }  // namespace ssg
-
-#if SSG_GEMM_TIMELINE
-extern "C" int ssg_debug_timeline(unsigned long long *host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(ssg::g_timeline), sizeof(unsigned long long) * (size_t)n);
-}
-#endif

@@ -41,6 +41,8 @@ struct CastArgs {
                                      // (bf16 source, no per-column factor, transposed copy requested)
     uint8_t *dst = nullptr;          // [rows, cols]
     uint8_t *dst_t = nullptr;        // [cols, rows] or null
+    unsigned long long *counters = nullptr;   // optional (no transposed copy): [0] += elements beyond the format's
+                                     // range under the scale (saturated), [1] += nonzero elements cast to +-0
 };
 void launch_cast(const CastArgs &a, hipStream_t st);
 
@@ -50,10 +52,11 @@ void launch_col_amax(const void *src, const void *src2, SrcKind kind, int64_t ro
 
 // Per-channel factors from the per-channel maxima (Section 4.4) and the range
 // of s^-1 * w3 for the folded weight.  smooth = 0: one factor for all channels.
-//   hmax_bits: scratch for the plain mode (zeroed by the caller)
+//   hmax_bits: scratch for the plain mode (zeroed by the caller); receives the tensor's range
+//   h_scale_given: plain mode only, optional device scalar: the scale of h as the caller gives it
 void launch_channel_factors(const float *h_camax, const float *w3_camax, int64_t f, int smooth,
                             float *s, float *sinv, uint32_t *amax_w3s_bits, uint32_t *hmax_bits,
-                            hipStream_t st);
+                            const float *h_scale_given, hipStream_t st);
 
 // amax_bits = max_i fl32(w3_camax[i] * sinv[i]) as float bits (zeroed by the caller).
 void launch_fold_range(const float *w3_camax, const float *sinv, int64_t f, uint32_t *amax_bits, hipStream_t st);
@@ -100,8 +103,12 @@ struct GemmArgs {
     uint32_t *amax_bits2 = nullptr;     //                 same for |dG|
     const float *q_scale = nullptr, *q_scale2 = nullptr;          // EPI_SWIGLU_BWD_Q: scales of dU, dG (device)
     float *q_scale_out = nullptr, *q_scale_out2 = nullptr;        //                   where the scales used are recorded
+    void *keep_u = nullptr, *keep_g = nullptr;                    //                   optional bf16 [M,N]: the rounded dU, dG
+                                                                  //                   the codes were cast from (both or neither)
 };
-// false (nothing launched): inconsistent arguments (part / add / epilogue)
+// Whether the argument set is one the kernels are built for (part / add / epilogue / layout combinations).
+bool gemm_args_ok(const GemmArgs &a);
+// false (nothing launched): gemm_args_ok(a) is false
 bool launch_gemm(const GemmArgs &a, hipStream_t st);
 
 // Benchmark hook: called by launch_gemm before and after the kernel launch (no-ops unless enabled).
@@ -143,11 +150,5 @@ struct AdamArgs {
 size_t adam_scalar_words();
 void launch_adam_init(uint32_t *scalars, uint8_t *codes, size_t code_bytes, hipStream_t st);
 void launch_adam_step(const AdamArgs &a, hipStream_t st);
-
-// register-only MFMA loop (ssg_probe.hip): 64 KiB of operand bytes in, 256 KiB checksum sink out
-double mfma_rate_flops(int iters);
-size_t mfma_rate_operand_bytes();
-size_t mfma_rate_sink_bytes();
-void launch_mfma_rate(const void *operands, void *sink, int iters, hipStream_t st);
 
 }  // namespace ssg

@@ -5,9 +5,14 @@
 // random bytes measurably below it.  This kernel keeps 16 accumulator blocks (256 registers) per
 // wave, one wave per SIMD -- the register shape of the 4-wave GEMM -- and issues nothing but
 // v_mfma_f32_32x32x64_f8f6f4, so its time is the ceiling any GEMM on that data can approach.
-#include "ssg_internal.h"
+//
+// Built into a library of its own (libssg_probe.so) that only the benchmark loads: it is a
+// measurement aid, not part of the block's interface.
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
 
-namespace ssg {
+namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -43,14 +48,22 @@ __global__ void __launch_bounds__(kProbeThreads) mfma_rate_kernel(const int *ope
 }
 
 
-double mfma_rate_flops(int iters) {
-    return (double)kProbeBlocks * (kProbeThreads / 64) * (double)iters * (kProbeFrags * kProbeFrags) * 2.0 * 32 * 32 * 64;
-}
-size_t mfma_rate_operand_bytes() { return (size_t)kProbeThreads * kProbeFrags * 16 * sizeof(int); }     // 64 KiB
-size_t mfma_rate_sink_bytes() { return (size_t)kProbeBlocks * kProbeThreads * sizeof(float); }          // 256 KiB
-void launch_mfma_rate(const void *operands, void *sink, int iters, hipStream_t st) {
-    hipLaunchKernelGGL(mfma_rate_kernel, dim3(kProbeBlocks), dim3(kProbeThreads), 0, st, (const int *)operands,
-                       (float *)sink, iters);
-}
+}  // namespace
 
-}  // namespace ssg
+// Launches the loop: `iters` passes of 16 MFMAs per wave on the operand fragments in the first 64 KiB of
+// `workspace` (device; the caller fills them); a 256 KiB checksum is written after them, so `workspace_bytes`
+// must be at least 320 KiB.  *flops (host, may be NULL) receives the flop count of the launch; the caller
+// times it.  Returns 0, or -1 on a bad argument / -4 when the launch reported an error.
+extern "C" int ssg_probe_mfma_rate(void *workspace, size_t workspace_bytes, int iters, double *flops, void *stream) {
+    const size_t operand_bytes = (size_t)kProbeThreads * kProbeFrags * 16 * sizeof(int);        // 64 KiB
+    const size_t sink_bytes = (size_t)kProbeBlocks * kProbeThreads * sizeof(float);             // 256 KiB
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || workspace_bytes < operand_bytes + sink_bytes ||
+        iters <= 0 || iters > (1 << 24))
+        return -1;
+    if (flops)
+        *flops = (double)kProbeBlocks * (kProbeThreads / 64) * (double)iters * (kProbeFrags * kProbeFrags) * 2.0 * 32 * 32 * 64;
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(kProbeBlocks), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const int *>(workspace),
+                       reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + operand_bytes), iters);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}

@@ -12,9 +12,6 @@ typedef short ssg_i16x2 __attribute__((ext_vector_type(2)));
 #include "ssg_device.h"
 #include "ssg_internal.h"
 
-#ifndef SSG_AMAX_BLOCKS
-#define SSG_AMAX_BLOCKS 512
-#endif
 namespace ssg {
 
 // ------------------------------------------------------------------ fill
@@ -127,7 +124,7 @@ void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, i
     size_t n8 = n / 8;      // n is a multiple of 256 at every call site (rows, cols multiples of 16)
     if (n8 == 0) return;
     const size_t units = (n8 + 2047) / 2048;
-    const size_t cap = slots > 1 ? 2048 : SSG_AMAX_BLOCKS;
+    const size_t cap = slots > 1 ? 2048 : 512;
     const size_t per_block = (units + cap - 1) / cap;               // units per workgroup, the same for all
     unsigned blocks = (unsigned)((units + per_block - 1) / per_block);
     if (kind == SRC_BF16)
@@ -160,14 +157,18 @@ __device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint3
     o[3] = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x07060302u);
 }
 
-template <class Loader, int FMT, bool COLSCALE, bool TRANSPOSED, bool RECORD = false>
+// COUNT: also count, into counters[0] and counters[1], the elements whose scaled magnitude lies beyond the
+// rounding interval of the largest finite value (only the clamp keeps them finite: overflow, Section 3) and
+// the nonzero elements whose code is +-0 (underflow).
+template <class Loader, int FMT, bool COLSCALE, bool TRANSPOSED, bool RECORD = false, bool COUNT = false>
 __global__ void __launch_bounds__(256)
 cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col_scale,
             const float *__restrict__ amax, int amax_slots, float *__restrict__ amax_out,
             const float *__restrict__ scale_in, int pow2,
             float *__restrict__ scale_out, uint8_t *__restrict__ dst, uint8_t *__restrict__ dst_t,
-            uint32_t *__restrict__ record = nullptr) {
+            uint32_t *__restrict__ record = nullptr, unsigned long long *__restrict__ counters = nullptr) {
     __shared__ uint32_t tile[TRANSPOSED ? kTile * kTPitchWords : 1];
+    uint32_t n_sat = 0, n_flush = 0;
 
     float sigma = 1.0f;
     bool tensor_scale = false;
@@ -236,13 +237,23 @@ cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const size_t off = (size_t)(row0 + lr + r) * (size_t)cols + (size_t)col;
+                uint32_t nonzero = 0;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
+                    if (COUNT) nonzero |= (v[r][i] != 0.0f ? 1u : 0u) << i;
                     if (COLSCALE) v[r][i] = __fmul_rn(v[r][i], cs[i]);
                     if (tensor_scale) v[r][i] = __fmul_rn(v[r][i], sigma);
+                    if (COUNT) n_sat += fabsf(v[r][i]) > Fp8Traits<FMT>::overflow_above ? 1u : 0u;
                 }
                 lo[r] = satcast_pk4<FMT>(v[r][0], v[r][1], v[r][2], v[r][3]);
                 hi[r] = satcast_pk4<FMT>(v[r][4], v[r][5], v[r][6], v[r][7]);
+                if (COUNT) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const uint32_t code = ((i < 4 ? lo[r] : hi[r]) >> (8 * (i & 3))) & 0x7fu;
+                        n_flush += (code == 0u && ((nonzero >> i) & 1u)) ? 1u : 0u;
+                    }
+                }
                 *reinterpret_cast<uint2 *>(dst + off) = make_uint2(lo[r], hi[r]);
             }
         }
@@ -271,6 +282,22 @@ cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col
 #pragma unroll
             for (int k = 1; k < 4; ++k) m = m > wave_seen[k] ? m : wave_seen[k];
             if (m) atomicMax(record + ((blockIdx.y * gridDim.x + blockIdx.x) % kAmaxSlots) * kAmaxSlotStride, m);
+        }
+    }
+    if (COUNT) {
+        // one atomic per workgroup and counter, and none for a zero count
+        __shared__ uint32_t wave_counts[4][2];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            n_sat += (uint32_t)__shfl_xor((int)n_sat, off, 64);
+            n_flush += (uint32_t)__shfl_xor((int)n_flush, off, 64);
+        }
+        if ((threadIdx.x & 63) == 0) { wave_counts[threadIdx.x >> 6][0] = n_sat; wave_counts[threadIdx.x >> 6][1] = n_flush; }
+        __syncthreads();
+        if (threadIdx.x < 2) {
+            const uint32_t c = wave_counts[0][threadIdx.x] + wave_counts[1][threadIdx.x] + wave_counts[2][threadIdx.x] +
+                               wave_counts[3][threadIdx.x];
+            if (c) atomicAdd(counters + threadIdx.x, (unsigned long long)c);
         }
     }
     if (TRANSPOSED) {
@@ -308,6 +335,17 @@ static void launch_cast_l(const Loader &ld, const CastArgs &a, hipStream_t st) {
                                    a.dst_t, a.record);
             return;
         }
+    }
+    if (a.counters && !tr) {
+        if (cs)
+            hipLaunchKernelGGL((cast_kernel<Loader, FMT, true, false, false, true>), grid, dim3(256), 0, st, ld, a.rows, a.cols,
+                               a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst,
+                               a.dst_t, nullptr, a.counters);
+        else
+            hipLaunchKernelGGL((cast_kernel<Loader, FMT, false, false, false, true>), grid, dim3(256), 0, st, ld, a.rows, a.cols,
+                               a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst,
+                               a.dst_t, nullptr, a.counters);
+        return;
     }
     if (cs && tr) SSG_CAST(true, true);
     else if (cs) SSG_CAST(true, false);
@@ -411,8 +449,8 @@ void launch_col_amax(const void *src, const void *src2, SrcKind kind, int64_t ro
 // W3: rounding is monotone, so max_j fl32(|w_ji| * sinv_i) = fl32(max_j |w_ji| * sinv_i).
 __global__ void __launch_bounds__(256)
 channel_factors_kernel(const float *__restrict__ h_camax, const float *__restrict__ w3_camax, int64_t f,
-                       int smooth, const uint32_t *__restrict__ hmax_bits, float *__restrict__ s,
-                       float *__restrict__ sinv, uint32_t *__restrict__ amax_w3s_bits) {
+                       int smooth, const uint32_t *__restrict__ hmax_bits, const float *__restrict__ h_scale_given,
+                       float *__restrict__ s, float *__restrict__ sinv, uint32_t *__restrict__ amax_w3s_bits) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     uint32_t wbits = 0;
     if (i < f) {
@@ -422,7 +460,8 @@ channel_factors_kernel(const float *__restrict__ h_camax, const float *__restric
             si = scale_from_amax(a, 448.0f, 0);
             sv = a > 0.0f ? __fdiv_rn(a, 448.0f) : 1.0f;
         } else {
-            si = scale_from_amax(__uint_as_float(*hmax_bits), 448.0f, 0);
+            // plain block: one scale for the whole tensor, from its own range or as the caller gives it
+            si = h_scale_given ? *h_scale_given : scale_from_amax(__uint_as_float(*hmax_bits), 448.0f, 0);
             sv = 1.0f;
         }
         s[i] = si;
@@ -442,12 +481,13 @@ vec_max_kernel(const float *__restrict__ v, int64_t n, uint32_t *__restrict__ ou
 }
 
 void launch_channel_factors(const float *h_camax, const float *w3_camax, int64_t f, int smooth, float *s,
-                            float *sinv, uint32_t *amax_w3s_bits, uint32_t *hmax_bits, hipStream_t st) {
+                            float *sinv, uint32_t *amax_w3s_bits, uint32_t *hmax_bits, const float *h_scale_given,
+                            hipStream_t st) {
     const unsigned blocks = (unsigned)((f + 255) / 256);
     if (!smooth)
         hipLaunchKernelGGL(vec_max_kernel, dim3(blocks), dim3(256), 0, st, h_camax, f, hmax_bits);
     hipLaunchKernelGGL(channel_factors_kernel, dim3(blocks), dim3(256), 0, st, h_camax, w3_camax, f, smooth,
-                       hmax_bits, s, sinv, amax_w3s_bits);
+                       hmax_bits, smooth ? nullptr : h_scale_given, s, sinv, amax_w3s_bits);
 }
 
 __global__ void __launch_bounds__(256)

@@ -84,15 +84,21 @@ def test_gemm_uniform_codes_full_dynamic_range():
 @pytest.mark.gpu
 def test_mfma_rate_probe_runs_and_checks_its_arguments():
     """The register-only MFMA loop: flop count as documented, checksum written, small workspace refused."""
+    import ctypes
+    import os
+    probe = ctypes.CDLL(os.path.join(os.path.dirname(ssg.LIB_PATH), "libssg_probe.so"))   # the benchmark's helper library
+    probe.ssg_probe_mfma_rate.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
+                                          ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
     ws = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda:0")
     ws[:65536].fill_(0x38)                       # E4M3 1.0 everywhere: every accumulator ends at iters * 64
-    flops = ssg.ssg_probe_mfma_rate(ws, 3)
+    flops = ctypes.c_double(0.0)
+    st = torch.cuda.current_stream().cuda_stream
+    assert probe.ssg_probe_mfma_rate(ws.data_ptr(), ws.numel(), 3, ctypes.byref(flops), st) == 0
     torch.cuda.synchronize()
-    assert flops == 256 * 4 * 3 * 16 * 2.0 * 32 * 32 * 64
+    assert flops.value == 256 * 4 * 3 * 16 * 2.0 * 32 * 32 * 64
     sink = ws[65536:65536 + 256 * 256 * 4].view(torch.float32)
     assert torch.all(sink == 16 * 16 * 3 * 64.0)
-    with pytest.raises(ssg.SsgError):
-        ssg.ssg_probe_mfma_rate(ws[:4096], 3)
+    assert probe.ssg_probe_mfma_rate(ws.data_ptr(), 4096, 3, ctypes.byref(flops), st) == -1
 
 
 @pytest.mark.parametrize("c_dtype", [ssg.SSG_F32, ssg.SSG_BF16])
@@ -145,3 +151,20 @@ def test_kmajor_unsupported_combination_is_refused():
     with pytest.raises(ssg.SsgError) as e:
         ssg.ssg_gemm_fp8_layout(t, ssg.SSG_E4M3, 1, t, ssg.SSG_E4M3, 0, 256, 256, 256, None, None, c, ssg.SSG_F32)
     assert e.value.status == ssg.SSG_ERR_UNSUPPORTED
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("c_dtype", [ssg.SSG_F32, ssg.SSG_BF16])
+def test_extreme_scales_do_not_zero_the_product(c_dtype):
+    """A gradient tensor with a tiny range has a scale near 1e35; times a weight scale the product of the two
+    scales leaves the binary32 range although the dequantized result does not.  The oracle divides in float64."""
+    rng = np.random.default_rng(11)
+    M, N, K = 64, 48, 256
+    a, b = _codes(rng, ssg.SSG_E5M2, (M, K)), _codes(rng, ssg.SSG_E4M3, (N, K))
+    sa, sb = np.float32(57344.0) / np.float32(1e-30), np.float32(448.0) / np.float32(1e-3)
+    with np.errstate(over="ignore"):
+        assert not np.isfinite(sa * sb)                   # the binary32 product of the scales overflows
+    got = _run(a, ssg.SSG_E5M2, b, float(sa), float(sb), c_dtype)
+    ref = gemm.matmul_nt(a, fp8.E5M2, b, fp8.E4M3) / (np.float64(sa) * np.float64(sb))
+    assert np.abs(ref).max() > 1e-36 and np.isfinite(ref).all()
+    gu.assert_close_gemm(got, ref, c_dtype == ssg.SSG_BF16, "extreme scales")

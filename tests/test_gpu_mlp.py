@@ -13,16 +13,28 @@ import paper_2409_12517_amd as ssg  # noqa: E402
 import gpu_util as gu  # noqa: E402
 
 
+# End-to-end bounds against the pure oracle (the stage-by-stage tiers on identical operands carry the 2e-3 bar):
+# about twice the largest value measured over the configurations of this file and the Llama2-7B shape
+# (largest measured: y 2.8e-3 / 1.3e-2, gradients 4.3e-3 / 5.7e-2, codes 2.0e-3 / 2.8e-5).
+E2E_NORM_FWD, E2E_MAX_FWD = 6e-3, 3e-2        # y: relative Frobenius norm, max|err| / max|ref|
+E2E_NORM_BWD, E2E_MAX_BWD = 1e-2, 0.12        # dX, dW1..3
+HQ_DIFF_FRAC, HQ_DIFF_GT1_FRAC = 4e-3, 6e-5   # fraction of h^ codes that differ from the oracle's; by more than one step
+
+
 class Block:
     """Device buffers of one forward+backward call and typed views into saved/workspace."""
 
-    def __init__(self, inp, smooth=1, y_dtype=None, dw_dtype=None, rnd=None):
+    def __init__(self, inp, smooth=1, y_dtype=None, dw_dtype=None, rnd=None, h_scale=None, count=False):
         self.T, self.d = inp["x"].shape
         self.f = inp["W1"].shape[0]
+        # optional: a given scale of h (plain block) and the overflow / underflow counters of the h cast
+        self.h_scale = None if h_scale is None else torch.tensor([h_scale], dtype=torch.float32, device=gu.DEV)
+        self.h_counters = torch.full((2,), -1, dtype=torch.int64, device=gu.DEV) if count else None
         self.desc = ssg.make_desc(self.T, self.d, self.f, smooth=smooth,
                                   rnd=ssg.SSG_ROUND_EXACT_DIV if rnd is None else rnd,
                                   y_dtype=ssg.SSG_BF16 if y_dtype is None else y_dtype,
-                                  dw_dtype=ssg.SSG_F32 if dw_dtype is None else dw_dtype)
+                                  dw_dtype=ssg.SSG_F32 if dw_dtype is None else dw_dtype,
+                                  h_scale=self.h_scale, h_counters=self.h_counters)
         self.x, self.W1, self.W2, self.W3 = (gu.dev(inp[k]) for k in ("x", "W1", "W2", "W3"))
         self.dY = gu.dev(inp["dY"]) if inp.get("dY") is not None else None
         ydt = torch.bfloat16 if self.desc.y_dtype == ssg.SSG_BF16 else torch.float32
@@ -34,6 +46,7 @@ class Block:
         self.dW1 = torch.empty(self.f, self.d, dtype=wdt, device=gu.DEV)
         self.dW2 = torch.empty(self.f, self.d, dtype=wdt, device=gu.DEV)
         self.dW3 = torch.empty(self.d, self.f, dtype=wdt, device=gu.DEV)
+        self.report = {}          # measured end-to-end deviations from the pure oracle, filled by the checks
 
     def fwd(self):
         ssg.ssg_mlp_fwd(self.desc, self.x, self.W1, self.W2, self.W3, self.y, self.saved)
@@ -56,12 +69,12 @@ def _np_inputs(inp):
     return {k: synth.bf16_to_f32_numpy(v) for k, v in inp.items() if isinstance(v, torch.Tensor) and v.dtype == torch.bfloat16}
 
 
-def check_forward(blk: Block, npi, smooth=1, scales=None):
+def check_forward(blk: Block, npi, smooth=1, scales=None, h_scale=None):
     """Tiered comparison of one forward call with the oracle.  ``scales``: the per-tensor scales the call
-    was given (delayed scaling); None = current scaling."""
+    was given (delayed scaling); None = current scaling.  ``h_scale``: the given scale of h (plain block)."""
     T, d, f = blk.T, blk.d, blk.f
-    ref = mlp.forward(npi["x"], npi["W1"], npi["W2"], npi["W3"], smooth=bool(smooth), scales=scales)
-    sc = gu.f32(blk.sv("scales", (8,), torch.float32))
+    ref = mlp.forward(npi["x"], npi["W1"], npi["W2"], npi["W3"], smooth=bool(smooth), scales=scales, h_scale=h_scale)
+    sc = gu.f32(blk.sv("scales", (16,), torch.float32))
     # tier 1: quantized inputs and their scales are bit-exact
     assert sc[0] == ref.sx and sc[1] == ref.sw1 and sc[2] == ref.sw2
     x_q = gu.u8(blk.sv("x_q", (T, d), torch.uint8))
@@ -85,7 +98,8 @@ def check_forward(blk: Block, npi, smooth=1, scales=None):
         w3q_ref, sw3_ref, amax_w3s = mlp.fold_w3(npi["W3"], sinv_ref)
     else:
         a = np.abs(h_np).max(axis=0)
-        hq_ref, sh, _ = quant.quantize_per_tensor(h_np, fp8.E4M3)
+        hq_ref, sh, _ = quant.quantize_per_tensor(h_np, fp8.E4M3, scale=h_scale)
+        assert sc[8] == a.max()                                     # the range of h is recorded either way
         s_ref, sinv_ref = np.full(f, sh, np.float32), np.ones(f, np.float32)
         w3q_ref, sw3_ref, amax_w3s = quant.quantize_per_tensor(npi["W3"], fp8.E4M3)
     assert np.array_equal(gu.f32(blk.sv("h_camax", (f,), torch.float32)), a)
@@ -100,13 +114,31 @@ def check_forward(blk: Block, npi, smooth=1, scales=None):
     y_cont = fp8_gemm.matmul_nt(h_q, fp8.E4M3, w3_q, fp8.E4M3) / (float(sw3_ref) * (1.0 if smooth else float(s_ref[0])))
     bf_y = blk.desc.y_dtype == ssg.SSG_BF16
     gu.assert_close_gemm(gu.f32(blk.y), mlp.round_bf16(y_cont) if bf_y else y_cont, bf_y, "Y (continued)")
-    # tier 5: end to end against the oracle.  A bf16 rounding of U or G that differs (fp32 vs fp64
-    # accumulation) can move a channel's maximum, hence its factor and many of its FP8 codes, so the
-    # two outputs differ by FP8 decision noise, not by the GEMM bar; bound it normwise.
-    rel = np.linalg.norm(gu.f32(blk.y) - ref.Y) / np.linalg.norm(ref.Y)
-    assert rel < 1e-2, rel
+    # tier 5 (end to end against the pure oracle).  A bf16 rounding of U or G that differs (fp32 vs fp64
+    # accumulation at a rounding boundary) moves h by one bf16 step; if that element is its channel's maximum the
+    # factor moves with it.  So the codes of h^ may differ from the oracle's -- by one step only, on a small
+    # fraction of the elements -- and y differs by that FP8 decision noise.  Measured and bounded:
+    rep = blk.report
+    y_got = gu.f32(blk.y)
+    rep["y_rel_norm"] = float(np.linalg.norm(y_got - ref.Y) / np.linalg.norm(ref.Y))
+    rep["y_max_ratio"] = float(np.abs(y_got - ref.Y).max() / np.abs(ref.Y).max())
+    assert rep["y_rel_norm"] < E2E_NORM_FWD, rep
+    assert rep["y_max_ratio"] < E2E_MAX_FWD, rep
     if smooth:
-        assert np.all(np.abs(s_ref / ref.s - 1) < 2.0 ** -5)
+        rep["s_rel_dev"] = float(np.abs(s_ref / ref.s - 1).max())
+        assert rep["s_rel_dev"] <= 2.0 ** -6, rep
+        mag_got, mag_ref = (h_q & 0x7F).astype(np.int16), (ref.h_q & 0x7F).astype(np.int16)
+        # Codes that differ from the pure oracle's: almost all by one step (a factor s_i that moved, or a bf16
+        # step of U or G next to a rounding boundary of the cast).  More than one step happens only where u is
+        # next to zero: there one fp32-vs-fp64 accumulation difference is several bf16 steps of u, hence of h
+        # (each such code is still the exact cast of the device's own h: tier 3).
+        step = np.abs(mag_got - mag_ref)
+        rep["hq_diff_frac"] = float((h_q != ref.h_q).mean())
+        rep["hq_diff_gt1_frac"] = float((step > 1).mean())
+        rep["hq_max_step"] = int(step.max())
+        sign_differs = ((h_q ^ ref.h_q) & 0x80) != 0
+        assert not np.any(sign_differs & ((mag_got > 8) | (mag_ref > 8))), "a sign differs away from zero"
+        assert rep["hq_diff_frac"] < HQ_DIFF_FRAC and rep["hq_diff_gt1_frac"] < HQ_DIFF_GT1_FRAC, rep
     # the oracle's forward state rebuilt from the GPU's stored tensors, for the backward checks
     fw_gpu = mlp.Forward(quantized=True, smooth=bool(smooth), x_q=x_q, sx=np.float32(sc[0]),
                          w1_q=gu.u8(blk.sv("w1_q", (f, d), torch.uint8)), sw1=np.float32(sc[1]),
@@ -116,7 +148,17 @@ def check_forward(blk: Block, npi, smooth=1, scales=None):
     return ref, fw_gpu
 
 
+def continue_backward(fw_gpu, dY, dU, dG, ydt, wdt, scales=None):
+    """The oracle's backward continued from stored bf16 dU, dG: its first half for dY^ and its scale, then its
+    second half (quantization of dU, dG and the four gradient contractions) on the stored tensors."""
+    bw = mlp.backward_grad_h(fw_gpu, dY, scales=scales)
+    bw.dU, bw.dG = np.asarray(dU, np.float64), np.asarray(dG, np.float64)
+    return mlp.backward_operand_grads(fw_gpu, bw, dx_dtype=ydt, dw_dtype=wdt, scales=scales)
+
+
 def check_backward(blk: Block, npi, ref_fw, fw_gpu, smooth=1, scales=None):
+    """``scales``: the per-tensor scales the call was given (delayed scaling; the descriptor must then ask for
+    the bf16 dU, dG to be kept); None = current scaling."""
     T, d, f = blk.T, blk.d, blk.f
     delayed = scales is not None
     bf_y = blk.desc.y_dtype == ssg.SSG_BF16
@@ -128,47 +170,34 @@ def check_backward(blk: Block, npi, ref_fw, fw_gpu, smooth=1, scales=None):
     dy_q = gu.u8(blk.wv("dy_q", (T, d), torch.uint8))
     assert wsc[0] == cont.sdy and np.array_equal(dy_q, cont.dy_q)
     assert delayed or wsc[3] == quant.amax(npi["dY"])
+    # stage 2: dU, dG on identical inputs (one GEMM plus the SwiGLU derivative)
+    dU = gu.f32(blk.wv("dU", (T, f), torch.bfloat16)); dG = gu.f32(blk.wv("dG", (T, f), torch.bfloat16))
+    gu.assert_close_gemm(dU, cont.dU, True, "dU"); gu.assert_close_gemm(dG, cont.dG, True, "dG")
+    # stage 3: quantization of the GPU's own bf16 dU, dG, bit-exact -- under delayed scaling too, where the fused
+    # epilogue casts them with the scales of the history (values beyond the remembered range saturate)
+    cont2 = continue_backward(fw_gpu, npi["dY"], dU, dG, ydt, wdt, scales=scales)
+    assert wsc[1] == cont2.sdu and wsc[2] == cont2.sdg
     if delayed:
-        # Under delayed scaling the dH epilogue emits the E5M2 codes of dU, dG directly (no bf16 tensors exist).
-        # The code is decided from fp32 values accumulated in the matrix core's order, so what is checked is the
-        # value: decode(code) / scale must be a correct E5M2 rounding (half an ulp = 2^-3 relative; half the
-        # smallest subnormal absolute; clipped at the format maximum) of a value within the GEMM bar of the
-        # oracle's bf16 dU, dG -- and the outright decisions must agree almost everywhere.
-        table = fp8.decode_table(fp8.E5M2).astype(np.float64)
-        codes = {}
-        for nm, ref_v, ref_q, sc_given in (("du_q", cont.dU, cont.du_q, float(scales["du"])), ("dg_q", cont.dG, cont.dg_q, float(scales["dg"]))):
-            q = gu.u8(blk.wv(nm, (T, f), torch.uint8))
-            codes[nm] = q
-            got = table[q] / sc_given
-            lim = 57344.0 / sc_given
-            want = np.clip(ref_v, -lim, lim)
-            tol = 2e-3 * np.abs(ref_v).max() + gu.bf16_ulp(ref_v) + 2.0 ** -3 * np.abs(want) * (1 + 1e-6) + 2.0 ** -17 / sc_given
-            assert np.all(np.abs(got - want) <= tol), nm
-            assert (q != ref_q).mean() < 2e-2, (nm, (q != ref_q).mean())
         assert wsc[1] == np.float32(scales["du"]) and wsc[2] == np.float32(scales["dg"])
-        cont2 = mlp.backward(fw_gpu, npi["dY"], dx_dtype=ydt, dw_dtype=wdt, scales=scales,
-                             stored_codes=(codes["du_q"], codes["dg_q"]))
     else:
-        # stage 2: dU, dG on identical inputs (one GEMM plus the SwiGLU derivative)
-        dU = gu.f32(blk.wv("dU", (T, f), torch.bfloat16)); dG = gu.f32(blk.wv("dG", (T, f), torch.bfloat16))
-        gu.assert_close_gemm(dU, cont.dU, True, "dU"); gu.assert_close_gemm(dG, cont.dG, True, "dG")
-        # stage 3: quantization of the GPU's own dU, dG, bit-exact
-        cont2 = mlp.backward(fw_gpu, npi["dY"], dx_dtype=ydt, dw_dtype=wdt, stored_dU_dG=(dU, dG), scales=scales)
-        assert wsc[1] == cont2.sdu and wsc[2] == cont2.sdg
         assert wsc[4] == quant.amax(dU) and wsc[5] == quant.amax(dG)
-        assert np.array_equal(gu.u8(blk.wv("du_q", (T, f), torch.uint8)), cont2.du_q)
-        assert np.array_equal(gu.u8(blk.wv("dg_q", (T, f), torch.uint8)), cont2.dg_q)
+    assert np.array_equal(gu.u8(blk.wv("du_q", (T, f), torch.uint8)), cont2.du_q)
+    assert np.array_equal(gu.u8(blk.wv("dg_q", (T, f), torch.uint8)), cont2.dg_q)
     # stage 4: the four gradient GEMMs on identical inputs
     gu.assert_close_gemm(gu.f32(blk.dx), cont2.dX, bf_y, "dX")
     gu.assert_close_gemm(gu.f32(blk.dW1), cont2.dW1, bf_w, "dW1")
     gu.assert_close_gemm(gu.f32(blk.dW2), cont2.dW2, bf_w, "dW2")
     gu.assert_close_gemm(gu.f32(blk.dW3), cont2.dW3, bf_w, "dW3")
-    # stage 5: end to end against the oracle, normwise (FP8 decision noise, see check_forward)
+    # stage 5: end to end against the pure oracle (FP8 decision noise, see check_forward): measured and bounded
     ref = mlp.backward(ref_fw, npi["dY"], dx_dtype=ydt, dw_dtype=wdt, scales=scales)
     for name, got in (("dX", blk.dx), ("dW1", blk.dW1), ("dW2", blk.dW2), ("dW3", blk.dW3)):
         r = getattr(ref, name)
-        rel = np.linalg.norm(gu.f32(got) - r) / np.linalg.norm(r)
-        assert rel < 2e-2, (name, rel)
+        g = gu.f32(got)
+        blk.report[name + "_rel_norm"] = float(np.linalg.norm(g - r) / np.linalg.norm(r))
+        blk.report[name + "_max_ratio"] = float(np.abs(g - r).max() / np.abs(r).max())
+        assert blk.report[name + "_rel_norm"] < E2E_NORM_BWD, (name, blk.report)
+        assert blk.report[name + "_max_ratio"] < E2E_MAX_BWD, (name, blk.report)
+    print(f"\nend-to-end vs the pure oracle (T={T} d={d} f={f} smooth={smooth}):", {k: float(f"{v:.3g}") for k, v in blk.report.items()})
     return ref, cont2
 
 
@@ -192,6 +221,39 @@ def test_ragged_shapes_and_outlier_channels(T, d, f, aligned):
     ref_fw, g = check_forward(blk, npi)
     blk.bwd()
     check_backward(blk, npi, ref_fw, g)
+
+
+def test_plain_block_with_a_given_h_scale_and_device_counters():
+    """Figure 4(a) under a scale of h that comes from elsewhere (delayed scaling, Section 2): a stale scale that
+    is too large makes the largest elements overflow E4M3 (they saturate), one that is too small flushes the small
+    ones to zero (Section 3).  Codes, y and all gradients follow the oracle run with the same scale; the two
+    device counters equal the oracle's counts on the device's own fp32 h."""
+    inp = synth.make_inputs(272, 256, 688, seed=71, aligned_channels=4)
+    npi = _np_inputs(inp)
+    probe = Block(inp, smooth=0)
+    probe.fwd()
+    cur = float(gu.f32(probe.sv("s", (688,), torch.float32))[0])          # the current-scaling scale of h
+    for factor in (1.0, 64.0, 1.0 / 64.0):
+        blk = Block(inp, smooth=0, h_scale=cur * factor, count=True)
+        blk.fwd()
+        ref_fw, fw_gpu = check_forward(blk, npi, smooth=0, h_scale=np.float32(cur * factor))
+        sat, flushed = (int(v) for v in blk.h_counters.cpu())
+        assert sat == quant.count_saturated(fw_gpu.h, np.float32(cur * factor), fp8.E4M3)
+        assert flushed == quant.count_flushed(fw_gpu.h, fw_gpu.h_q)
+        assert (sat > 0) == (factor > 1.0)
+        blk.bwd()
+        check_backward(blk, npi, ref_fw, fw_gpu, smooth=0)
+    # Smooth-SwiGLU on the same input: nothing overflows, and far fewer elements are flushed than under the
+    # current per-tensor scale (the aligned channels set that scale)
+    sm = Block(inp, smooth=1, count=True)
+    sm.fwd()
+    _, fw_sm = check_forward(sm, npi, smooth=1)
+    sat_s, flushed_s = (int(v) for v in sm.h_counters.cpu())
+    assert sat_s == 0 == quant.count_saturated(fw_sm.h, fw_sm.s[None, :], fp8.E4M3)
+    assert flushed_s == quant.count_flushed(fw_sm.h, fw_sm.h_q)
+    cur_blk = Block(inp, smooth=0, count=True)
+    cur_blk.fwd()
+    assert int(cur_blk.h_counters[0]) == 0 and int(cur_blk.h_counters[1]) > 10 * max(flushed_s, 1)
 
 
 def test_fp32_outputs_bf16_weight_grads_and_pow2_scales():

@@ -66,11 +66,47 @@ def test_entry_points_reject_bad_arguments_before_launching():
     assert e.value.status == ssg.SSG_ERR_SHAPE
     d = ssg.make_desc(256, 256, 688)
     with pytest.raises(ssg.SsgError) as e:
-        ssg.ssg_mlp_fwd(d, 256, 256, 256, 0, 256, 256, stream=0)          # W3 NULL
+        ssg.ssg_mlp_fwd(d, 256, 256, 256, 0, 256, 256, stream=0, saved_bytes=1 << 40)          # W3 NULL
     assert e.value.status == ssg.SSG_ERR_ARG and "W3" in str(e.value)
     with pytest.raises(ssg.SsgError) as e:
         ssg.ssg_mlp_bwd(ssg.make_desc(256, 256, 100), 256, 256, 256, 256, 256, 256, 256, stream=0)
     assert e.value.status == ssg.SSG_ERR_SHAPE
+
+
+def test_undersized_buffers_are_refused_before_launching():
+    """saved / workspace / prepared one byte short of their size query: SSG_ERR_WORKSPACE, nothing enqueued
+    (no GPU is present here, so a launch would have failed differently)."""
+    import paper_2409_12517_amd as ssg
+    d = ssg.make_desc(256, 256, 688)
+    need_s, need_w = ssg.ssg_mlp_saved_bytes(d), ssg.ssg_mlp_workspace_bytes(d)
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_mlp_fwd(d, 256, 256, 256, 256, 256, 256, stream=0, saved_bytes=need_s - 1)
+    assert e.value.status == ssg.SSG_ERR_WORKSPACE and str(need_s) in str(e.value)
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_mlp_bwd(d, 256, 256, 256, 256, 256, 256, 256, stream=0, saved_bytes=need_s - 1, workspace_bytes=need_w)
+    assert e.value.status == ssg.SSG_ERR_WORKSPACE
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_mlp_bwd(d, 256, 256, 256, 256, 256, 256, 256, stream=0, saved_bytes=need_s, workspace_bytes=need_w - 1)
+    assert e.value.status == ssg.SSG_ERR_WORKSPACE and "workspace" in str(e.value)
+    need_p, need_iw = ssg.ssg_infer_prepared_bytes(d), ssg.ssg_infer_workspace_bytes(d)
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_infer_prepare(d, 256, 256, 256, 256, 256, 256, stream=0, prepared_bytes=need_p - 1)
+    assert e.value.status == ssg.SSG_ERR_WORKSPACE
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_infer_fwd(d, 256, 256, 256, 256, stream=0, prepared_bytes=need_p, workspace_bytes=need_iw - 1)
+    assert e.value.status == ssg.SSG_ERR_WORKSPACE
+
+
+def test_given_h_scale_and_counters_are_validated():
+    import paper_2409_12517_amd as ssg
+    # a given scale of h belongs to the plain block only
+    assert ssg.ssg_mlp_saved_bytes(ssg.make_desc(256, 256, 688, smooth=1, h_scale=4096)) == 0
+    assert "plain" in ssg.ssg_last_error()
+    assert ssg.ssg_mlp_saved_bytes(ssg.make_desc(256, 256, 688, smooth=0, h_scale=4096)) > 0
+    d = ssg.make_desc(256, 256, 688, smooth=0)
+    d.h_scale_mode = ssg.SSG_SCALE_GIVEN                      # GIVEN without a pointer
+    assert ssg.ssg_mlp_saved_bytes(d) == 0
+    assert ssg.ssg_mlp_saved_bytes(ssg.make_desc(256, 256, 688, h_counters=4100)) == 0   # misaligned counters
 
 
 def test_adam_entry_points_validate_before_launching():
