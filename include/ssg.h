@@ -51,7 +51,8 @@ typedef enum {
     SSG_OK = 0,
     SSG_ERR_ARG = -1,          /* null pointer, bad enum, misaligned pointer */
     SSG_ERR_SHAPE = -2,        /* extent not a positive multiple of 16, or too large */
-    SSG_ERR_WORKSPACE = -3,    /* a caller-allocated buffer is smaller than its *_bytes() query */
+    SSG_ERR_WORKSPACE = -3,    /* a caller-allocated buffer is smaller than its *_bytes() query, or the shape is beyond
+                                  what the static scratch of ssg_infer_fwd_noalloc holds */
     SSG_ERR_HIP = -4,          /* a launch reported an error (text in ssg_last_error) */
     SSG_ERR_UNSUPPORTED = -5
 } ssg_status;
@@ -239,6 +240,18 @@ ssg_status ssg_infer_prepare(const ssg_mlp_desc *desc, const void *W1, const voi
                              const float *sinv, void *prepared, size_t prepared_bytes, void *stream);
 ssg_status ssg_infer_fwd(const ssg_mlp_desc *desc, const void *x, const void *prepared, size_t prepared_bytes, void *y,
                          void *workspace, size_t workspace_bytes, void *stream);
+/* ssg_infer_fwd for callers that cannot allocate device memory and have no workspace to hand over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  The workspace of the call
+ * (x^ [T,d], h^ [T,f], the range slots of x) lies in a static device array inside the library instead
+ * (ssg_infer_noalloc_max_bytes() = 16 MiB, held by every GPU the library runs on until the process ends); a shape
+ * with ssg_infer_workspace_bytes(desc) beyond that returns SSG_ERR_WORKSPACE with nothing launched.  Same kernels
+ * and same results as ssg_infer_fwd; no hipMalloc, hipFree or allocating library routine is called, and the range
+ * slots are cleared by a small fill kernel (no memset node).  All calls on one GPU share that GPU's array, which
+ * keeps the last call's contents: calls that overlap in time on one GPU (two streams, two threads) race and must
+ * be serialised by the caller.  The array's device address is looked up once per GPU on the first call there. */
+size_t ssg_infer_noalloc_max_bytes(void);
+ssg_status ssg_infer_fwd_noalloc(const ssg_mlp_desc *desc, const void *x, const void *prepared, size_t prepared_bytes,
+                                 void *y, void *stream);
 ssg_status ssg_infer_view(const ssg_mlp_desc *desc, const void *prepared, const void *workspace, ssg_infer_view_t *out);
 
 /* ---- Adam with both moments in FP8 (Section 5) -------------------------------

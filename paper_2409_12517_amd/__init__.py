@@ -35,6 +35,7 @@ EXPORTS = [
     "ssg_mlp_fwd", "ssg_mlp_bwd", "ssg_mlp_view_saved", "ssg_mlp_view_workspace",
     "ssg_mlp_scaling_state_bytes", "ssg_mlp_scaling_init",
     "ssg_infer_prepared_bytes", "ssg_infer_workspace_bytes", "ssg_infer_prepare", "ssg_infer_fwd", "ssg_infer_view",
+    "ssg_infer_noalloc_max_bytes", "ssg_infer_fwd_noalloc",
     "ssg_adam_state_bytes", "ssg_adam_init", "ssg_adam_step", "ssg_adam_view_state",
     "ssg_profile_enable", "ssg_profile_select", "ssg_profile_read",
 ]
@@ -104,6 +105,9 @@ _lib.ssg_infer_workspace_bytes.argtypes = [POINTER(ssg_mlp_desc)]
 _lib.ssg_infer_workspace_bytes.restype = c_size_t
 _lib.ssg_infer_prepare.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 6 + [c_size_t, c_void_p]
 _lib.ssg_infer_fwd.argtypes = [POINTER(ssg_mlp_desc), c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_size_t, c_void_p]
+_lib.ssg_infer_noalloc_max_bytes.argtypes = []
+_lib.ssg_infer_noalloc_max_bytes.restype = c_size_t
+_lib.ssg_infer_fwd_noalloc.argtypes = [POINTER(ssg_mlp_desc), c_void_p, c_void_p, c_size_t, c_void_p, c_void_p]
 _lib.ssg_infer_view.argtypes = [POINTER(ssg_mlp_desc), c_void_p, c_void_p, POINTER(ssg_infer_view_t)]
 _lib.ssg_adam_state_bytes.argtypes = [c_int64]
 _lib.ssg_adam_state_bytes.restype = c_size_t
@@ -277,6 +281,15 @@ def ssg_infer_prepare(desc, W1, W2, W3, s, sinv, prepared, stream=None, prepared
 def ssg_infer_fwd(desc, x, prepared, y, workspace, stream=None, prepared_bytes=None, workspace_bytes=None) -> None:
     _check(_lib.ssg_infer_fwd(ctypes.byref(desc), _ptr(x), _ptr(prepared), _nbytes(prepared, prepared_bytes), _ptr(y),
                               _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream)))
+
+
+def ssg_infer_noalloc_max_bytes() -> int:
+    return int(_lib.ssg_infer_noalloc_max_bytes())
+
+
+def ssg_infer_fwd_noalloc(desc, x, prepared, y, stream=None, prepared_bytes=None) -> None:
+    _check(_lib.ssg_infer_fwd_noalloc(ctypes.byref(desc), _ptr(x), _ptr(prepared), _nbytes(prepared, prepared_bytes),
+                                      _ptr(y), _stream(stream)))
 
 
 def ssg_infer_view(desc, prepared, workspace) -> ssg_infer_view_t:

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "../../include/ssg.h"
@@ -298,7 +299,7 @@ ssg_status ssg_infer_prepare(const ssg_mlp_desc *desc, const void *W1, const voi
 
 namespace {
 // The forward of the folded form on a workspace that holds infer_work_layout(T, d, f).total bytes; shared by
-// ssg_infer_fwd.
+// ssg_infer_fwd (caller's workspace) and ssg_infer_fwd_noalloc (the library's static device array).
 ssg_status infer_forward(const char *who, const ssg_mlp_desc *desc, const void *x, const void *prepared, void *y,
                          uint8_t *wk, hipStream_t st) {
     const int64_t T = desc->T, dm = desc->d, f = desc->f;
@@ -334,6 +335,33 @@ ssg_status infer_forward(const char *who, const ssg_mlp_desc *desc, const void *
     return check_launch(who);
 }
 
+// ---- the workspace of ssg_infer_fwd_noalloc: a static device array, one copy per GPU -------------------
+constexpr size_t kNoAllocScratchBytes = (size_t)16 << 20;
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+unsigned char *g_scratch_ptr[kMaxDevices] = {};       // device address of `scratch` on each GPU, looked up once
+std::mutex g_scratch_mutex;
+
+// The address of this GPU's copy of `scratch` (the array's name is a host-side stand-in, never a device address).
+ssg_status scratch_address(const char *who, unsigned char **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return fail(SSG_ERR_HIP, "%s: hipGetDevice failed or device index beyond %d", who, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr)
+            return fail(SSG_ERR_HIP, "%s: hipGetSymbolAddress(scratch): %s", who, hipGetErrorString(e));
+        g_scratch_ptr[dev] = static_cast<unsigned char *>(ptr);
+    }
+    *out = g_scratch_ptr[dev];
+    return SSG_OK;
+}
 }  // namespace
 
 ssg_status ssg_infer_fwd(const ssg_mlp_desc *desc, const void *x, const void *prepared, size_t prepared_bytes, void *y,
@@ -348,6 +376,27 @@ ssg_status ssg_infer_fwd(const ssg_mlp_desc *desc, const void *x, const void *pr
     if (workspace_bytes < need_w)
         return fail(SSG_ERR_WORKSPACE, "ssg_infer_fwd: workspace holds %zu bytes, %zu needed", workspace_bytes, need_w);
     return infer_forward("ssg_infer_fwd", desc, x, prepared, y, static_cast<uint8_t *>(workspace), (hipStream_t)stream);
+}
+
+size_t ssg_infer_noalloc_max_bytes(void) { return kNoAllocScratchBytes; }
+
+ssg_status ssg_infer_fwd_noalloc(const ssg_mlp_desc *desc, const void *x, const void *prepared, size_t prepared_bytes,
+                                 void *y, void *stream) {
+    ssg_status rc = check_infer_desc(desc, "ssg_infer_fwd_noalloc");
+    if (rc != SSG_OK) return rc;
+    SSG_REQUIRE_PTR(x); SSG_REQUIRE_PTR(prepared); SSG_REQUIRE_PTR(y);
+    const size_t need_p = infer_prepared_layout(desc->d, desc->f).total;
+    const size_t need_w = infer_work_layout(desc->T, desc->d, desc->f).total;
+    if (prepared_bytes < need_p)
+        return fail(SSG_ERR_WORKSPACE, "ssg_infer_fwd_noalloc: prepared holds %zu bytes, %zu needed", prepared_bytes, need_p);
+    if (need_w > kNoAllocScratchBytes)
+        return fail(SSG_ERR_WORKSPACE,
+                    "ssg_infer_fwd_noalloc: T=%lld d=%lld f=%lld needs %zu bytes of scratch, the static array holds %zu "
+                    "(use ssg_infer_fwd with a caller-allocated workspace)",
+                    (long long)desc->T, (long long)desc->d, (long long)desc->f, need_w, kNoAllocScratchBytes);
+    unsigned char *ptr = nullptr;
+    if ((rc = scratch_address("ssg_infer_fwd_noalloc", &ptr)) != SSG_OK) return rc;
+    return infer_forward("ssg_infer_fwd_noalloc", desc, x, prepared, y, ptr, (hipStream_t)stream);
 }
 
 ssg_status ssg_infer_view(const ssg_mlp_desc *desc, const void *prepared, const void *workspace, ssg_infer_view_t *out) {

@@ -95,6 +95,12 @@ def test_undersized_buffers_are_refused_before_launching():
     with pytest.raises(ssg.SsgError) as e:
         ssg.ssg_infer_fwd(d, 256, 256, 256, 256, stream=0, prepared_bytes=need_p, workspace_bytes=need_iw - 1)
     assert e.value.status == ssg.SSG_ERR_WORKSPACE
+    # the allocation-free forward: a shape whose workspace exceeds the static array is refused with the limit named
+    big = ssg.make_desc(4096, 4096, 11008)
+    assert ssg.ssg_infer_workspace_bytes(big) > ssg.ssg_infer_noalloc_max_bytes() == 16 << 20
+    with pytest.raises(ssg.SsgError) as e:
+        ssg.ssg_infer_fwd_noalloc(big, 256, 256, 256, stream=0, prepared_bytes=ssg.ssg_infer_prepared_bytes(big))
+    assert e.value.status == ssg.SSG_ERR_WORKSPACE and "static" in str(e.value)
 
 
 def test_given_h_scale_and_counters_are_validated():
