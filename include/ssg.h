@@ -294,26 +294,29 @@ ssg_status ssg_adam_step(const ssg_adam_desc *desc, const void *grad, float *w, 
 ssg_status ssg_adam_view_state(int64_t n, int32_t step, const void *state, ssg_adam_state_view *out);
 
 /* ---- kernel timing for benchmarks (optional) --------------------------------
- * The one piece of state the library keeps, off by default.  While enabled,
- * every GEMM launch (and each pass of the Adam step) is bracketed by two HIP events recorded on the launch's
- * own stream (events are host objects; no device memory is allocated).
+ * The one piece of state the library keeps, off by default.  While enabled, every kernel launch of the
+ * library is bracketed by two HIP events recorded on the launch's own stream (events are host objects; no
+ * device memory is allocated).
  *   ssg_profile_enable(n)  n > 0: create n event pairs and start recording (records beyond n are
  *                          dropped); n = 0: stop and destroy the events.
- *   ssg_profile_read       waits for the recorded events, writes up to `cap` durations in
- *                          milliseconds and their tags (host arrays), clears the record list and
- *                          returns the number written, or a negative ssg_status.
- *                          tag = 2 * epilogue + a_fmt with epilogue 0 = plain store (y, dx, dW),
- *                          1 = fused SwiGLU forward (U, G, channel maxima), 2 = fused SwiGLU backward,
- *                          3 = fused SwiGLU product + E4M3 cast of the inference form;
- *                          9 and 10 are the two launches of the input gradient (first product to fp32
- *                          scratch; second product plus scratch).
- *                          The two passes of ssg_adam_step are recorded too: tag 32 = range pass,
- *                          33 = update pass. */
+ *   ssg_profile_select(t)  record only launches with tag t (so that the brackets do not perturb the other
+ *                          kernels of a timed region); t < 0 = every launch (the default).  Survives
+ *                          ssg_profile_enable.
+ *   ssg_profile_read       waits for the recorded events, writes up to `cap` durations in milliseconds, their
+ *                          tags and (bytes may be NULL) the algorithmic bytes of each launch (host arrays),
+ *                          clears the record list and returns the number written, or a negative ssg_status.
+ * Tags.  GEMMs (bytes = 0: priced in flops by the caller): 2 * epilogue + a_fmt with epilogue 0 = plain store
+ * (y: tag 0; a weight gradient: tag 1), 1 = fused SwiGLU forward (U, G, channel maxima: tag 2), 2 = fused SwiGLU
+ * backward (dH: tag 5), 3 = fused SwiGLU product + E4M3 cast of the inference form (tag 6); 11 = the input
+ * gradient, both products in one launch (9 and 10: its two launches on shapes where that form is not built);
+ * 16 = grouped launch {dH, dW3}; 17 = grouped launch {dX, dW1, dW2}.
+ * Elementwise passes (bytes = algorithmic bytes moved): 40 = per-tensor range, 41 = per-tensor cast, 42 = cast
+ * of the SwiGLU product from bf16 U, G with per-channel factors, 43 = cast of W3 with the inverse factors folded
+ * in, 44 = per-column range, 45 = small bookkeeping kernels (resets, factors, history update).
+ * Adam: 32 = range pass, 33 = update pass. */
 ssg_status ssg_profile_enable(int max_records);
-/* record only launches with this tag (so that the brackets do not perturb the other kernels of a timed
- * region); tag < 0 = every launch (the default).  Survives ssg_profile_enable. */
 ssg_status ssg_profile_select(int tag);
-int ssg_profile_read(float *ms, int *tags, int cap);
+int ssg_profile_read(float *ms, int *tags, double *bytes, int cap);
 
 #ifdef __cplusplus
 }

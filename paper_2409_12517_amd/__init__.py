@@ -95,7 +95,7 @@ _lib.ssg_mlp_view_saved.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg
 _lib.ssg_mlp_view_workspace.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_workspace_view)]
 _lib.ssg_profile_enable.argtypes = [c_int]
 _lib.ssg_profile_select.argtypes = [c_int]
-_lib.ssg_profile_read.argtypes = [POINTER(c_float), POINTER(c_int), c_int]
+_lib.ssg_profile_read.argtypes = [POINTER(c_float), POINTER(c_int), POINTER(ctypes.c_double), c_int]
 _lib.ssg_mlp_scaling_state_bytes.argtypes = []
 _lib.ssg_mlp_scaling_state_bytes.restype = c_size_t
 _lib.ssg_mlp_scaling_init.argtypes = [c_void_p, c_void_p]
@@ -255,13 +255,17 @@ def ssg_profile_select(tag: int) -> None:
     _check(_lib.ssg_profile_select(tag))
 
 
-def ssg_profile_read(cap: int):
-    """Returns (durations_ms, tags) of the GEMM launches recorded since the last read."""
+def ssg_profile_read(cap: int, with_bytes: bool = False):
+    """Returns (durations_ms, tags) of the launches recorded since the last read; with_bytes = True adds the
+    algorithmic bytes of each launch (0 for GEMMs) as a third list."""
     ms = (c_float * cap)()
     tags = (c_int * cap)()
-    n = _lib.ssg_profile_read(ms, tags, cap)
+    nbytes = (ctypes.c_double * cap)()
+    n = _lib.ssg_profile_read(ms, tags, nbytes, cap)
     if n < 0:
         raise SsgError(n, ssg_last_error())
+    if with_bytes:
+        return list(ms[:n]), list(tags[:n]), list(nbytes[:n])
     return list(ms[:n]), list(tags[:n])
 
 

@@ -12,7 +12,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssg.so")
-SOURCES = ["ssg_api.hip", "ssg_quant.hip", "ssg_gemm.hip", "ssg_adam.hip"]
+SOURCES = ["ssg_api.hip", "ssg_quant.hip", "ssg_gemm.hip", "ssg_gemm_bwd.hip", "ssg_adam.hip"]
 PROBE_LIB = os.path.join(HERE, "libssg_probe.so")
 PROBE_SOURCES = ["ssg_probe.hip"]
 

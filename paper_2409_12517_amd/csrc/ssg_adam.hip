@@ -243,11 +243,12 @@ void launch_adam_step(const AdamArgs &a, hipStream_t st) {
     };
     const unsigned grid_r = grid(8 * kRangeHalves, (size_t)1 << 20), grid_u = grid(8 * kUpdateHalves, 2048);
     // timing records (when enabled): tag 32 = range pass, 33 = update pass
-    profile_before(32, st);
+    const double gbytes = a.grad_bf16 ? 2.0 : 4.0;       // algorithmic bytes per element: gradient + two codes; update: + w in/out, bf16 copy, codes out
+    profile_before(32, st, (gbytes + 2.0) * (double)a.n);
     if (a.grad_bf16) hipLaunchKernelGGL((adam_range_kernel<true, kRangeHalves>), dim3(grid_r), dim3(kAdamThreads), 0, st, p);
     else hipLaunchKernelGGL((adam_range_kernel<false, kRangeHalves>), dim3(grid_r), dim3(kAdamThreads), 0, st, p);
     profile_after(st);
-    profile_before(33, st);
+    profile_before(33, st, (gbytes + 2.0 + 4.0 + 4.0 + (a.w_bf16 ? 2.0 : 0.0) + 2.0) * (double)a.n);
     if (a.grad_bf16) hipLaunchKernelGGL((adam_update_kernel<true, kUpdateHalves>), dim3(grid_u), dim3(kAdamThreads), 0, st, p);
     else hipLaunchKernelGGL((adam_update_kernel<false, kUpdateHalves>), dim3(grid_u), dim3(kAdamThreads), 0, st, p);
     profile_after(st);

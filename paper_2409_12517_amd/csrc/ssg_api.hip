@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -24,6 +25,13 @@ ssg_status fail(ssg_status code, const char *fmt, ...) {
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
     return code;
+}
+
+// Grouped launches of the backward GEMMs are on unless the environment says SSG_GEMM_GROUPING=0 (read once; a
+// switch for A/B timing, the results are the same either way).
+bool gemm_grouping_enabled() {
+    static const bool on = [] { const char *e = std::getenv("SSG_GEMM_GROUPING"); return !(e && e[0] == '0'); }();
+    return on;
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -147,6 +155,7 @@ ssg_status check_desc(const ssg_mlp_desc *d, const char *who) {
 struct ProfileState {
     std::vector<hipEvent_t> start, stop;
     std::vector<int> tag;
+    std::vector<double> bytes;
     int used = 0;
     int only_tag = -1;       // -1: record every launch; otherwise only launches with this tag
     bool open = false;       // a start event was recorded and waits for its stop
@@ -156,12 +165,13 @@ ProfileState g_prof;
 }  // namespace
 
 namespace ssg {
-void profile_before(int tag, hipStream_t st) {
+void profile_before(int tag, hipStream_t st, double bytes) {
     g_prof.open = false;
     if (g_prof.only_tag >= 0 && tag != g_prof.only_tag) return;
     if (g_prof.used >= (int)g_prof.start.size()) return;
     if (hipEventRecord(g_prof.start[g_prof.used], st) != hipSuccess) return;
     g_prof.tag[g_prof.used] = tag;
+    g_prof.bytes[g_prof.used] = bytes;
     g_prof.open = true;
 }
 void profile_after(hipStream_t st) {
@@ -193,10 +203,11 @@ ssg_status ssg_profile_enable(int max_records) {
         g_prof.stop.push_back(b);
     }
     g_prof.tag.assign((size_t)max_records, 0);
+    g_prof.bytes.assign((size_t)max_records, 0.0);
     return SSG_OK;
 }
 
-int ssg_profile_read(float *ms, int *tags, int cap) {
+int ssg_profile_read(float *ms, int *tags, double *bytes, int cap) {
     if (!ms || !tags || cap < 0) return fail(SSG_ERR_ARG, "ssg_profile_read: bad argument");
     int n = g_prof.used < cap ? g_prof.used : cap;
     for (int i = 0; i < n; ++i) {
@@ -204,6 +215,7 @@ int ssg_profile_read(float *ms, int *tags, int cap) {
             hipEventElapsedTime(&ms[i], g_prof.start[i], g_prof.stop[i]) != hipSuccess)
             return fail(SSG_ERR_HIP, "ssg_profile_read: event query failed");
         tags[i] = g_prof.tag[i];
+        if (bytes) bytes[i] = g_prof.bytes[i];
     }
     g_prof.used = 0;
     return n;
@@ -826,8 +838,11 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     g3.layout = 2;                                                                     // dY^ [T,d] = [K,M], h^ [T,f] = [K,N]
     g3.A = wk + Wl.dy_q; g3.B = sv + L.h_q; g3.sa = wsc + W_SDY; g3.sb = desc->smooth ? nullptr : s;
     g3.col_scale = desc->smooth ? sinv : nullptr; g3.C = dW3; g3.c_f32 = dw_f32;
-    // a13: dX = dU^ w1^ / (sdu sw1) + dG^ w2^ / (sdg sw2): two launches, the first product through fp32 scratch
+    // a13: dX = dU^ w1^ / (sdu sw1) + dG^ w2^ / (sdg sw2).  One launch that runs both products into the same
+    // accumulators where the shape allows (whole K steps and tile columns); otherwise two launches, the first
+    // product through fp32 scratch
     float *dx_tmp = reinterpret_cast<float *>(wk + Wl.dx_tmp);
+    const bool dx_one = ssg::gemm_sum_in_one_launch_ok(dm, f);
     ssg::GemmArgs g4a, g4b;
     g4a.epilogue = ssg::EPI_STORE; g4a.a_fmt = ssg::kE5M2; g4a.M = T; g4a.N = dm; g4a.K = f; g4a.part = 1;
     g4a.layout = 1;                                                                    // w1^ [f,d] = [K,N]
@@ -835,14 +850,24 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     g4b = g4a; g4b.part = 2;
     g4b.A = wk + Wl.dg_q; g4b.B = sv + L.w2_q; g4b.sa = wsc + W_SDG; g4b.sb = sc + S_SW2; g4b.add = dx_tmp;
     g4b.C = dx; g4b.c_f32 = desc->y_dtype == SSG_F32;
+    if (dx_one) {
+        g4a.part = 3; g4a.C = dx; g4a.c_f32 = g4b.c_f32;
+        g4a.A_ph2 = g4b.A; g4a.B_ph2 = g4b.B; g4a.sa_ph2 = g4b.sa; g4a.sb_ph2 = g4b.sb;
+    }
     // a14: dW1 = dU^T x^ / (sdu sx), dW2 = dG^T x^ / (sdg sx)
     ssg::GemmArgs g5a, g5b;
     g5a.epilogue = ssg::EPI_STORE; g5a.a_fmt = ssg::kE5M2; g5a.M = f; g5a.N = dm; g5a.K = T;
     g5a.layout = 2;                                                                    // dU^ [T,f] = [K,M], x^ [T,d] = [K,N]
     g5a.A = wk + Wl.du_q; g5a.B = sv + L.x_q; g5a.sa = wsc + W_SDU; g5a.sb = sc + S_SX; g5a.C = dW1; g5a.c_f32 = dw_f32;
     g5b = g5a; g5b.A = wk + Wl.dg_q; g5b.sa = wsc + W_SDG; g5b.C = dW2;
-    for (const ssg::GemmArgs *a : {&g, &g3, &g4a, &g4b, &g5a, &g5b})
+    for (const ssg::GemmArgs *a : {&g, &g3, &g4a, &g5a, &g5b})
         if (!ssg::gemm_args_ok(*a)) return fail(SSG_ERR_ARG, "ssg_mlp_bwd: internal GEMM arguments");
+    if (!dx_one && !ssg::gemm_args_ok(g4b)) return fail(SSG_ERR_ARG, "ssg_mlp_bwd: internal GEMM arguments");
+    // Grouped launches: {dH, dW3} (both read dY^; dW3 does not wait for dU, dG) and {dX, dW1, dW2} share one grid
+    // each, so that a partly filled last round of workgroups is paid once per group and the epilogue traffic of one
+    // GEMM runs under the main loops of the others
+    const ssg::GemmArgs *group_a[2] = {&g, &g3}, *group_b[3] = {&g4a, &g5a, &g5b};
+    const bool grouped = gemm_grouping_enabled() && dx_one && ssg::gemm_group_ok(group_a, 2) && ssg::gemm_group_ok(group_b, 3);
     if ((rc = check_entry("ssg_mlp_bwd")) != SSG_OK) return rc;
 
     ssg::launch_fill_u32(wscb, (Wl.partials - Wl.scalars) / 4 + 3 * ssg::kAmaxSlotWords, 0u, st);
@@ -860,7 +885,8 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     ssg::launch_cast(c, st);
     c.record = nullptr;
 
-    ssg::launch_gemm(g, st);
+    if (grouped) ssg::launch_gemm_group(group_a, 2, st);
+    else ssg::launch_gemm(g, st);
 
     // a11: two tensors, two E5M2 scales (their ranges came out of the epilogue above either way)
     auto cast_grad = [&](const void *src, float *amax_slots, float *amax_out, float *scale_out, uint8_t *dst) {
@@ -869,14 +895,17 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
         c.amax = amax_slots; c.amax_out = amax_out; c.scale_in = nullptr;
         ssg::launch_cast(c, st);
     };
-    // (running each cast right before the GEMMs that read its output, or dW3 first, measured the same within 0.3 %)
     cast_grad(wk + Wl.dU, reinterpret_cast<float *>(part_du), wsc + W_AMAX_DU, wsc + W_SDU, wk + Wl.du_q);
     cast_grad(wk + Wl.dG, reinterpret_cast<float *>(part_dg), wsc + W_AMAX_DG, wsc + W_SDG, wk + Wl.dg_q);
-    ssg::launch_gemm(g3, st);
-    ssg::launch_gemm(g4a, st);
-    ssg::launch_gemm(g4b, st);
-    ssg::launch_gemm(g5a, st);
-    ssg::launch_gemm(g5b, st);
+    if (grouped) {
+        ssg::launch_gemm_group(group_b, 3, st);
+    } else {
+        ssg::launch_gemm(g3, st);
+        ssg::launch_gemm(g4a, st);
+        if (!dx_one) ssg::launch_gemm(g4b, st);
+        ssg::launch_gemm(g5a, st);
+        ssg::launch_gemm(g5b, st);
+    }
     if (state) {
         ssg::ScalingUpdate u;
         u.pow2 = pow2; u.count = 3;

@@ -1,0 +1,739 @@
+// FP8 MFMA GEMM for gfx950 with the block's fused epilogues: the code of one output tile (device side).
+// Included by the translation units that instantiate the kernels (ssg_gemm.hip, ssg_gemm_bwd.hip).
+//
+//   C[m,n] = sum_k A[m,k] * B[n,k]      A [M,K], B [N,K] FP8 codes, K contiguous
+//
+// (the inner products of Eq. 2, the last linear layer of the display after it,
+// and their gradient contractions).  fp32 accumulation on the matrix cores with
+// v_mfma_f32_32x32x64_f8f6f4, the only FP8 form that reaches the full rate on
+// this chip; its per-operand format selectors take E4M3 or E5M2.
+//
+// Workgroup: 256 threads = 4 waves as 2 (M) x 2 (N), one per SIMD; tile 256 x 256 x 128;
+// each wave owns 128 x 128 outputs = 4 x 4 MFMA blocks (256 accumulator registers).
+// Operand tiles are streamed global -> LDS with 16-byte direct-to-LDS loads (no staging
+// registers) into a ring of five 32 KB tiles.  A row of a tile is 128 bytes; the eight
+// 16-byte chunks of a row are stored XOR-permuted by the row index so that the lanes that
+// read the same logical chunk of different rows spread over all banks.
+//
+// Epilogues:
+//   STORE       C = acc / (sa*sb) [* col_scale[n]] [+ addend], bf16 or fp32.  A sum of two
+//               products (the input gradient) runs as two launches: the first leaves its
+//               scaled product as fp32 scratch, the second adds it before rounding.
+//   SWIGLU      B tile = 128 rows of W1 and the same 128 rows of W2, so a wave
+//               holds u and g of the same (t,i): stores bf16 U, G and folds
+//               max_t |u * Swish(g)| into the per-channel maxima (Section 4.4).
+//   SWIGLU_BWD  acc -> dH (times the channel factor s_i), reads bf16 U, G, stores
+//               bf16 dU, dG and folds their amax.
+//   SWIGLU_Q    as SWIGLU, but stores only the E4M3 cast of u * Swish(g) (inference form).
+//   SWIGLU_BWD_Q as SWIGLU_BWD, but dU, dG leave as E5M2 codes under given scales (delayed scaling).
+#pragma once
+#include "ssg_device.h"
+#include "ssg_internal.h"
+
+namespace ssg {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef __attribute__((address_space(1))) const void *global_void_ptr;
+
+constexpr int BM = 256, BN = 256, BK = 128;
+constexpr int kUnitBytes = BM * BK;               // one operand tile of one K step: 256 rows x 128 B = 32 KB
+constexpr int kUnits = 5;                         // ring of operand tiles in LDS: all 160 KB
+
+static __device__ uint4 g_zero_chunk = {0u, 0u, 0u, 0u}; // source of the zero fill of a ragged K tail (one per translation unit)
+
+struct GemmParams {
+    const uint8_t *A, *B, *B2;
+    int64_t M, N, K;
+    const float *sa, *sb, *sb2, *col_scale;
+    void *C, *C2;
+    const uint16_t *U, *G;
+    uint32_t *camax_bits, *amax_bits, *amax_bits2;
+    int c_f32;
+    int tiles_m, tiles_n;
+    float *tmp;          // fp32 [M, N] scratch for the two-launch form of a sum of two products (may be null)
+    const float *add;    // gemm_kernel<.., ADD>: fp32 [M, N] added before the store
+    const float *q_scale, *q_scale2;        // EPI_SWIGLU_BWD_Q: scales of dU, dG
+    float *q_scale_out, *q_scale_out2;      //                   where the scales used are recorded
+    uint16_t *keep_u, *keep_g;              //                   optional: the bf16 dU, dG the codes were cast from
+    // PART = 3 (a sum of two products in one tile): operands and scales of the second product, same shapes
+    const uint8_t *A_ph2, *B_ph2;
+    const float *sa_ph2, *sb_ph2;
+};
+
+// An LDS row holds the 128 bytes (eight 16-byte chunks, one full cache line) of one matrix row for one
+// K step.  Two rows fill the 256-byte bank period, so rows r, r+2, r+4, ... would collide when 16
+// lanes read the same chunk of 16 consecutive rows; XOR-ing the chunk index with (r >> 1) & 7
+// spreads 16 consecutive rows over the sixteen 16-byte bank groups.
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+
+// Direct-to-LDS loads are issued through inline assembly: the compiler would otherwise wait for
+// ALL outstanding LDS-DMA loads before every ds_read (it cannot tell the two LDS stages apart),
+// which serialises memory latency with the MFMA work.  M0 carries the wave-uniform LDS
+// destination; lane i lands at M0 + 16*i.  The vmcnt waits are placed by hand in the main loop.
+__device__ __forceinline__ void dma16(const uint8_t *g, uint32_t lds_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_addr), "v"(g) : "memory", "m0");
+#else
+    (void)g; (void)lds_addr;
+#endif
+}
+
+// Same with a wave-uniform 64-bit base in SGPRs and a 32-bit per-lane byte offset: no VALU work per issue.
+__device__ __forceinline__ void dma16_s(const uint8_t *base_uniform, uint32_t lane_off, uint32_t lds_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base_uniform) : "memory", "m0");
+#else
+    (void)base_uniform; (void)lane_off; (void)lds_addr;
+#endif
+}
+
+template <int AFMT>
+__device__ __forceinline__ v16f mfma(const v8i &a, const v8i &b, const v16f &c) {
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, AFMT, 0, 0, 0, 0, 0);
+}
+
+// The dequantization factor 1 / (sa * sb).  The product of two binary32 scales can leave the binary32 range
+// (the scale of a gradient tensor with a tiny range reaches 1e38) and its reciprocal can fall among the
+// subnormals, so it is formed in binary64 and handed out as a normal binary32 factor `a` (rounded once) times
+// an exact power of two `post`, which is 1 except in those extreme cases.
+struct Dequant { float a, post; };
+__device__ __forceinline__ Dequant inv_scale_product(const float *sa, const float *sb) {
+    double p = 1.0;
+    if (sa) p = (double)*sa;
+    if (sb) p *= (double)*sb;
+    const double r = 1.0 / p;
+    Dequant d;
+    d.post = 1.0f;
+    if (r < 0x1p-100) d.post = 0x1p-96f;
+    else if (r > 0x1p100) d.post = 0x1p96f;
+    d.a = (float)(r / (double)d.post);
+    return d;
+}
+
+// Workgroup -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its
+// own L2, so give every XCD a contiguous range of a tile order in which any 32 consecutive tiles
+// (one per CU of the XCD) form a 4 x 8 patch: 12 operand tiles fetched for 32 computed.
+// `vblock` is the workgroup's index among the workgroups of this GEMM (the launch's blockIdx.x, or the index
+// inside its share of a grouped launch, which keeps vblock % 8 = the XCD).
+__device__ __forceinline__ void map_tile(const GemmParams &p, int vblock, int &tile_m, int &tile_n) {
+    const int total = p.tiles_m * p.tiles_n;
+    const int per_xcd = (total + 7) / 8;
+    int t = (vblock & 7) * per_xcd + (vblock >> 3);
+    if ((total & 7) != 0) {
+        // ranges are uneven: fall back to the identity when the remapped id would leave the grid
+        const int full = total & ~7;
+        t = vblock < full ? (vblock & 7) * (full >> 3) + (vblock >> 3) : vblock;
+    }
+    constexpr int kGroupM = 4;
+    const int group_tiles = kGroupM * p.tiles_n;
+    const int gidx = t / group_tiles;
+    const int first_m = gidx * kGroupM;
+    const int gsize = (p.tiles_m - first_m) < kGroupM ? (p.tiles_m - first_m) : kGroupM;
+    const int in_group = t - gidx * group_tiles;
+    tile_m = first_m + in_group % gsize;
+    tile_n = in_group / gsize;
+}
+
+// ------------------------------------------------------------------------------------------------
+// 4 waves (one per SIMD), 128 x 128 wave tiles: 256 accumulator registers per lane (the AGPR half of
+// the register file); every A and B row block is read from LDS by only two waves.  With a single
+// wave per SIMD there is no partner to hide stalls, so the wave software-pipelines itself: while the
+// 16 MFMAs of one 64-wide K half run from one fragment set, the next half's fragments are read into
+// the other set, one fragment after every second MFMA, and one direct-to-LDS load of the new operand
+// tiles follows every pair of MFMAs throughout the K step.  One barrier per K step, in its middle: by
+// then every wave holds both halves of step k in registers, so the barrier both retires step k's ring
+// slots and publishes step k+1 (each wave first waits for its own DMA share).
+constexpr int kThreads = 256;
+
+// PART (plain store only) names the role in a sum of two products run as two launches: 1 = first half (stores
+// its scaled product as fp32 scratch; the same code as 0, a separate symbol so that profiles tell it from the
+// weight-gradient GEMMs), 2 = second half (the fp32 matrix p.add [M, N] is added to the scaled result before it
+// is rounded and stored).  0 = an ordinary GEMM.
+// LAY names how the operands lie in memory: 0 = both with the contraction index contiguous (A [M,K], B [N,K]);
+// 1 = B "K-major" (stored [K,N], N contiguous); 2 = both K-major (A stored [K,M]).  A K-major tile is streamed
+// into LDS as 128 rows of K x 256 bytes and its MFMA fragments are read with the transposing LDS load, so the
+// backward contractions read the forward's quantized tensors as they are: no transposed copies exist.
+// PART = 3: the sum of two products in one tile -- the K loop runs twice, over (A, B) and then over (A_ph2, B_ph2)
+// of the same shapes, and the accumulators are rescaled by the ratio of the two dequantization factors in
+// between, so that one epilogue with the second factor finishes both.
+template <int EPI, int AFMT, int PART, int LAY>
+__device__ __forceinline__ void gemm_tile(const GemmParams &p, const int vblock, uint8_t *smem) {
+    constexpr bool ADD = PART == 2;
+    constexpr bool TWO = PART == 3;
+    static_assert(!TWO || EPI == EPI_STORE, "a sum of two products ends in the plain store epilogue");
+    constexpr bool AKM = LAY == 2, BKM = LAY >= 1;
+    constexpr bool kBwd = EPI == EPI_SWIGLU_BWD || EPI == EPI_SWIGLU_BWD_Q;     // dH -> dU, dG through the SwiGLU derivative
+    static_assert(!(BKM && (EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_Q)), "the dual-B forms take K-contiguous operands");
+    constexpr bool kDual = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_Q;     // B tile = 128 rows of W1 + 128 rows of W2
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int l = tid & 63;            // (not const: see the note at the epilogue)
+    const int wm = w >> 1, wn = w & 1;
+    int tile_m, tile_n;
+    map_tile(p, vblock, tile_m, tile_n);
+    const int64_t m0 = (int64_t)tile_m * BM;
+    const int64_t n0 = (int64_t)tile_n * (kDual ? BN / 2 : BN);
+
+    // DMA slots: a unit is 32 instructions of 1 KB, 8 per wave.  K-contiguous operand: an instruction is 8 rows x
+    // 128 B (rows (8w+j)*8 + l/8).  K-major operand: 4 rows of K x 256 B (K rows (8w+j)*4 + l/16); the sixteen
+    // 16-byte chunks of a row are permuted so that a transposing read is free of bank conflicts: chunk c of K row k
+    // sits at position c ^ (k & 7) ^ (((c & 1) ^ (k >> 5 & 1)) << 3).  The 32 lanes of one K group read eight
+    // consecutive K rows of two adjacent chunks: the XOR with k & 7 spreads the rows over the eight positions of a
+    // half row, the chunk's own low bit picks the half, so the 32 words cover all 64 banks exactly once.
+    const int lrow = l >> 3;
+    const int chunk_even = (l & 7) ^ swz(lrow), chunk_odd = (l & 7) ^ swz(8 + lrow);
+    // the chunk that belongs at position `pos` of K row k (the map is its own inverse in the low three bits)
+    auto kmaj_chunk = [](int k, int pos) {
+        const int low = (pos ^ k) & 7;
+        return low | ((((pos >> 3) ^ (k >> 5) ^ low) & 1) << 3);
+    };
+    uint32_t a_lane[8], b_lane[8];
+    const uint8_t *b_src = p.B;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int row = (w * 8 + j) * 8 + lrow;
+        const int ck = ((j & 1) ? chunk_odd : chunk_even) * 16;
+        const int kr = (w * 8 + j) * 4 + (l >> 4);                     // K-major: K row of this lane's chunk
+        const int ckm = kmaj_chunk(kr, l & 15) * 16;                    //          and the chunk it fetches
+        if (AKM) {
+            a_lane[j] = (uint32_t)((int64_t)kr * p.M + m0) + ckm;
+        } else {
+            int64_t gm = m0 + row;
+            gm = gm < p.M ? gm : p.M - 1;
+            a_lane[j] = (uint32_t)(gm * p.K) + ck;
+        }
+        if (BKM) {
+            b_lane[j] = (uint32_t)((int64_t)kr * p.N + n0) + ckm;
+        } else {
+            int64_t gn;
+            if (kDual) gn = n0 + (row & 127);
+            else gn = n0 + row;
+            gn = gn < p.N ? gn : p.N - 1;
+            b_lane[j] = (uint32_t)(gn * p.K) + ck;
+        }
+    }
+    if (kDual && w >= 2) b_src = p.B2;      // waves 2, 3 fill tile rows 128..255
+    const uint32_t lds_w = (uint32_t)(w * 8) * 1024u;
+
+    // LDS byte offset of this lane's two 16-byte chunks of a fragment row, per K half; the row block of a
+    // fragment adds a wave-uniform base and a compile-time multiple of 4 KB (an instruction immediate)
+    uint32_t frag_off[2][2];
+#pragma unroll
+    for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            frag_off[kh][e] = (uint32_t)((l & 31) * BK + (((kh * 4 + (l >> 5) * 2 + e) ^ swz(l & 31)) << 4));
+    // K-major operand: lane offsets of the transposing reads.  In every group of 16 lanes the even lanes supply
+    // the 8-byte words whose byte j goes to output lane j, the odd lanes those for output lane 8+j; lane p of a
+    // group therefore points at K row p/2 (of eight) and at half p%2 of the 16-byte chunk that holds the group's
+    // 16 rows of the 32-row block.  Four such reads (K rows +0, +8, +16, +24) make one fragment.
+    uint32_t tr_a[4], tr_b[4];
+    {
+        const int g16 = l >> 4, kg = g16 >> 1, g1 = g16 & 1, t = (l & 15) >> 1, e = l & 1;
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            // position of chunk c in K row k = kg * 32 + t (+ multiples of 8 and 64, which do not enter)
+            const int ca = wm * 8 + rb * 2 + g1, cb = wn * 8 + rb * 2 + g1;
+            const int pa = ((ca ^ t) & 7) | ((((ca >> 3) ^ kg ^ ca) & 1) << 3);
+            const int pb = ((cb ^ t) & 7) | ((((cb >> 3) ^ kg ^ cb) & 1) << 3);
+            tr_a[rb] = (uint32_t)((kg * 32 + t) * 256 + (pa << 4) + e * 8);
+            tr_b[rb] = (uint32_t)((kg * 32 + t) * 256 + (pb << 4) + e * 8);
+        }
+    }
+    const uint32_t a_wave_base = (uint32_t)(wm * 128) * BK;
+    const uint32_t b_wave_base = (uint32_t)(kDual ? wn * 64 : wn * 128) * BK;
+    auto b_block_off = [](int nb) -> uint32_t {      // SWIGLU: blocks 0, 1 from the W1 rows, 2, 3 from the W2 rows
+        return (uint32_t)(kDual ? (nb >> 1) * 128 + (nb & 1) * 32 : nb * 32) * BK;
+    };
+
+    v16f acc[4][4];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mb][nb][i] = 0.0f;
+
+    const int nk = (int)((p.K + BK - 1) / BK);
+    // the staging patch of the epilogue (one 32 x 128 slab of a wave's accumulators at a time), also used where a
+    // sum of two products changes the units of its accumulators
+    constexpr int kPitch = 136;                        // floats; 4 rows apart lands on the other 32 banks
+    float *stg = reinterpret_cast<float *>(smem) + w * (32 * kPitch);
+    // where accumulator register i of column block nb of a slab lies in the patch
+    auto stg_at = [&](int nb, int i) { return ((i >> 2) * 8 + (l >> 5) * 4 + (i & 3)) * kPitch + nb * 32 + (l & 31); };
+#pragma nounroll
+    for (int phase = 0; phase < (TWO ? 2 : 1); ++phase) {
+        const uint8_t *a_src = (TWO && phase == 1) ? p.A_ph2 : p.A;
+        if (TWO && phase == 1) b_src = p.B_ph2;
+        const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
+        // general issue of unit u (unit u = A (even) / B (odd) tile of K step u/2, ring slot u % 5): any
+        // K, zero fill of a ragged K tail
+        auto issue_unit = [&](int u) {
+            const int k = u >> 1;
+            if (k >= nk) return;
+            const uint32_t dst = smem_base + (uint32_t)(u % kUnits) * kUnitBytes + lds_w;
+            const int64_t kbase = (int64_t)k * BK;
+            const int64_t Kseg = p.K;
+            const bool is_b = (u & 1) != 0;
+            const uint8_t *base = is_b ? b_src : a_src;
+            const uint8_t *zero = reinterpret_cast<const uint8_t *>(&g_zero_chunk);
+            const bool kmajor = is_b ? BKM : AKM;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (kmajor) {
+                    const int kr = (w * 8 + j) * 4 + (l >> 4);
+                    const int64_t col = (is_b ? n0 : m0) + kmaj_chunk(kr, l & 15) * 16;
+                    const int64_t ld = is_b ? p.N : p.M;
+                    const bool ok = kbase + kr < Kseg && col < ld;      // extents are multiples of 16: a chunk is all in or out
+                    dma16(ok ? base + (kbase + kr) * ld + col : zero, dst + j * 1024);
+                    continue;
+                }
+                const int row = (w * 8 + j) * 8 + lrow;
+                const int ck = ((j & 1) ? chunk_odd : chunk_even) * 16;
+                int64_t g = (is_b ? n0 + (kDual ? (row & 127) : row) : m0 + row);
+                const int64_t lim = is_b ? p.N : p.M;
+                g = g < lim ? g : lim - 1;
+                const bool k_ok = kbase + ck < Kseg;
+                dma16(k_ok ? base + g * Kseg + kbase + ck : zero, dst + j * 1024);
+            }
+        };
+        v8i fa[2][4], fb[2][4];
+        // The i-th fragment read of a K half, in the order the MFMAs need them (B0 A0 B1 B2 B3 A1 A2 A3:
+        // the first four MFMAs use A0 with B0..B3), from ring slots sa / sb; g = 0..3: A row blocks,
+        // 4..7: B row blocks
+        auto load_frag = [&](int set, uint32_t sa, uint32_t sb, int kh, int i) {
+            constexpr int kOrder[8] = {4, 0, 5, 6, 7, 1, 2, 3};
+            const int g = kOrder[i];
+            if ((g < 4 && AKM) || (g >= 4 && BKM)) {
+                typedef int v2i_t __attribute__((ext_vector_type(2)));
+                typedef __attribute__((address_space(3))) v2i_t *lds_v2i_ptr;
+                const uint8_t *base = smem + (g < 4 ? sa * kUnitBytes + tr_a[g] : sb * kUnitBytes + tr_b[g - 4]) + kh * 64 * 256;
+                const v2i_t q0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(base));
+                const v2i_t q1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(base + 8 * 256));
+                const v2i_t q2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(base + 16 * 256));
+                const v2i_t q3 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(base + 24 * 256));
+                const v8i f = v8i{q0.x, q0.y, q1.x, q1.y, q2.x, q2.y, q3.x, q3.y};
+                if (g < 4) fa[set][g] = f; else fb[set][g - 4] = f;
+                return;
+            }
+            const uint32_t ub = g < 4 ? sa * kUnitBytes + a_wave_base : sb * kUnitBytes + b_wave_base;   // uniform
+            const uint32_t imm = g < 4 ? (uint32_t)(g * 32 * BK) : b_block_off(g - 4);
+            const uint4 lo = *reinterpret_cast<const uint4 *>(smem + (frag_off[kh][0] + ub) + imm);
+            const uint4 hi = *reinterpret_cast<const uint4 *>(smem + (frag_off[kh][1] + ub) + imm);
+            const v8i f = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            if (g < 4) fa[set][g] = f; else fb[set][g - 4] = f;
+        };
+        auto mfma2 = [&](int set, int g) {          // MFMAs 2g and 2g+1 of the 16 of a half step
+#pragma unroll
+            for (int q = 2 * g; q < 2 * g + 2; ++q)
+                acc[q >> 2][q & 3] = mfma<AFMT>(fa[set][q >> 2], fb[set][q & 3], acc[q >> 2][q & 3]);
+        };
+        // s_waitcnt lgkmcnt(0) through the builtin (gfx9 encoding: vmcnt and expcnt fields at their
+        // maxima), so that the compiler's own wait bookkeeping sees it
+        auto wait_lds = [&]() { __builtin_amdgcn_s_waitcnt(0xC07F); };
+
+        // Schedule of a K step k (units 2k, 2k+1 in ring slots sa, sb):
+        //   first half   16 MFMAs on fragment set 0 (k, K half 0); reads (k, half 1) into set 1;
+        //                issues unit 2k+4 (A of step k+2) into the slot that B of step k-1 left
+        //   barrier      each wave first waits for its share of units 2k+2, 2k+3 and for its LDS reads:
+        //                step k's slots are free, step k+1 is visible to all
+        //   second half  16 MFMAs on set 1; reads (k+1, half 0) into set 0; issues unit 2k+5 (B of
+        //                step k+2) into the slot of unit 2k
+        // so one DMA instruction follows every pair of MFMAs throughout and the texture path never
+        // sees a burst.
+        // (a K-major operand also needs its 256 tile columns to exist: the fast body does no column check)
+        const bool whole = (p.K % BK) == 0 && (!AKM || m0 + BM <= p.M) && (!BKM || n0 + BN <= p.N);
+        const int64_t a_step = AKM ? (int64_t)BK * p.M : BK, b_step = BKM ? (int64_t)BK * p.N : BK;   // bytes per K step
+        if (TWO || (whole && nk >= 2)) {
+            // the first four units from wave-uniform bases and the lane offsets the steady state uses
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t dst = smem_base + (uint32_t)u * kUnitBytes + lds_w;
+                const uint8_t *base = (u & 1) ? b_src + (u >> 1) * b_step : a_src + (u >> 1) * a_step;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) dma16_s(base, (u & 1) ? b_lane[j] : a_lane[j], dst + j * 1024);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) issue_unit(u);
+        }
+        if (nk >= 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");       // units 0 and 1 have landed
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    #pragma unroll
+        for (int g = 0; g < 8; ++g) load_frag(0, 0, 1, 0, g);
+
+        // Steady state: when every K step is whole, the steps whose new units exist run a body without
+        // any per-instruction check: wave-uniform source pointers, lane offsets from registers.  The
+        // last two steps, and every step of a ragged shape, take the general body.
+        // (a sum of two products is launched on whole shapes with at least two K steps only: no general body)
+        const int kfast = (TWO || whole) ? (nk > 2 ? nk - 2 : 0) : 0;
+        uint32_t sa = 0, sb = 1, sp = 4;             // ring slots of units 2k, 2k+1 and 2k+4
+        auto next_slot = [](uint32_t s) { const uint32_t t = s + 2; return t >= (uint32_t)kUnits ? t - kUnits : t; };
+        // wave-uniform sources of the units issued during step k (K step k+2): running pointers in scalar registers
+        const uint8_t *ua = a_src + 2 * a_step, *ub = b_src + 2 * b_step;
+        for (int k = 0; k < kfast; ++k) {
+            const uint32_t sa_n = next_slot(sa), sb_n = next_slot(sb);
+            const uint32_t d4 = smem_base + sp * kUnitBytes + lds_w;
+            const uint32_t d5 = smem_base + sa * kUnitBytes + lds_w;
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                mfma2(0, g);
+                load_frag(1, sa, sb, 1, g);
+                dma16_s(ua, a_lane[g], d4 + g * 1024);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");       // all but unit 2k+4 have landed
+            wait_lds();
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                mfma2(1, g);
+                load_frag(0, sa_n, sb_n, 0, g);
+                dma16_s(ub, b_lane[g], d5 + g * 1024);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            sp = sb; sa = sa_n; sb = sb_n;
+            ua += a_step; ub += b_step;
+        }
+        for (int k = kfast; k < nk; ++k) {
+            const uint32_t sa_n = next_slot(sa), sb_n = next_slot(sb);
+            if (!TWO) issue_unit(2 * k + 4);
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                mfma2(0, g);
+                load_frag(1, sa, sb, 1, g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (k + 2 < nk) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            wait_lds();
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            if (!TWO) issue_unit(2 * k + 5);
+            // (after the last step the fragment reads touch a stale slot and are never used)
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                mfma2(1, g);
+                load_frag(0, sa_n, sb_n, 0, g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            sa = sa_n; sb = sb_n;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (TWO && phase == 0) {
+            // The accumulators hold the first product in units of 1 / (sa sb); the second accumulates in units of
+            // 1 / (sa_ph2 sb_ph2).  They change units on a round trip through the wave's LDS patch (the ring is
+            // drained here): stored from their registers, multiplied in place by ordinary vector code, loaded
+            // back.  (Multiplying them in registers makes this compiler shuffle all 256 of them through the other
+            // half of the register file and spill.)
+            asm volatile("" : "+v"(l));      // as at the epilogue: keep this block's lane arithmetic inside the block
+            const float rho = (float)(((double)*p.sa_ph2 * (double)*p.sb_ph2) / ((double)*p.sa * (double)*p.sb));
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        stg[stg_at(nb, i)] = acc[mb][nb][i];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int e = (q * 64 + l) * 4;
+                    float4 *at = reinterpret_cast<float4 *>(stg + (e >> 7) * kPitch + (e & 127));
+                    float4 v = *at;
+                    v.x *= rho; v.y *= rho; v.z *= rho; v.w *= rho;
+                    *at = v;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        acc[mb][nb][i] = stg[stg_at(nb, i)];
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            __syncthreads();            // the patches overlap the ring slots the next product's first loads fill
+        }
+    }
+
+    // ---- epilogue: per-wave LDS patch, one 32 x 128 slab (mb) at a time
+    // (In the two-product form the loop above is executed twice; the compiler would compute the epilogue's lane
+    // arithmetic before it and spill it across.  The empty statement makes the lane id opaque from here on.)
+    if (TWO) asm volatile("" : "+v"(l));
+    auto stage_slab = [&](int mb) {
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                stg[stg_at(nb, i)] = acc[mb][nb][i];
+    };
+    auto load8 = [&](int r, int c, float (&v)[8]) {
+        const float4 a = *reinterpret_cast<const float4 *>(stg + r * kPitch + c);
+        const float4 b = *reinterpret_cast<const float4 *>(stg + r * kPitch + c + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    };
+    auto pack_bf16x8 = [&](const float (&v)[8]) {
+        uint32_t q[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) q[k] = pack_bf16x2(v[2 * k], v[2 * k + 1]);
+        return make_uint4(q[0], q[1], q[2], q[3]);
+    };
+    auto unpack_bf16x8 = [&](const uint4 q, float (&v)[8]) {
+        const uint32_t w4[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[2 * k] = __uint_as_float(w4[k] << 16);
+            v[2 * k + 1] = __uint_as_float(w4[k] & 0xffff0000u);
+        }
+    };
+
+    if (EPI == EPI_STORE || kBwd) {
+        // lane -> (row of the slab in 8 passes of 4 rows, 8 columns c8 of the wave's 128)
+        const int c8 = (l & 15) * 8;
+        const int64_t col = n0 + wn * 128 + c8;
+        const bool col_ok = col < p.N;
+        const Dequant dq = TWO ? inv_scale_product(p.sa_ph2, p.sb_ph2) : inv_scale_product(p.sa, p.sb);
+        const float alpha = dq.a;
+        const bool post = dq.post != 1.0f;               // wave-uniform, false except for extreme scales
+        float f[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) f[k] = alpha;
+        if (p.col_scale && col_ok) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) f[k] = __fmul_rn(alpha, p.col_scale[col + k]);
+        }
+        // running |.| maxima of the stored dU, dG as floats: rounding to bf16 is monotone, so the
+        // maximum of the rounded values is the rounded maximum (taken once, at the end); fmaxf drops NaN
+        float du_maxf = 0.0f, dg_maxf = 0.0f;
+        float q_su = 1.0f, q_sg = 1.0f;
+        if (EPI == EPI_SWIGLU_BWD_Q) {
+            q_su = *p.q_scale; q_sg = *p.q_scale2;
+            if (vblock == 0 && tid == 0) { *p.q_scale_out = q_su; *p.q_scale_out2 = q_sg; }
+        }
+        uint4 ru[2][8], rg[2][8];
+        auto fetch_ug = [&](int mb) {                  // the slab's stored U, G (or addend): rows in 8 passes of 4
+            if (!kBwd && !ADD) return;
+#pragma unroll
+            for (int pass = 0; pass < 8; ++pass) {
+                const int64_t row = m0 + wm * 128 + mb * 32 + pass * 4 + (l >> 4);
+                if (col_ok && row < p.M) {
+                    const size_t at = (size_t)row * (size_t)p.N + (size_t)col;
+                    if (ADD) {
+                        ru[mb & 1][pass] = *reinterpret_cast<const uint4 *>(p.add + at);
+                        rg[mb & 1][pass] = *reinterpret_cast<const uint4 *>(p.add + at + 4);
+                    } else {
+                        ru[mb & 1][pass] = *reinterpret_cast<const uint4 *>(p.U + at);
+                        rg[mb & 1][pass] = *reinterpret_cast<const uint4 *>(p.G + at);
+                    }
+                }
+            }
+        };
+        fetch_ug(0);
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            if (mb + 1 < 4) fetch_ug(mb + 1);          // one slab ahead: the loads fly while this slab is worked
+            stage_slab(mb);
+            if (EPI == EPI_STORE && !ADD && p.c_f32) {
+                // fp32 output: one 16-byte store per lane and pass, consecutive lanes on consecutive 16 bytes, so
+                // every store instruction writes two whole 512-byte row segments
+                const int c4 = (l & 31) * 4;
+                const int64_t col4 = n0 + wn * 128 + c4;
+                float f4[4] = {alpha, alpha, alpha, alpha};
+                if (p.col_scale && col4 < p.N) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) f4[k] = __fmul_rn(alpha, p.col_scale[col4 + k]);
+                }
+#pragma unroll
+                for (int pass = 0; pass < 16; ++pass) {
+                    const int r = pass * 2 + (l >> 5);
+                    const int64_t row = m0 + wm * 128 + mb * 32 + r;
+                    const float4 a = *reinterpret_cast<const float4 *>(stg + r * kPitch + c4);
+                    if (col4 >= p.N || row >= p.M) continue;
+                    float *out = reinterpret_cast<float *>(p.C) + (size_t)row * (size_t)p.N + (size_t)col4;
+                    float4 o = make_float4(__fmul_rn(a.x, f4[0]), __fmul_rn(a.y, f4[1]), __fmul_rn(a.z, f4[2]), __fmul_rn(a.w, f4[3]));
+                    if (post) o = make_float4(o.x * dq.post, o.y * dq.post, o.z * dq.post, o.w * dq.post);
+                    *reinterpret_cast<float4 *>(out) = o;
+                }
+                continue;
+            }
+#pragma unroll
+            for (int pass = 0; pass < 8; ++pass) {
+                const int r = pass * 4 + (l >> 4);
+                const int64_t row = m0 + wm * 128 + mb * 32 + r;
+                float v[8];
+                load8(r, c8, v);
+                if (!col_ok || row >= p.M) continue;
+                const size_t at = (size_t)row * (size_t)p.N + (size_t)col;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = __fmul_rn(v[k], f[k]);
+                if (post) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] *= dq.post;
+                }
+                if (ADD) {
+                    const uint4 a0 = ru[mb & 1][pass], a1 = rg[mb & 1][pass];
+                    const uint32_t aw[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] = __fadd_rn(v[k], __uint_as_float(aw[k]));
+                }
+                if (EPI == EPI_STORE) {
+                    if (p.c_f32) {
+                        float *out = reinterpret_cast<float *>(p.C) + at;
+                        *reinterpret_cast<float4 *>(out) = make_float4(v[0], v[1], v[2], v[3]);
+                        *reinterpret_cast<float4 *>(out + 4) = make_float4(v[4], v[5], v[6], v[7]);
+                    } else {
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = pack_bf16x8(v);
+                    }
+                } else {
+                    float u[8], g[8], du[8], dg[8];
+                    unpack_bf16x8(ru[mb & 1][pass], u);
+                    unpack_bf16x8(rg[mb & 1][pass], g);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        swiglu_grad_f32(u[k], g[k], v[k], du[k], dg[k]);
+                        du_maxf = fmaxf(du_maxf, fabsf(du[k]));
+                        dg_maxf = fmaxf(dg_maxf, fabsf(dg[k]));
+                    }
+                    const uint4 qu = pack_bf16x8(du), qg = pack_bf16x8(dg);
+                    if (EPI == EPI_SWIGLU_BWD_Q) {
+                        // delayed scaling: the scales are known beforehand, so the bf16 values (formed only to
+                        // round as the stored-tensor path does) go straight to E5M2 codes
+                        unpack_bf16x8(qu, du);
+                        unpack_bf16x8(qg, dg);
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            du[k] = __fmul_rn(du[k], q_su);
+                            dg[k] = __fmul_rn(dg[k], q_sg);
+                        }
+                        *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(p.C) + at) = satcast_pk8<kE5M2>(du);
+                        *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(p.C2) + at) = satcast_pk8<kE5M2>(dg);
+                        if (p.keep_u) {
+                            *reinterpret_cast<uint4 *>(p.keep_u + at) = qu;
+                            *reinterpret_cast<uint4 *>(p.keep_g + at) = qg;
+                        }
+                    } else {
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = qu;
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C2) + at) = qg;
+                    }
+                }
+            }
+        }
+        // bf16 bits of the rounded maxima (an infinite maximum, 0x7f80, is kept; NaN never enters)
+        uint32_t du_max = pack_bf16x2(du_maxf, 0.0f) & 0x7fffu, dg_max = pack_bf16x2(dg_maxf, 0.0f) & 0x7fffu;
+        if (kBwd) {
+            du_max = wave_max_u32(du_max);
+            dg_max = wave_max_u32(dg_max);
+            uint32_t *red = reinterpret_cast<uint32_t *>(smem + 4 * 32 * kPitch * 4);   // past the staging patches
+            if (l == 0) { red[2 * w] = du_max; red[2 * w + 1] = dg_max; }
+            __syncthreads();
+            if (tid < 2) {
+                uint32_t m = 0;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) m = m > red[2 * k + tid] ? m : red[2 * k + tid];
+                uint32_t *dst = tid == 0 ? p.amax_bits : p.amax_bits2;
+                if (m) atomicMax(dst + (vblock % kAmaxSlots) * kAmaxSlotStride, m << 16);
+            }
+        }
+    } else {   // EPI_SWIGLU, EPI_SWIGLU_Q: slab columns 0..63 are u, 64..127 are g of the same 64 channels
+        const int c8 = (l & 7) * 8;
+        const int64_t col = n0 + wn * 64 + c8;
+        const bool col_ok = col < p.N;
+        const Dequant dq_u = inv_scale_product(p.sa, p.sb), dq_g = inv_scale_product(p.sa, p.sb2);
+        const float alpha_u = dq_u.a, alpha_g = dq_g.a;
+        const bool post = dq_u.post != 1.0f || dq_g.post != 1.0f;
+        float hmaxf[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};   // fmaxf drops NaN
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            stage_slab(mb);
+#pragma unroll
+            for (int pass = 0; pass < 4; ++pass) {
+                const int r = pass * 8 + (l >> 3);
+                const int64_t row = m0 + wm * 128 + mb * 32 + r;
+                float u[8], g[8];
+                load8(r, c8, u);
+                load8(r, 64 + c8, g);
+                if (!col_ok || row >= p.M) continue;
+                const size_t at = (size_t)row * (size_t)p.N + (size_t)col;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    u[k] = __fmul_rn(u[k], alpha_u);
+                    g[k] = __fmul_rn(g[k], alpha_g);
+                }
+                if (post) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) { u[k] *= dq_u.post; g[k] *= dq_g.post; }
+                }
+                if (EPI == EPI_SWIGLU_Q) {
+                    // inference: the factor s_i is already inside u (folded into w1), so the product is cast as
+                    // it stands; nothing else is stored
+                    float h[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) h[k] = swiglu_f32(u[k], g[k]);
+                    *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(p.C) + at) = satcast_pk8<kE4M3>(h);
+                    continue;
+                }
+                const uint4 qu = pack_bf16x8(u), qg = pack_bf16x8(g);
+                *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C) + at) = qu;
+                *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.C2) + at) = qg;
+                unpack_bf16x8(qu, u);
+                unpack_bf16x8(qg, g);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) hmaxf[k] = fmaxf(hmaxf[k], fabsf(swiglu_f32(u[k], g[k])));
+            }
+        }
+        uint32_t hmax[8];                                // non-negative floats order like their bit patterns
+#pragma unroll
+        for (int k = 0; k < 8; ++k) hmax[k] = __float_as_uint(hmaxf[k]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+#pragma unroll
+            for (int off = 8; off < 64; off <<= 1) {
+                const uint32_t o = (uint32_t)__shfl_xor((int)hmax[k], off, 64);
+                hmax[k] = hmax[k] > o ? hmax[k] : o;
+            }
+        if (EPI == EPI_SWIGLU && l < 8 && col_ok) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (hmax[k]) atomicMax(&p.camax_bits[col + k], hmax[k]);
+        }
+    }
+}
+
+// One GEMM per launch: workgroup b computes the tile that map_tile assigns to it.
+template <int EPI, int AFMT, int PART = 0, int LAY = 0>
+__global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[kUnits * kUnitBytes];
+    gemm_tile<EPI, AFMT, PART, LAY>(p, (int)blockIdx.x, smem);
+}
+
+// Host side: the kernel's parameter block from the launch interface's argument set.
+inline GemmParams make_gemm_params(const GemmArgs &a) {
+    GemmParams p;
+    p.A = a.A; p.B = a.B; p.B2 = a.B2;
+    p.M = a.M; p.N = a.N; p.K = a.K;
+    p.sa = a.sa; p.sb = a.sb; p.sb2 = a.sb2; p.col_scale = a.col_scale;
+    p.C = a.C; p.C2 = a.C2;
+    p.U = (const uint16_t *)a.U; p.G = (const uint16_t *)a.G;
+    p.camax_bits = a.camax_bits; p.amax_bits = a.amax_bits; p.amax_bits2 = a.amax_bits2;
+    p.c_f32 = a.c_f32;
+    p.tmp = nullptr;
+    p.add = a.add;
+    p.q_scale = a.q_scale; p.q_scale2 = a.q_scale2; p.q_scale_out = a.q_scale_out; p.q_scale_out2 = a.q_scale_out2;
+    p.keep_u = (uint16_t *)a.keep_u; p.keep_g = (uint16_t *)a.keep_g;
+    p.A_ph2 = a.A_ph2; p.B_ph2 = a.B_ph2; p.sa_ph2 = a.sa_ph2; p.sb_ph2 = a.sb_ph2;
+    p.tiles_m = (int)((a.M + BM - 1) / BM);
+    const int n_per_tile = (a.epilogue == EPI_SWIGLU || a.epilogue == EPI_SWIGLU_Q) ? BN / 2 : BN;
+    p.tiles_n = (int)((a.N + n_per_tile - 1) / n_per_tile);
+    return p;
+}
+
+}  // namespace ssg

@@ -89,8 +89,13 @@ struct GemmArgs {
     // EPI_STORE as one half of a sum of two products run as two launches:
     //   part = 1: C is the fp32 scratch [M, N] that receives this product, scaled (c_f32 = 1)
     //   part = 2: `add` (that scratch) is added to this product, scaled, before rounding into C
+    //   part = 3: the whole sum in one launch: C = A B^T / (sa sb) + A_ph2 B_ph2^T / (sa_ph2 sb_ph2), the second pair of
+    //             operands of the same shapes, formats and layout; all four scale pointers are required
+    // (parts are built for the input gradient: A E5M2, layout 1)
     int part = 0;
     const float *add = nullptr;
+    const uint8_t *A_ph2 = nullptr, *B_ph2 = nullptr;
+    const float *sa_ph2 = nullptr, *sb_ph2 = nullptr;
     // dequantization: alpha = 1 / (sa * sb); null pointer = 1
     const float *sa = nullptr, *sb = nullptr, *sb2 = nullptr;   // sb2: scale of B2
     const float *col_scale = nullptr;   // optional [N] factor (EPI_STORE, EPI_SWIGLU_BWD)
@@ -110,10 +115,23 @@ struct GemmArgs {
 bool gemm_args_ok(const GemmArgs &a);
 // false (nothing launched): gemm_args_ok(a) is false
 bool launch_gemm(const GemmArgs &a, hipStream_t st);
+bool launch_gemm_bwd(const GemmArgs &a, hipStream_t st);       // the backward forms (called by launch_gemm)
+bool gemm_sum_in_one_launch_ok(int64_t N, int64_t K);           // shapes for which part = 3 is built
+int gemm_profile_tag(const GemmArgs &a);
+// Several independent GEMMs in one grid, their tiles alternating in dispatch order.  Built groups:
+//   { dH (EPI_SWIGLU_BWD or _Q), weight gradient (EPI_STORE, layout 2, A E5M2) }
+//   { input gradient as one launch (part = 3), weight gradient, weight gradient }
+// gemm_group_ok tells whether `list` is one of them with every member valid; launch_gemm_group returns false
+// (nothing launched) otherwise.  Timing tags: 16 and 17.
+bool gemm_group_ok(const GemmArgs *const *list, int n);
+bool launch_gemm_group(const GemmArgs *const *list, int n, hipStream_t st);
 
-// Benchmark hook: called by launch_gemm before and after the kernel launch (no-ops unless enabled).
-void profile_before(int tag, hipStream_t st);
+// Benchmark hook: called by the launchers before and after a kernel launch (no-ops unless enabled).  `bytes`: the
+// algorithmic bytes the launch moves (elementwise passes), 0 where the caller prices the launch itself (GEMMs).
+void profile_before(int tag, hipStream_t st, double bytes = 0.0);
 void profile_after(hipStream_t st);
+// tags of the elementwise passes (the GEMM tags are listed with ssg_profile_read)
+constexpr int kTagAmax = 40, kTagCast = 41, kTagCastSwiglu = 42, kTagCastColscale = 43, kTagColAmax = 44, kTagSmall = 45;
 
 // ---- delayed scaling: amax history per tensor (ssg_quant.hip) ----------------------
 // State words: tensor k (0..5 = x, w1, w2, dy, du, dg) owns words [32k, 32k+32): [0] the scale the next
