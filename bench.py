@@ -27,32 +27,51 @@ if ROOT not in sys.path:
 
 PEAK_FP8_TFLOPS = 5000.0          # MI355X dense FP8 MFMA peak (published: 5.0 PFLOP/s)
 METRIC = "FP8 Smooth-SwiGLU MLP fwd+bwd TFLOP/s (7B shape), % of FP8 MFMA peak"
-# tag of ssg_profile_read -> kernel symbol as rocprofv3 prints it (template args: epilogue, A format, part of a two-launch sum, operand layout: 0 = both K-contiguous,
-# 1 = B K-major, 2 = A and B K-major);
-# the input gradient is two launches (the second adds the first's fp32 result)
-TAG_NAMES = {0: "gemm_kernel<0, 0, 0, 0>", 1: "gemm_kernel<0, 1, 0, 2>", 2: "gemm_kernel<1, 0, 0, 0>",
-             5: "gemm_kernel<2, 1, 0, 1>", 9: "gemm_kernel<0, 1, 1, 1>", 10: "gemm_kernel<0, 1, 2, 1>"}
-TAG_ROLES = {0: "y = h^ w3~^T", 1: "dW3, dW1, dW2", 2: "U, G + SwiGLU + channel maxima", 5: "dH + SwiGLU backward",
-             9: "dX, first product (to fp32 scratch)", 10: "dX, second product + scratch"}
+# tag of ssg_profile_read -> kernel symbol as rocprofv3 prints it.  gemm_kernel<epilogue, A format, part, layout>:
+# epilogue 0 = store, 1 = SwiGLU forward, 2 = SwiGLU backward; part 3 = a sum of two products in one launch;
+# layout 0 = both operands K-contiguous, 1 = B K-major, 2 = A and B K-major.  The backward GEMMs run as two grouped
+# launches; the single-launch tags appear only when the grouping is switched off (SSG_GEMM_GROUPING=0).
+TAG_NAMES = {0: "gemm_kernel<0, 0, 0, 0>", 2: "gemm_kernel<1, 0, 0, 0>", 16: "gemm_group_dh_dw3_kernel<2>",
+             17: "gemm_group_dx_dw_kernel", 5: "gemm_kernel<2, 1, 0, 1>", 1: "gemm_kernel<0, 1, 0, 2>",
+             11: "gemm_kernel<0, 1, 3, 1>", 9: "gemm_kernel<0, 1, 1, 1>", 10: "gemm_kernel<0, 1, 2, 1>"}
+TAG_ROLES = {0: "y = h^ w3~^T", 2: "U, G + SwiGLU + channel maxima", 16: "dH + SwiGLU backward, then dW3 (one grid)",
+             17: "dX (both products), then dW1, dW2 (one grid)", 5: "dH + SwiGLU backward", 1: "dW3, dW1, dW2",
+             11: "dX, both products in one launch", 9: "dX, first product (to fp32 scratch)",
+             10: "dX, second product + scratch"}
+# elementwise passes: tag -> (kernel family as rocprofv3 prints it, role)
+ELEMENTWISE = {40: ("amax_bf16_kernel", "per-tensor range of x, W1, W2, dY"),
+               41: ("cast_kernel<LoadBf16, *, false, ...>", "per-tensor cast of x, W1, W2, dY, dU, dG"),
+               42: ("cast_kernel<LoadSwiglu, 0, true, ...>", "h^ = cast(s_i h) from bf16 U, G"),
+               43: ("cast_kernel<LoadBf16, 0, true, ...>", "w3~ = Q(s^-1 w3)"),
+               44: ("col_amax_bf16_kernel", "per-channel range of W3"),
+               45: ("reset / fill / channel_factors kernels", "bookkeeping")}
+PEAK_HBM_GBS = 8000.0             # MI355X HBM3E (published: 8 TB/s)
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "bench_7b_hbm_traffic.txt")
 
-# L2<->memory bytes per launch of the dominant kernel (gemm_kernel<0, 1, 0, 2>: dW3, dW1, dW2) from two
-# rocprofv3 --pmc runs of this command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
-# reads for a 1 GiB copy (factors 2.000 and 1.000); see profiles/bench_7b_hbm_traffic.txt.  Algorithmic
-# bytes of that launch: 61.9 MB of FP8 operands read + 180.4 MB of fp32 written.
-MEASURED_TRAFFIC_BYTES = {"gemm_kernel<0, 1, 0, 2>": 318.3e6 + 180.4e6}
 
-
-def gemm_flops_by_tag(T, d, f):
-    """Algorithmic flops per step and launches per step of each GEMM kernel instantiation."""
+def gemm_flops_by_tag(T, d, f, grouped=True):
+    """Algorithmic flops per step and launches per step of each GEMM launch tag."""
     one = 2.0 * T * d * f
-    return {
-        0: (one, 1),          # y = h^ w3~^T
-        2: (2 * one, 1),      # U and G in one launch
-        5: (one, 1),          # dH
-        1: (3 * one, 3),      # dW3, dW1, dW2
-        9: (one, 1),          # dX: first product
-        10: (one, 1),         # dX: second product, adds the first
-    }
+    if grouped:
+        return {0: (one, 1),          # y = h^ w3~^T
+                2: (2 * one, 1),      # U and G in one launch
+                16: (2 * one, 1),     # dH and dW3
+                17: (4 * one, 1)}     # dX (two products), dW1, dW2
+    return {0: (one, 1), 2: (2 * one, 1), 5: (one, 1), 1: (3 * one, 3), 11: (2 * one, 1)}
+
+
+def measured_traffic_bytes(kernel: str):
+    """L2 <-> memory bytes per launch of `kernel` (FETCH_SIZE + WRITE_SIZE, calibrated) from the tracked table that
+    `bench.py --summarize-profiles` writes from two rocprofv3 --pmc runs of this benchmark; None when the table
+    has no row for it (e.g. another workload)."""
+    try:
+        for line in open(TRAFFIC_TABLE):
+            cols = line.rstrip("\n").split("\t")
+            if len(cols) >= 5 and cols[0].strip().startswith(kernel):
+                return (float(cols[2]) + float(cols[3])) * 1e6
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def cpu_baseline(T_sample: int, cfg):
@@ -77,16 +96,10 @@ def cpu_baseline(T_sample: int, cfg):
             "seconds": dt}
 
 
-PEAK_HBM_GBS = 8000.0             # MI355X HBM3E (published: 8 TB/s)
 ADAM_KERNELS = {32: "adam_range_kernel<false, 2>", 33: "adam_update_kernel<false, 1>"}
 # algorithmic bytes per element: range pass reads g (4) + two codes; update pass reads g, two codes and w (4),
 # writes w (4), the bf16 copy (2) and two codes
 ADAM_BYTES = {32: 6.0, 33: 18.0}
-# L2<->memory bytes per launch of the update pass at 45.1 M elements, from the same two rocprofv3 --pmc runs as
-# MEASURED_TRAFFIC_BYTES below (profiles/bench_7b_hbm_traffic.txt): 452.3 MB fetched + 375.4 MB written, against
-# 811.6 MB algorithmic
-ADAM_MEASURED_TRAFFIC_BYTES = {45088768: 452.3e6 + 375.4e6}
-
 
 def bench_adam(ssg, torch, grads, weights, steps, warmup, stream, cpu_sample=1 << 22, with_cpu=True):
     """Next row after the block: the Adam step with E4M3 / E5M2 moments (Section 5) on the block's three
@@ -112,6 +125,7 @@ def bench_adam(ssg, torch, grads, weights, steps, warmup, stream, cpu_sample=1 <
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    ssg.ssg_profile_select(-1)
     ssg.ssg_profile_enable(6 * steps)
     t0 = time.perf_counter()
     for _ in range(steps):
@@ -130,7 +144,8 @@ def bench_adam(ssg, torch, grads, weights, steps, warmup, stream, cpu_sample=1 <
            "value": (ADAM_BYTES[32] + ADAM_BYTES[33]) * n_total / (dt / steps) / 1e9,
            "ms_per_step": dt * 1e3 / steps, "elements": n_total, "steps": steps, "dtype": "f32 (moments e4m3 / e5m2)",
            "roofline": {"bound": "hbm", "kernel": ADAM_KERNELS[dom], "achieved": achieved, "peak": PEAK_HBM_GBS,
-                        "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS, "traffic": ADAM_MEASURED_TRAFFIC_BYTES.get(n_one),
+                        "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
+                        "traffic": measured_traffic_bytes(ADAM_KERNELS[dom]) if n_one == 11008 * 4096 else None,
                         "avg_launch_ms": avg[dom], "bytes_per_launch": ADAM_BYTES[dom] * n_one,
                         "kernels": {ADAM_KERNELS[tg]: {"avg_ms": avg[tg], "gbs": ADAM_BYTES[tg] * n_one / (avg[tg] * 1e-3) / 1e9}
                                     for tg in (32, 33)}}}
@@ -184,6 +199,136 @@ def mfma_ceiling(ssg, torch, saved_view_bytes, stream):
     return out
 
 
+# ---------------------------------------------------------------------------------------------------------------
+# Summaries of rocprofv3 runs of this benchmark, as kept under profiles/ (host-only mode: --summarize-profiles DIR).
+# DIR holds the CSV output of four runs (each started from /tmp with TMPDIR=/tmp):
+PROFILE_COMMANDS = {
+    "stats": "rocprofv3 --kernel-trace --stats --output-format csv -d DIR/stats -o stats -- python3 bench.py --steps 20 --warmup 5 --no-cpu-baseline",
+    "fetch": "rocprofv3 --pmc FETCH_SIZE --output-format csv -d DIR/fetch -o fetch -- python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --copy-probe",
+    "write": "rocprofv3 --pmc WRITE_SIZE --output-format csv -d DIR/write -o write -- python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --copy-probe",
+    "mfma": "rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_F8 SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE GRBM_GUI_ACTIVE --output-format csv -d DIR/mfma -o mfma -- python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline",
+}
+
+
+def summarize_profiles(src: str) -> int:
+    import collections
+    import csv
+    import glob
+    import subprocess
+    out_dir = os.path.join(ROOT, "profiles")
+    os.makedirs(out_dir, exist_ok=True)
+    try:
+        commit = subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], capture_output=True, text=True).stdout.strip()
+    except OSError:
+        commit = "?"
+
+    def short(k):
+        return k.replace("void ", "").replace("ssg::", "")[:100]
+
+    def find(sub, suffix):
+        hits = glob.glob(os.path.join(src, sub, "**", "*" + suffix), recursive=True)
+        return hits[0] if hits else None
+
+    shape = "Llama2-7B MLP shape, fwd+bwd, T=4096 d=4096 f=11008"
+    legend = ("gemm_kernel<epilogue, A format, part, layout>: epilogue 0 = store, 1 = SwiGLU forward (U, G, channel maxima), 2 = SwiGLU "
+              "backward, 3 = SwiGLU + E4M3 cast (inference form), 4 = SwiGLU backward + E5M2 cast (delayed scaling); A format 0 = E4M3, "
+              "1 = E5M2; part 3 = a sum of two products in one launch; layout 0 = both operands K-contiguous, 1 = B K-major, 2 = A and B "
+              "K-major.  gemm_group_dh_dw3_kernel = dH then dW3 in one grid; gemm_group_dx_dw_kernel = dX then dW1, dW2 in one grid.")
+    # 1. per-kernel durations
+    stats = find("stats", "kernel_stats.csv")
+    if stats:
+        rows = list(csv.DictReader(open(stats)))
+        with open(os.path.join(out_dir, "bench_7b_kernel_stats.txt"), "w") as fo:
+            fo.write(f"rocprofv3 per-kernel summary of the benchmark ({shape}); library at commit {commit}\n")
+            fo.write("command (from /tmp, TMPDIR=/tmp):\n  " + PROFILE_COMMANDS["stats"] + "\n")
+            fo.write("The run traces everything bench.py does: warm-up, a per-kernel breakdown pass, the timed steps of the headline "
+                     "configuration, then the weights_cached, delayed-scaling, plain-FP8 and inference variants, the Adam steps and the "
+                     "MFMA ceiling probe (mfma_rate_kernel).\n" + legend + "\n\n")
+            fo.write("%-102s %6s %12s %10s %10s %7s\n" % ("kernel", "calls", "avg_us", "min_us", "max_us", "pct"))
+            for r in rows:
+                fo.write("%-102s %6s %12.2f %10.2f %10.2f %7s\n" % (short(r["Name"]), r["Calls"], float(r["AverageNs"]) / 1e3,
+                                                                   float(r["MinNs"]) / 1e3, float(r["MaxNs"]) / 1e3, r["Percentage"]))
+            log = find("stats", "bench.json") or os.path.join(src, "stats.json")
+            if os.path.exists(log):
+                lines = [l for l in open(log) if l.startswith('{"metric"')]
+                if lines:
+                    dd = json.loads(lines[-1])
+                    rf = dd["roofline"]
+                    fo.write("\nbench.py line of the same run: %.0f TFLOP/s, %.3f ms/step; HIP-event average of the dominant kernel %s: "
+                             "%.1f us (%.0f TFLOP/s, %.1f%% of the 5.0 PFLOP/s dense FP8 peak)\n"
+                             % (dd["value"], dd["ms_per_step"], rf["kernel"], rf["avg_launch_ms"] * 1e3, rf["achieved"], 100 * rf["frac"]))
+                    for k, v in rf["kernels"].items():
+                        fo.write("   %-30s %-46s x%d  event avg %.1f us  %.0f TFLOP/s\n"
+                                 % (k, v.get("role", ""), v["launches_per_step"], v["avg_ms"] * 1e3, v["tflops"]))
+                    for k, v in rf.get("elementwise", {}).items():
+                        fo.write("   %-40s %-42s x%d  event avg %.1f us  %.0f GB/s (%.0f%% of 8 TB/s)\n"
+                                 % (k, v["role"], v["launches_per_step"], v["avg_us"], v["GBps"], 100 * v["frac_of_hbm_peak"]))
+    # 2. L2 <-> memory traffic
+    fe_p, wr_p = find("fetch", "counter_collection.csv"), find("write", "counter_collection.csv")
+    if fe_p and wr_p:
+        def agg(path, counter):
+            acc = collections.defaultdict(list)
+            for r in csv.DictReader(open(path)):
+                if r["Counter_Name"] == counter:
+                    acc[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+            return acc
+        fe, wr = agg(fe_p, "FETCH_SIZE"), agg(wr_p, "WRITE_SIZE")
+        copy = "__amd_rocclr_copyBuffer"
+        big = lambda v: [x for x in v if x > 0.5 * max(v)]
+        cf, cw = sum(big(fe[copy])) / len(big(fe[copy])), sum(big(wr[copy])) / len(big(wr[copy]))
+        ff, fw = 1048576.0 / cf, 1048576.0 / cw
+        with open(TRAFFIC_TABLE, "w") as fo:
+            fo.write(f"L2 <-> memory traffic per dispatch at the {shape} (FETCH_SIZE / WRITE_SIZE, KiB per dispatch); library at commit {commit}\n")
+            fo.write("commands (from /tmp, TMPDIR=/tmp), one counter per run:\n  " + PROFILE_COMMANDS["fetch"] + "\n  " + PROFILE_COMMANDS["write"] + "\n")
+            fo.write("calibration: --copy-probe runs three 1 GiB device-to-device copies (the large __amd_rocclr_copyBuffer dispatches): "
+                     "FETCH_SIZE reads %.1f KiB, WRITE_SIZE %.1f KiB for 1048576 KiB moved each way\n  => factor FETCH %.3f, WRITE %.3f "
+                     "(applied below).  FETCH_SIZE counts L2 fills (from the memory-side cache or HBM), so re-reads of operand tiles that "
+                     "miss L2 show up here.\n" % (cf, cw, ff, fw))
+            fo.write("bench.py reads this table (tab-separated: kernel, dispatches, fetch_MB, write_MB, total_MB) for `roofline.traffic`.\n\n")
+            fo.write("kernel\tn\tfetch_MB\twrite_MB\ttotal_MB\n")
+            keys = sorted(set(fe) | set(wr), key=lambda k: -(sum(fe.get(k, [0])) + sum(wr.get(k, [0]))))
+            for k in keys:
+                if "at::native" in k or "rocclr" in k:
+                    continue
+                a = sum(fe.get(k, [0])) / max(1, len(fe.get(k, [0]))) * ff * 1024 / 1e6
+                b = sum(wr.get(k, [0])) / max(1, len(wr.get(k, [0]))) * fw * 1024 / 1e6
+                fo.write("%s\t%d\t%.1f\t%.1f\t%.1f\n" % (short(k), len(fe.get(k, [])), a, b, a + b))
+            fo.write("\nalgorithmic bytes for comparison (MB): gemm_group_dx_dw_kernel reads dU^, dG^ (2 x 45.1), w1^, w2^ (2 x 45.1), x^ (16.8) "
+                     "and writes dX bf16 (33.6) + dW1, dW2 fp32 (2 x 180.4) = 591.6; gemm_group_dh_dw3_kernel reads dY^ (16.8), w3~ (45.1), "
+                     "h^ (45.1), bf16 U, G (180.4) and writes bf16 dU, dG (180.4) + dW3 fp32 (180.4) = 648.2; gemm_kernel<1, 0, 0, 0> reads "
+                     "x^, w1^, w2^ (107.0) and writes bf16 U, G (180.4) = 287.4; adam_update_kernel at 45.09 M elements: 18 B/element = 811.6.\n")
+    # 3. MFMA / LDS counters of the GEMMs
+    mf_p = find("mfma", "counter_collection.csv")
+    if mf_p:
+        mf = collections.defaultdict(lambda: collections.defaultdict(list))
+        dur = collections.defaultdict(list)
+        seen = set()
+        for r in csv.DictReader(open(mf_p)):
+            mf[r["Kernel_Name"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
+            key = (r["Kernel_Name"], r.get("Dispatch_Id"))
+            if key not in seen:
+                seen.add(key)
+                dur[r["Kernel_Name"]].append(float(r["End_Timestamp"]) - float(r["Start_Timestamp"]))
+        with open(os.path.join(out_dir, "gemm_7b_mfma_counters.txt"), "w") as fo:
+            fo.write(f"MFMA and LDS counters of the GEMM kernels at the {shape}; library at commit {commit}\ncommand (from /tmp, TMPDIR=/tmp):\n  "
+                     + PROFILE_COMMANDS["mfma"] + "\n")
+            fo.write("GRBM_GUI_ACTIVE is summed over the 8 XCDs (a register-only MFMA loop at the full rate reads 8 x 2.39 GHz x duration), so "
+                     "shader clock = GRBM/8/duration; MFMA utilisation = SQ_VALU_MFMA_BUSY_CYCLES / (1024 SIMDs x GRBM/8).  Dispatches are "
+                     "serialised under --pmc, so durations here are a little shorter than in the timed run.\n" + legend + "\n\n")
+            fo.write("%-44s %5s %10s %10s %10s %16s %16s\n" % ("kernel", "n", "dur_us", "clock_GHz", "mfma_util", "lds_conflict_cyc", "lds_active_cyc"))
+            for k, c in mf.items():
+                if "gemm" not in k:
+                    continue
+                n = len(c["GRBM_GUI_ACTIVE"])
+                g = sum(c["GRBM_GUI_ACTIVE"]) / n
+                t = sum(dur[k]) / len(dur[k])
+                fo.write("%-44s %5d %10.1f %10.2f %9.1f%% %16.0f %16.0f\n"
+                         % (short(k)[:44], n, t / 1e3, g / 8 / t, 100 * sum(c["SQ_VALU_MFMA_BUSY_CYCLES"]) / n / 1024 / (g / 8),
+                            sum(c["SQ_LDS_BANK_CONFLICT"]) / n, sum(c["SQ_LDS_IDX_ACTIVE"]) / n))
+    print("profiles written under", out_dir)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -196,7 +341,12 @@ def main() -> int:
     ap.add_argument("--copy-probe", action="store_true",
                     help="first run three 1 GiB device-to-device copies (a kernel of known traffic, used to "
                          "calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--summarize-profiles", metavar="DIR", default=None,
+                    help="host-only: write the summaries under profiles/ from the rocprofv3 CSV output in DIR "
+                         "(see PROFILE_COMMANDS) and exit")
     args = ap.parse_args()
+    if args.summarize_profiles:
+        return summarize_profiles(args.summarize_profiles)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
@@ -240,28 +390,37 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
 
-    # the timed region: exactly K steps; the launches of the dominant kernel (the three dW GEMMs, tag 1) are
-    # bracketed by HIP events on the launch stream -- only those, because every bracket costs a few microseconds
-    # of serialisation and the other kernels are timed in a separate, untimed pass below
-    DOMINANT_TAG = 1
+    # per-kernel breakdown of every launch of the step (GEMMs and elementwise passes), HIP events on the launch
+    # stream: a separate pass before the timed region, not part of `value` (every bracket serialises the stream
+    # for a few microseconds, so small kernels read a little long here)
+    bsteps = max(5, args.steps // 5)
+    ssg.ssg_profile_select(-1)
+    ssg.ssg_profile_enable(64 * bsteps)
+    for _ in range(bsteps):
+        step()
+    torch.cuda.synchronize()
+    ms_list, tags, nbytes = ssg.ssg_profile_read(64 * bsteps, with_bytes=True)
+    per_tag = {}
+    for ms, tg, nb in zip(ms_list, tags, nbytes):
+        per_tag.setdefault(tg, []).append((ms, nb))
+    gemm_tags = [tg for tg in per_tag if tg < 32]
+    grouped = 17 in per_tag
+    # dominant kernel = the GEMM launch with the largest share of the step
+    DOMINANT_TAG = max(gemm_tags, key=lambda tg: sum(m for m, _ in per_tag[tg]))
+
+    # the timed region: exactly K steps; only the launches of the dominant kernel are bracketed by HIP events
+    fl = gemm_flops_by_tag(T, d, f, grouped)
+    dom_launches = fl[DOMINANT_TAG][1]
     ssg.ssg_profile_select(DOMINANT_TAG)
-    ssg.ssg_profile_enable(3 * args.steps)
+    ssg.ssg_profile_enable(dom_launches * args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    dom_ms, _ = ssg.ssg_profile_read(3 * args.steps)
-    # per-kernel breakdown of all eight GEMM launches: a separate pass, not part of `value`
-    launches_per_step = 8
-    bsteps = max(5, args.steps // 5)
+    dom_ms, _ = ssg.ssg_profile_read(dom_launches * args.steps)
     ssg.ssg_profile_select(-1)
-    ssg.ssg_profile_enable(launches_per_step * bsteps)
-    for _ in range(bsteps):
-        step()
-    torch.cuda.synchronize()
-    ms_list, tags = ssg.ssg_profile_read(launches_per_step * bsteps)
     ssg.ssg_profile_enable(0)
 
     # second figure: the same step with W1/W2 quantized once (weights_cached = 1), as when several
@@ -357,29 +516,37 @@ def main() -> int:
     flops_step = 18.0 * T * d * f
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
-    # per-kernel averages; dominant = largest share of the step
-    per_tag = {}
-    for ms, tg in zip(ms_list, tags):
-        per_tag.setdefault(tg, []).append(ms)
-    fl = gemm_flops_by_tag(T, d, f)
+    # per-kernel averages of the breakdown pass
     kernels = {}
-    for tg, v in per_tag.items():
+    for tg in gemm_tags:
+        v = [m for m, _ in per_tag[tg]]
         flops_per_launch = fl[tg][0] / fl[tg][1]
         avg = sum(v) / len(v)
         kernels[TAG_NAMES.get(tg, str(tg))] = {
             "role": TAG_ROLES.get(tg, ""), "launches_per_step": fl[tg][1], "avg_ms": avg,
             "tflops": flops_per_launch / (avg * 1e-3) / 1e12}
-    dom_tag = max(per_tag, key=lambda tg: sum(per_tag[tg]))
-    assert dom_tag == DOMINANT_TAG, "the dW GEMMs are expected to be the largest share of the step"
+    elementwise = {}
+    for tg, (kname, role) in ELEMENTWISE.items():
+        if tg not in per_tag:
+            continue
+        v = per_tag[tg]
+        t_ms, b = sum(m for m, _ in v), sum(nb for _, nb in v)
+        gbs = b / (t_ms * 1e-3) / 1e9 if t_ms > 0 else 0.0
+        elementwise[kname] = {"role": role, "launches_per_step": len(v) // bsteps, "avg_us": t_ms * 1e3 / len(v),
+                              "us_per_step": t_ms * 1e3 / bsteps, "algorithmic_MB_per_step": b / bsteps / 1e6,
+                              "GBps": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+    dom_tag = DOMINANT_TAG
     dom_avg = sum(dom_ms) / len(dom_ms)                 # from the timed region itself
     dom_flops = fl[dom_tag][0] / fl[dom_tag][1]
     achieved = dom_flops / (dom_avg * 1e-3) / 1e12
-    gemm_ms = sum(ms_list) / bsteps
+    gemm_ms = sum(m for tg in gemm_tags for m, _ in per_tag[tg]) / bsteps
+    ew_ms = sum(m for tg in per_tag if tg >= 40 for m, _ in per_tag[tg]) / bsteps
     roofline = {"bound": "mfma", "kernel": TAG_NAMES.get(dom_tag, str(dom_tag)), "achieved": achieved,
                 "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP8_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get(TAG_NAMES.get(dom_tag, "")), "avg_launch_ms": dom_avg,
-                "flops_per_launch": dom_flops, "all_gemm_ms_per_step": gemm_ms,
-                "non_gemm_ms_per_step": ms_per_step - gemm_ms, "kernels": kernels}
+                "traffic": measured_traffic_bytes(TAG_NAMES.get(dom_tag, "?")) if cfg.name == "7b" else None,
+                "avg_launch_ms": dom_avg, "flops_per_launch": dom_flops, "all_gemm_ms_per_step": gemm_ms,
+                "non_gemm_ms_per_step": ms_per_step - gemm_ms, "elementwise_ms_per_step_bracketed": ew_ms,
+                "kernels": kernels, "elementwise": elementwise}
 
     out = {
         "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,

@@ -118,7 +118,7 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st);
 bool launch_gemm_bwd(const GemmArgs &a, hipStream_t st);       // the backward forms (called by launch_gemm)
 bool gemm_sum_in_one_launch_ok(int64_t N, int64_t K);           // shapes for which part = 3 is built
 int gemm_profile_tag(const GemmArgs &a);
-// Several independent GEMMs in one grid, their tiles alternating in dispatch order.  Built groups:
+// Several independent GEMMs in one grid, the workgroups of one following those of the other.  Built groups:
 //   { dH (EPI_SWIGLU_BWD or _Q), weight gradient (EPI_STORE, layout 2, A E5M2) }
 //   { input gradient as one launch (part = 3), weight gradient, weight gradient }
 // gemm_group_ok tells whether `list` is one of them with every member valid; launch_gemm_group returns false
