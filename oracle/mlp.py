@@ -15,6 +15,10 @@ Quantized forms:
     s_i before the cast and the inverse is folded into w3 before *its*
     quantization, w3~_i = Q(s_i^-1 * w3_i) (the display after Eq. 2).
 
+Comparison variant (Section 4.3, Table 3 "FP8 + SwiGLU output in BF16"): the quantization of the last linear
+layer is disabled -- the SwiGLU output stays in bf16 and that layer, with its two gradient contractions, runs on
+bf16 operands; everything else is FP8 as above (``w3_layer_fp8=False``).
+
 Readings where the paper is silent (all "parity unpinned" by the paper):
   * s_i = fl32(448 / a_i) with a_i = max_t |h_ti| (largest absolute value over
     all tokens of the call), s_i^-1 = fl32(a_i / 448), both 1 when a_i = 0;
@@ -26,6 +30,9 @@ Readings where the paper is silent (all "parity unpinned" by the paper):
     activations and weights stay E4M3 (Section 6.2).  dU and dG are rounded to
     bf16 and then quantized per tensor with separate scales.
   * Outputs y, dx are bf16; weight gradients are binary32.
+  * With the last layer left in bf16: h is rounded once to bf16 (from the binary32 product), W3 and dY are used as
+    the bf16 tensors they are, no scales are involved; the rest of the backward pass (E5M2 dU, dG; dX, dW1, dW2 in
+    FP8) is unchanged.
 
 Between the named rounding points everything is float64.
 """
@@ -81,6 +88,8 @@ def channel_scales(h: np.ndarray):
 class Forward:
     quantized: bool
     smooth: bool
+    w3_layer_fp8: bool = True                # False: the last linear layer runs on bf16 operands (Section 4.3)
+    h_b: Optional[np.ndarray] = None         # bf16-valued SwiGLU output of that variant
     # quantized operands and their scales (None when quantized=False)
     x_q: Optional[np.ndarray] = None
     sx: Optional[np.float32] = None
@@ -116,15 +125,16 @@ def fold_w3(W3: np.ndarray, sinv: np.ndarray):
 
 
 def forward(x, W1, W2, W3, *, quantized: bool = True, smooth: bool = True,
-            y_dtype: str = "bf16", h_scale=None, scales=None) -> Forward:
+            y_dtype: str = "bf16", h_scale=None, scales=None, w3_layer_fp8: bool = True) -> Forward:
     """One forward pass of the block.  x, W1, W2, W3 are float arrays holding
     the (bf16-representable) inputs.  ``h_scale`` (plain mode only) is a
     caller-given per-tensor scale for h, as under delayed scaling.  ``scales``
     may give the per-tensor scales of "x", "w1", "w2" (delayed scaling,
     Section 2: the scale comes from earlier iterations; values beyond the range
-    it allows saturate); the ranges seen in this call are returned in ``amax``."""
+    it allows saturate); the ranges seen in this call are returned in ``amax``.  ``w3_layer_fp8=False`` leaves
+    the last linear layer unquantized (bf16 SwiGLU output times bf16 W3), the comparison variant of Section 4.3."""
     x = np.asarray(x); W1 = np.asarray(W1); W2 = np.asarray(W2); W3 = np.asarray(W3)
-    out = Forward(quantized=quantized, smooth=smooth)
+    out = Forward(quantized=quantized, smooth=smooth, w3_layer_fp8=w3_layer_fp8)
 
     if not quantized:
         # Q := identity, no rounding points: the real-valued function.
@@ -157,6 +167,13 @@ def forward(x, W1, W2, W3, *, quantized: bool = True, smooth: bool = True,
     # 3. SwiGLU product, one rounding to binary32
     out.h = round_f32(swiglu.swiglu(out.U, out.G))
 
+    if not w3_layer_fp8:
+        # Section 4.3: the SwiGLU output is not quantized; the last linear layer sees bf16 operands
+        out.h_b = round_bf16(out.h)
+        out.W3 = np.asarray(W3, np.float64)
+        out.Y = _round_out(out.h_b @ out.W3.T, y_dtype)
+        return out
+
     if smooth:
         # 4. per-channel factor and cast
         out.a, out.s, out.sinv = channel_scales(out.h)
@@ -178,6 +195,7 @@ def forward(x, W1, W2, W3, *, quantized: bool = True, smooth: bool = True,
 class Backward:
     dy_q: Optional[np.ndarray] = None
     sdy: Optional[np.float32] = None
+    dY: Optional[np.ndarray] = None          # the bf16 upstream gradient as used when the last layer is left in bf16
     dH: np.ndarray = field(default=None)
     dU: np.ndarray = field(default=None)     # bf16 values in quantized mode
     dG: np.ndarray = field(default=None)
@@ -199,6 +217,13 @@ def backward_grad_h(fw: Forward, dY, *, scales=None) -> Backward:
     bw = Backward()
     given = scales or {}
     bw.amax = {}
+    if not fw.w3_layer_fp8:
+        # last layer in bf16 (Section 4.3): its input gradient from the bf16 dY and W3, no quantization
+        bw.dY = np.asarray(dY, np.float64)
+        bw.dH = bw.dY @ fw.W3
+        dU, dG = swiglu.swiglu_grads(fw.U, fw.G, bw.dH)
+        bw.dU, bw.dG = round_bf16(dU), round_bf16(dG)
+        return bw
     # 7. upstream gradient to E5M2
     bw.dy_q, bw.sdy, bw.amax["dy"] = quant.quantize_per_tensor(dY, fp8.E5M2, scale=given.get("dy"))
     sdy, sw3 = np.float64(bw.sdy), np.float64(fw.sw3)
@@ -220,7 +245,6 @@ def backward_operand_grads(fw: Forward, bw: Backward, *, dx_dtype: str = "bf16",
     """Steps 10-12: quantize the bf16 dU, dG held in ``bw`` (two tensors, two E5M2 scales; ``scales`` may
     give "du", "dg"), then the input gradient and the three weight gradients.  Fills and returns ``bw``."""
     given = scales or {}
-    sdy = np.float64(bw.sdy)
     # 10. two tensors, two E5M2 scales
     bw.du_q, bw.sdu, bw.amax["du"] = quant.quantize_per_tensor(bw.dU, fp8.E5M2, scale=given.get("du"))
     bw.dg_q, bw.sdg, bw.amax["dg"] = quant.quantize_per_tensor(bw.dG, fp8.E5M2, scale=given.get("dg"))
@@ -236,6 +260,10 @@ def backward_operand_grads(fw: Forward, bw: Backward, *, dx_dtype: str = "bf16",
                         / (sdu * sx), dw_dtype)
     bw.dW2 = _round_out(gemm.matmul_nt(np.ascontiguousarray(bw.dg_q.T), fp8.E5M2, xT, fp8.E4M3)
                         / (sdg * sx), dw_dtype)
+    if not fw.w3_layer_fp8:
+        bw.dW3 = _round_out(bw.dY.T @ fw.h_b, dw_dtype)                    # bf16 operands (Section 4.3)
+        return bw
+    sdy = np.float64(bw.sdy)
     acc3 = gemm.matmul_nt(np.ascontiguousarray(bw.dy_q.T), fp8.E5M2,
                           np.ascontiguousarray(fw.h_q.T), fp8.E4M3)        # [d,f]
     if fw.smooth:

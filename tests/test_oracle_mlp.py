@@ -241,3 +241,61 @@ def test_planted_mistakes_are_caught_by_the_autograd_pin():
     sg = swiglu.sigmoid(g)
     wrong = dh * u * sg * (1.0 - g * (1.0 - sg))
     assert abs(wrong - dg) > 0.1
+
+
+# ------------------------------------------------------------------ last layer left in bf16 (Section 4.3)
+
+def test_bf16_last_layer_against_torch_bf16_matmul_and_autograd():
+    """The comparison variant of Table 3 ("SwiGLU output in BF16"): pins that do not restate the oracle.
+    (i) y against PyTorch's CPU bf16 matmul of the same bf16 operands (an independent library: it accumulates in
+    binary32 and rounds once, the oracle in binary64 and rounds once; they may differ by one bf16 step);
+    (ii) dH, dW3 against float64 autograd of the bilinear form sum(dY * (h W3^T)) at the oracle's own bf16 h;
+    (iii) the FP8 part upstream (x^, w1^, w2^, U, G) is the one of the fully quantized block, bit for bit;
+    (iv) leaving h in bf16 brings y closer to the unquantized block than either FP8 form of h."""
+    inp = _inputs(T=64, d=64, f=96, seed=17)
+    v = mlp.forward(inp["x"], inp["W1"], inp["W2"], inp["W3"], w3_layer_fp8=False)
+    q = mlp.forward(inp["x"], inp["W1"], inp["W2"], inp["W3"], smooth=True)
+    # (iii)
+    assert np.array_equal(v.x_q, q.x_q) and np.array_equal(v.w1_q, q.w1_q) and np.array_equal(v.w2_q, q.w2_q)
+    assert np.array_equal(v.U, q.U) and np.array_equal(v.G, q.G) and np.array_equal(v.h, q.h)
+    assert v.h_q is None and v.w3_q is None
+    # the stored SwiGLU output holds bf16 values, one rounding away from the binary32 product
+    assert np.array_equal(mlp.round_bf16(v.h_b), v.h_b)
+    assert np.abs(v.h_b - v.h).max() <= 2.0 ** -8 * np.abs(v.h).max()
+    # (i)
+    hb_t = torch.from_numpy(v.h_b).to(torch.bfloat16)
+    assert np.array_equal(hb_t.to(torch.float64).numpy(), v.h_b)          # exactly representable
+    w3_t = torch.from_numpy(inp["W3"]).to(torch.bfloat16)
+    y_t = (hb_t @ w3_t.T).to(torch.float64).numpy()
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(v.Y), 1e-30))) - 7)
+    assert np.all(np.abs(y_t - v.Y) <= ulp + 1e-6 * np.abs(v.Y).max())
+    assert np.mean(y_t == v.Y) > 0.9
+    # (ii)
+    b = mlp.backward(v, inp["dY"])
+    h_t = torch.tensor(v.h_b, dtype=torch.float64, requires_grad=True)
+    W3_t = torch.tensor(inp["W3"], dtype=torch.float64, requires_grad=True)
+    ((h_t @ W3_t.T) * torch.tensor(inp["dY"], dtype=torch.float64)).sum().backward()
+    assert np.abs(b.dH - h_t.grad.numpy()).max() <= 1e-12 * np.abs(b.dH).max()
+    assert np.abs(b.dW3 - W3_t.grad.numpy()).max() <= 2.0 ** -23 * np.abs(b.dW3).max()      # one binary32 rounding
+    assert b.dy_q is None and (b.du_q & 0x7F).max() == 0x7B
+    # the gradients that stay in FP8 are those of the quantized block fed with this dH
+    ref_f = mlp.forward(inp["x"], inp["W1"], inp["W2"], inp["W3"], quantized=False, smooth=False)
+    ref_b = mlp.backward(ref_f, inp["dY"])
+    for name in ("dX", "dW1", "dW2", "dW3"):
+        rel = np.linalg.norm(getattr(b, name) - getattr(ref_b, name)) / np.linalg.norm(getattr(ref_b, name))
+        assert rel < 0.12, (name, rel)
+    # (iv)
+    err = lambda f: np.linalg.norm(f.Y - ref_f.Y)
+    plain = mlp.forward(inp["x"], inp["W1"], inp["W2"], inp["W3"], smooth=False)
+    assert err(v) < err(q) and err(v) < err(plain)
+
+
+def test_bf16_last_layer_planted_mistakes_fail():
+    """A transposed W3 or a dW3 taken from the unrounded h must trip the pins above."""
+    inp = _inputs(T=32, d=32, f=32, seed=19)
+    v = mlp.forward(inp["x"], inp["W1"], inp["W2"], inp["W3"], w3_layer_fp8=False)
+    b = mlp.backward(v, inp["dY"])
+    wrong_dH = np.asarray(inp["dY"], np.float64) @ np.asarray(inp["W3"], np.float64).T       # square shapes: runs, but wrong
+    assert np.abs(wrong_dH - b.dH).max() > 0.1 * np.abs(b.dH).max()
+    dW3_unrounded = np.asarray(inp["dY"], np.float64).T @ v.h.astype(np.float64)
+    assert np.abs(dW3_unrounded - b.dW3).max() > 2.0 ** -20 * np.abs(b.dW3).max()
