@@ -494,6 +494,25 @@ def main() -> int:
     step()
     torch.cuda.synchronize()
 
+    # the paper's other comparison point, "FP8 + SwiGLU output in BF16" (Section 4.3, Table 3 row 2): the last linear
+    # layer and its two gradient contractions on bf16 operands, everything else FP8
+    desc_b = ssg.make_desc(T, d, f, smooth=0, w3_layer_bf16=1)
+    saved_b = torch.empty(ssg.ssg_mlp_saved_bytes(desc_b), dtype=torch.uint8, device=dev)
+    work_b = torch.empty(ssg.ssg_mlp_workspace_bytes(desc_b), dtype=torch.uint8, device=dev)
+    for _ in range(3):
+        ssg.ssg_mlp_fwd(desc_b, x, W1, W2, W3, y, saved_b, stream)
+        ssg.ssg_mlp_bwd(desc_b, dY, saved_b, dx, dW1, dW2, dW3, work_b, stream)
+    torch.cuda.synchronize()
+    t6 = time.perf_counter()
+    for _ in range(args.steps):
+        ssg.ssg_mlp_fwd(desc_b, x, W1, W2, W3, y, saved_b, stream)
+        ssg.ssg_mlp_bwd(desc_b, dY, saved_b, dx, dW1, dW2, dW3, work_b, stream)
+    torch.cuda.synchronize()
+    dt_bf16 = time.perf_counter() - t6
+    del saved_b, work_b
+    step()
+    torch.cuda.synchronize()
+
     # fourth figure: the inference form (end of Section 4.4): factors of a calibration call folded into w1, w3 once;
     # a forward is Q(x), one GEMM with the SwiGLU product and its E4M3 cast fused, one GEMM.  6*T*d*f flops.
     sview = ssg.ssg_mlp_view_saved(desc, saved)
@@ -565,6 +584,12 @@ def main() -> int:
                       "note": "the same step without Smooth-SwiGLU (smooth = 0, Figure 4a): what the per-channel "
                               "scaling costs on this machine (Table 3 of the paper reports the same comparison "
                               "end to end on Gaudi2)"},
+        "bf16_last_layer": {"value": 18.0 * T * d * f / (dt_bf16 / args.steps) / 1e12, "unit": "TFLOP/s",
+                            "ms_per_step": dt_bf16 * 1e3 / args.steps,
+                            "note": "the same step with the quantization of the last linear layer disabled (w3_layer_bf16 = 1: "
+                                    "bf16 SwiGLU output, y, dH and dW3 on bf16 operands, transposed bf16 copies written), the "
+                                    "row 'FP8 + SwiGLU output in BF16' of the paper's Table 3; Smooth-SwiGLU (the headline) sits "
+                                    "between it and plain_fp8, as in that table"},
         "inference_forward": {"value": 6.0 * T * d * f / (dt_infer / args.steps) / 1e12, "unit": "TFLOP/s",
                               "ms_per_call": dt_infer * 1e3 / args.steps,
                               "note": "forward only with the calibrated factors folded into w1 and w3 "

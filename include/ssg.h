@@ -156,6 +156,12 @@ typedef struct {
     int32_t keep_bf16_grads; /* SSG_SCALE_DELAYED only (no effect otherwise): 1 = ssg_mlp_bwd also stores the bf16 dU, dG
                                 that the fused epilogue rounds and casts from (for inspection; under current scaling
                                 they are always stored).  0 = only their E5M2 codes are written. */
+    int32_t w3_layer_bf16;   /* 1 = the comparison variant of Section 4.3 / Table 3 ("FP8 + SwiGLU output in BF16"): the
+                                quantization of the last linear layer is disabled -- the SwiGLU product is rounded once to
+                                bf16 and y = h W3^T, dH = dY W3 and dW3 = dY^T h run on bf16 operands (no scales, no
+                                per-channel factors); the other six contractions stay FP8.  Needs smooth = 0 and current
+                                scaling.  `saved` and `workspace` are larger (transposed bf16 copies of h, W3 and dY). */
+    int32_t reserved[3];     /* must be 0 */
     void *scaling_state;     /* device, ssg_mlp_scaling_state_bytes() bytes, or NULL.  When given, every call
                                 (current or delayed) enters the ranges it saw into the history. */
     const float *h_scale;    /* device, one float: the given scale of h (h_scale_mode = SSG_SCALE_GIVEN), else NULL */
@@ -204,6 +210,8 @@ typedef struct {
     const uint8_t *x_q, *w1_q, *w2_q, *h_q, *w3_q;       /* [T,d], [f,d], [f,d], [T,f], [d,f]: row-major only; the
                                                             backward reads them K-major, no transposed copies */
     const void *U, *G;                                   /* bf16 [T,f] */
+    const void *h_b, *h_bT, *w3T;                        /* w3_layer_bf16 = 1 only (else NULL): bf16 SwiGLU output [T,f],
+                                                            its transpose [f,T], W3 transposed [f,d] */
 } ssg_mlp_saved_view;
 typedef struct {
     const float *scales;     /* [0]=sdy [1]=sdu [2]=sdg [3]=amax_dy [4]=amax_du [5]=amax_dg ([3..5]: current scaling only) */
@@ -211,6 +219,7 @@ typedef struct {
     const void *dU, *dG;                                 /* bf16 [T,f]; under SSG_SCALE_DELAYED the dH epilogue emits the
                                                             E5M2 codes directly and these are written only when
                                                             desc.keep_bf16_grads = 1 */
+    const void *dyT;                                     /* w3_layer_bf16 = 1 only (else NULL): bf16 dY transposed [d,T] */
 } ssg_mlp_workspace_view;
 ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_mlp_saved_view *out);
 ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspace, ssg_mlp_workspace_view *out);
@@ -309,10 +318,12 @@ ssg_status ssg_adam_view_state(int64_t n, int32_t step, const void *state, ssg_a
  * (y: tag 0; a weight gradient: tag 1), 1 = fused SwiGLU forward (U, G, channel maxima: tag 2), 2 = fused SwiGLU
  * backward (dH: tag 5), 3 = fused SwiGLU product + E4M3 cast of the inference form (tag 6); 11 = the input
  * gradient, both products in one launch (9 and 10: its two launches on shapes where that form is not built);
- * 16 = grouped launch {dH, dW3}; 17 = grouped launch {dX, dW1, dW2}.
+ * 16 = grouped launch {dH, dW3}; 17 = grouped launch {dX, dW1, dW2}; bf16 operands (w3_layer_bf16 = 1): 20 = plain
+ * store (y, dW3), 21 = dH with the fused SwiGLU backward.
  * Elementwise passes (bytes = algorithmic bytes moved): 40 = per-tensor range, 41 = per-tensor cast, 42 = cast
  * of the SwiGLU product from bf16 U, G with per-channel factors, 43 = cast of W3 with the inverse factors folded
- * in, 44 = per-column range, 45 = small bookkeeping kernels (resets, factors, history update).
+ * in, 44 = per-column range, 45 = small bookkeeping kernels (resets, factors, history update), 46 = bf16 transposes
+ * (w3_layer_bf16 = 1).
  * Adam: 32 = range pass, 33 = update pass. */
 ssg_status ssg_profile_enable(int max_records);
 ssg_status ssg_profile_select(int tag);

@@ -44,7 +44,8 @@ EXPORTS = [
 class ssg_mlp_desc(Structure):
     _fields_ = [("T", c_int64), ("d", c_int64), ("f", c_int64), ("smooth", c_int32), ("rnd", c_int32),
                 ("y_dtype", c_int32), ("dw_dtype", c_int32), ("weights_cached", c_int32), ("scale_mode", c_int32),
-                ("h_scale_mode", c_int32), ("keep_bf16_grads", c_int32), ("scaling_state", c_void_p), ("h_scale", c_void_p),
+                ("h_scale_mode", c_int32), ("keep_bf16_grads", c_int32), ("w3_layer_bf16", c_int32), ("reserved", c_int32 * 3),
+                ("scaling_state", c_void_p), ("h_scale", c_void_p),
                 ("h_counters", c_void_p)]
 
 
@@ -64,11 +65,11 @@ class ssg_adam_state_view(Structure):
 
 class ssg_mlp_saved_view(Structure):
     _fields_ = [(n, c_void_p) for n in (
-        "scales", "s", "sinv", "h_camax", "w3_camax", "x_q", "w1_q", "w2_q", "h_q", "w3_q", "U", "G")]
+        "scales", "s", "sinv", "h_camax", "w3_camax", "x_q", "w1_q", "w2_q", "h_q", "w3_q", "U", "G", "h_b", "h_bT", "w3T")]
 
 
 class ssg_mlp_workspace_view(Structure):
-    _fields_ = [(n, c_void_p) for n in ("scales", "dy_q", "du_q", "dg_q", "dU", "dG")]
+    _fields_ = [(n, c_void_p) for n in ("scales", "dy_q", "du_q", "dg_q", "dU", "dG", "dyT")]
 
 
 _lib.ssg_last_error.restype = c_char_p
@@ -166,11 +167,12 @@ def _nbytes(t, given=None) -> int:
 def make_desc(T: int, d: int, f: int, smooth: int = 1, rnd: int = SSG_ROUND_EXACT_DIV,
               y_dtype: int = SSG_BF16, dw_dtype: int = SSG_F32, weights_cached: int = 0,
               scale_mode: int = SSG_SCALE_CURRENT, scaling_state=None, h_scale=None, h_counters=None,
-              keep_bf16_grads: int = 0) -> ssg_mlp_desc:
+              keep_bf16_grads: int = 0, w3_layer_bf16: int = 0) -> ssg_mlp_desc:
     """`scaling_state`: a device byte tensor of ssg_mlp_scaling_state_bytes() bytes; `h_scale`: a device float
     (plain block, given scale of h); `h_counters`: two device int64 words.  All kept alive by the caller."""
     return ssg_mlp_desc(T, d, f, smooth, rnd, y_dtype, dw_dtype, weights_cached, scale_mode,
-                        SSG_SCALE_GIVEN if h_scale is not None else SSG_SCALE_CURRENT, keep_bf16_grads,
+                        SSG_SCALE_GIVEN if h_scale is not None else SSG_SCALE_CURRENT, keep_bf16_grads, w3_layer_bf16,
+                        (c_int32 * 3)(0, 0, 0),
                         _ptr(scaling_state), _ptr(h_scale), _ptr(h_counters))
 
 

@@ -79,7 +79,7 @@ bool fmt_ok(int f) { return f == SSG_E4M3 || f == SSG_E5M2; }
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct SavedLayout {
-    size_t scalars, partials, s, sinv, h_camax, w3_camax, x_q, w1_q, w2_q, U, G, h_q, w3_q, total;
+    size_t scalars, partials, s, sinv, h_camax, w3_camax, x_q, w1_q, w2_q, U, G, h_q, w3_q, h_b, h_bT, w3T, total;
 };
 // scalar slots of `saved` (floats; amax slots are accumulated as bit patterns)
 enum { S_SX = 0, S_SW1, S_SW2, S_SW3, S_AMAX_X, S_AMAX_W1, S_AMAX_W2, S_AMAX_W3S, S_HMAX, S_COUNT = 64 };
@@ -99,11 +99,14 @@ SavedLayout saved_layout(const ssg_mlp_desc &d) {
     L.U = take(T * f * 2); L.G = take(T * f * 2);
     L.h_q = take(T * f);
     L.w3_q = take(f * dm);
+    // last layer left in bf16 (Section 4.3): the bf16 SwiGLU output, its transposed copy and W3 transposed
+    const size_t bf = d.w3_layer_bf16 ? 2 : 0;
+    L.h_b = take(T * f * bf); L.h_bT = take(T * f * bf); L.w3T = take(f * dm * bf);
     L.total = o;
     return L;
 }
 
-struct WorkLayout { size_t scalars, partials, dy_q, dU, dG, du_q, dg_q, dx_tmp, total; };
+struct WorkLayout { size_t scalars, partials, dy_q, dU, dG, du_q, dg_q, dx_tmp, dyT, total; };
 enum { W_SDY = 0, W_SDU, W_SDG, W_AMAX_DY, W_AMAX_DU, W_AMAX_DG, W_COUNT = 64 };
 
 WorkLayout work_layout(const ssg_mlp_desc &d) {
@@ -117,6 +120,7 @@ WorkLayout work_layout(const ssg_mlp_desc &d) {
     L.dU = take(T * f * 2); L.dG = take(T * f * 2);
     L.du_q = take(T * f); L.dg_q = take(T * f);
     L.dx_tmp = take(T * dm * 4);                        // fp32 first product of the input gradient
+    L.dyT = take(d.w3_layer_bf16 ? T * dm * 2 : 0);     // bf16 dY transposed (last layer left in bf16)
     L.total = o;
     return L;
 }
@@ -148,6 +152,14 @@ ssg_status check_desc(const ssg_mlp_desc *d, const char *who) {
     if (d->h_counters != nullptr && (reinterpret_cast<uintptr_t>(d->h_counters) & 7u))
         return fail(SSG_ERR_ARG, "%s: h_counters is not 8-byte aligned", who);
     if (d->keep_bf16_grads != 0 && d->keep_bf16_grads != 1) return fail(SSG_ERR_ARG, "%s: keep_bf16_grads must be 0 or 1", who);
+    if (d->w3_layer_bf16 != 0 && d->w3_layer_bf16 != 1) return fail(SSG_ERR_ARG, "%s: w3_layer_bf16 must be 0 or 1", who);
+    if (d->w3_layer_bf16) {
+        if (d->smooth) return fail(SSG_ERR_ARG, "%s: w3_layer_bf16 = 1 leaves the SwiGLU output unquantized: smooth must be 0", who);
+        if (d->scale_mode != SSG_SCALE_CURRENT || d->h_scale_mode != SSG_SCALE_CURRENT)
+            return fail(SSG_ERR_UNSUPPORTED, "%s: w3_layer_bf16 = 1 is built for current scaling only", who);
+    }
+    for (int i = 0; i < 3; ++i)
+        if (d->reserved[i] != 0) return fail(SSG_ERR_ARG, "%s: reserved fields must be 0", who);
     return SSG_OK;
 }
 
@@ -655,6 +667,9 @@ ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_m
     out->w1_q = b + L.w1_q; out->w2_q = b + L.w2_q;
     out->h_q = b + L.h_q; out->w3_q = b + L.w3_q;
     out->U = b + L.U; out->G = b + L.G;
+    out->h_b = desc->w3_layer_bf16 ? b + L.h_b : nullptr;
+    out->h_bT = desc->w3_layer_bf16 ? b + L.h_bT : nullptr;
+    out->w3T = desc->w3_layer_bf16 ? b + L.w3T : nullptr;
     return SSG_OK;
 }
 
@@ -668,6 +683,7 @@ ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspac
     out->dy_q = b + L.dy_q;
     out->du_q = b + L.du_q; out->dg_q = b + L.dg_q;
     out->dU = b + L.dU; out->dG = b + L.dG;
+    out->dyT = desc->w3_layer_bf16 ? b + L.dyT : nullptr;
     return SSG_OK;
 }
 
@@ -702,6 +718,11 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     g2.A = b + L.h_q; g2.B = b + L.w3_q;
     g2.sa = desc->smooth ? nullptr : s; g2.sb = sc + S_SW3;
     g2.C = y; g2.c_f32 = desc->y_dtype == SSG_F32;
+    const bool bf16_last = desc->w3_layer_bf16 != 0;
+    if (bf16_last) {
+        // Section 4.3: the last linear layer on bf16 operands: y = h_b W3^T, no scales
+        g2.a_fmt = ssg::kBF16; g2.A = b + L.h_b; g2.B = static_cast<const uint8_t *>(W3); g2.sa = nullptr; g2.sb = nullptr;
+    }
     if (!ssg::gemm_args_ok(g) || !ssg::gemm_args_ok(g2)) return fail(SSG_ERR_ARG, "ssg_mlp_fwd: internal GEMM arguments");
     if ((rc = check_entry("ssg_mlp_fwd")) != SSG_OK) return rc;
 
@@ -743,10 +764,30 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
         quantize_input(W1, f, dm, part_w1, 1, sc + S_AMAX_W1, sc + S_SW1, b + L.w1_q);
         quantize_input(W2, f, dm, part_w2, 2, sc + S_AMAX_W2, sc + S_SW2, b + L.w2_q);
         // per-channel range of w3, needed for the range of s^-1 * w3 (constant between weight updates)
-        ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
+        if (!bf16_last) ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
+        // last layer in bf16: its input gradient contracts over d, so W3 [d,f] is also kept transposed
+        else ssg::launch_transpose_bf16(W3, dm, f, b + L.w3T, st);
     }
 
     ssg::launch_gemm(g, st);
+
+    if (bf16_last) {
+        // the SwiGLU output stays in bf16 (rounded once from the fp32 product), straight and transposed
+        ssg::launch_swiglu_bf16(b + L.U, b + L.G, T, f, b + L.h_b, b + L.h_bT, st);
+        ssg::launch_gemm(g2, st);
+        if (state) {
+            ssg::ScalingUpdate u;
+            u.pow2 = pow2;
+            u.slots[0] = part_x; u.tensor[0] = 0; u.fmt[0] = ssg::kE4M3; u.count = 1;
+            if (!cached) {
+                u.slots[1] = part_w1; u.tensor[1] = 1; u.fmt[1] = ssg::kE4M3;
+                u.slots[2] = part_w2; u.tensor[2] = 2; u.fmt[2] = ssg::kE4M3;
+                u.count = 3;
+            }
+            ssg::launch_scaling_update(state, u, st);
+        }
+        return check_launch("ssg_mlp_fwd");
+    }
 
     // a5: factors s_i, s_i^-1 and the range of s^-1 * w3 (from the per-channel range of w3); plain block:
     // one scale for all of h, from its own range or as the caller gives it
@@ -860,6 +901,15 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     g5a.layout = 2;                                                                    // dU^ [T,f] = [K,M], x^ [T,d] = [K,N]
     g5a.A = wk + Wl.du_q; g5a.B = sv + L.x_q; g5a.sa = wsc + W_SDU; g5a.sb = sc + S_SX; g5a.C = dW1; g5a.c_f32 = dw_f32;
     g5b = g5a; g5b.A = wk + Wl.dg_q; g5b.sa = wsc + W_SDG; g5b.C = dW2;
+    const bool bf16_last = desc->w3_layer_bf16 != 0;
+    if (bf16_last) {
+        // Section 4.3: dH = dY W3 and dW3 = dY^T h_b on bf16 operands (the transposed copies give every operand its
+        // contraction index contiguous), no scales, no channel factors
+        g.a_fmt = ssg::kBF16; g.layout = 0; g.K = dm;
+        g.A = static_cast<const uint8_t *>(dy); g.B = sv + L.w3T; g.sa = nullptr; g.sb = nullptr; g.col_scale = nullptr;
+        g3.a_fmt = ssg::kBF16; g3.layout = 0;
+        g3.A = wk + Wl.dyT; g3.B = sv + L.h_bT; g3.sa = nullptr; g3.sb = nullptr; g3.col_scale = nullptr;
+    }
     for (const ssg::GemmArgs *a : {&g, &g3, &g4a, &g5a, &g5b})
         if (!ssg::gemm_args_ok(*a)) return fail(SSG_ERR_ARG, "ssg_mlp_bwd: internal GEMM arguments");
     if (!dx_one && !ssg::gemm_args_ok(g4b)) return fail(SSG_ERR_ARG, "ssg_mlp_bwd: internal GEMM arguments");
@@ -867,7 +917,8 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     // each, so that a partly filled last round of workgroups is paid once per group and the epilogue traffic of one
     // GEMM runs under the main loops of the others
     const ssg::GemmArgs *group_a[2] = {&g, &g3}, *group_b[3] = {&g4a, &g5a, &g5b};
-    const bool grouped = gemm_grouping_enabled() && dx_one && ssg::gemm_group_ok(group_a, 2) && ssg::gemm_group_ok(group_b, 3);
+    const bool grouped_b = gemm_grouping_enabled() && dx_one && ssg::gemm_group_ok(group_b, 3);
+    const bool grouped = grouped_b && ssg::gemm_group_ok(group_a, 2);
     if ((rc = check_entry("ssg_mlp_bwd")) != SSG_OK) return rc;
 
     ssg::launch_fill_u32(wscb, (Wl.partials - Wl.scalars) / 4 + 3 * ssg::kAmaxSlotWords, 0u, st);
@@ -876,13 +927,16 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     ssg::CastArgs c;
     c.src = dy; c.kind = ssg::SRC_BF16; c.rows = T; c.cols = dm; c.fmt = ssg::kE5M2; c.pow2 = pow2;
     c.amax_slots = ssg::kAmaxSlots; c.scale_out = wsc + W_SDY; c.dst = wk + Wl.dy_q;
-    if (delayed) {
+    if (bf16_last) {
+        // dY is used as the bf16 tensor it is; only its transposed copy is needed (for dW3)
+        ssg::launch_transpose_bf16(dy, T, dm, wk + Wl.dyT, st);
+    } else if (delayed) {
         c.scale_in = state_scale(3); c.record = state_dy_slots;
     } else {
         ssg::launch_amax(dy, ssg::SRC_BF16, (size_t)(T * dm), part_dy, ssg::kAmaxSlots, st);
         c.amax = reinterpret_cast<float *>(part_dy); c.amax_out = wsc + W_AMAX_DY;
     }
-    ssg::launch_cast(c, st);
+    if (!bf16_last) ssg::launch_cast(c, st);
     c.record = nullptr;
 
     if (grouped) ssg::launch_gemm_group(group_a, 2, st);
@@ -899,6 +953,9 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     cast_grad(wk + Wl.dG, reinterpret_cast<float *>(part_dg), wsc + W_AMAX_DG, wsc + W_SDG, wk + Wl.dg_q);
     if (grouped) {
         ssg::launch_gemm_group(group_b, 3, st);
+    } else if (grouped_b) {
+        ssg::launch_gemm(g3, st);
+        ssg::launch_gemm_group(group_b, 3, st);
     } else {
         ssg::launch_gemm(g3, st);
         ssg::launch_gemm(g4a, st);
@@ -912,6 +969,9 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
         u.slots[0] = delayed ? state_dy_slots : part_dy; u.tensor[0] = 3; u.fmt[0] = ssg::kE5M2;
         u.slots[1] = part_du; u.tensor[1] = 4; u.fmt[1] = ssg::kE5M2;
         u.slots[2] = part_dg; u.tensor[2] = 5; u.fmt[2] = ssg::kE5M2;
+        if (bf16_last) {                 // dY is not quantized: no range of it was taken
+            u.slots[0] = part_du; u.tensor[0] = 4; u.slots[1] = part_dg; u.tensor[1] = 5; u.count = 2;
+        }
         ssg::launch_scaling_update(state, u, st);
     }
     return check_launch("ssg_mlp_bwd");

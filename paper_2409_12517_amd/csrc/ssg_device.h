@@ -9,6 +9,7 @@ namespace ssg {
 
 constexpr int kE4M3 = 0;
 constexpr int kE5M2 = 1;
+constexpr int kBF16 = 2;            // operand type of the unquantized (bf16) GEMMs, beside the two FP8 formats
 
 template <int FMT> struct Fp8Traits;
 // overflow_above = fmax plus half the spacing of the top binade: a magnitude beyond it is kept finite only by

@@ -8,7 +8,9 @@ namespace ssg {
 bool gemm_args_ok(const GemmArgs &a) {
     if (a.epilogue < EPI_STORE || a.epilogue > EPI_SWIGLU_BWD_Q) return false;
     if (!a.A || !a.B || !a.C || a.M <= 0 || a.N <= 0 || a.K <= 0) return false;
-    if (a.a_fmt != kE4M3 && a.a_fmt != kE5M2) return false;
+    if (a.a_fmt != kE4M3 && a.a_fmt != kE5M2 && a.a_fmt != kBF16) return false;
+    // bf16 operands: the two forms the unquantized last layer needs, K-contiguous operands only
+    if (a.a_fmt == kBF16 && (a.layout != 0 || a.part != 0 || (a.epilogue != EPI_STORE && a.epilogue != EPI_SWIGLU_BWD))) return false;
     const bool dual = a.epilogue == EPI_SWIGLU || a.epilogue == EPI_SWIGLU_Q;
     if (dual && (!a.B2 || a.a_fmt != kE4M3 || a.layout != 0)) return false;
     if (a.epilogue == EPI_SWIGLU && (!a.C2 || !a.camax_bits)) return false;
@@ -16,7 +18,7 @@ bool gemm_args_ok(const GemmArgs &a) {
     if (a.layout < 0 || a.layout > 2) return false;
     const bool bwd = a.epilogue == EPI_SWIGLU_BWD || a.epilogue == EPI_SWIGLU_BWD_Q;
     // the backward forms are built for the block's own use: gradient operand E5M2, weight operand K-major
-    if (bwd && (a.layout != 1 || a.a_fmt != kE5M2)) return false;
+    if (bwd && a.a_fmt != kBF16 && (a.layout != 1 || a.a_fmt != kE5M2)) return false;
     if (a.epilogue == EPI_SWIGLU_BWD_Q && (!a.q_scale || !a.q_scale2 || !a.q_scale_out || !a.q_scale_out2)) return false;
     if (a.part < 0 || a.part > 3) return false;
     if (a.part != 0 && (a.layout != 1 || a.a_fmt != kE5M2)) return false;
@@ -37,6 +39,7 @@ int gemm_profile_tag(const GemmArgs &a) {
     // 2 * epilogue + A format; the halves of a sum of two products run as two launches get 9 and 10, the sum in
     // one launch 11
     if (a.part) return 8 + a.part;
+    if (a.a_fmt == kBF16) return a.epilogue == EPI_STORE ? 20 : 21;
     return 2 * (a.epilogue == EPI_SWIGLU_BWD_Q ? (int)EPI_SWIGLU_BWD : a.epilogue) + a.a_fmt;
 }
 
@@ -54,7 +57,8 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st) {
     profile_before(gemm_profile_tag(a), st);
     switch (a.epilogue) {
         case EPI_STORE:
-            if (a.layout == 2) launch_fmt<EPI_STORE, 2>(p, a.a_fmt, blocks, st);
+            if (a.a_fmt == kBF16) hipLaunchKernelGGL((gemm_kernel<EPI_STORE, kBF16, 0, 0>), dim3(blocks), dim3(kThreads), 0, st, p);
+            else if (a.layout == 2) launch_fmt<EPI_STORE, 2>(p, a.a_fmt, blocks, st);
             else if (a.layout == 1) launch_fmt<EPI_STORE, 1>(p, a.a_fmt, blocks, st);
             else launch_fmt<EPI_STORE, 0>(p, a.a_fmt, blocks, st);
             break;

@@ -62,7 +62,7 @@ bool gemm_group_ok(const GemmArgs *const *list, int n) {
     auto wgrad = [](const GemmArgs &a) { return a.epilogue == EPI_STORE && a.part == 0 && a.layout == 2 && a.a_fmt == kE5M2; };
     if (n == 2) {
         const GemmArgs &a = *list[0];
-        return (a.epilogue == EPI_SWIGLU_BWD || a.epilogue == EPI_SWIGLU_BWD_Q) && wgrad(*list[1]);
+        return (a.epilogue == EPI_SWIGLU_BWD || a.epilogue == EPI_SWIGLU_BWD_Q) && a.a_fmt == kE5M2 && wgrad(*list[1]);
     }
     return list[0]->epilogue == EPI_STORE && list[0]->part == 3 && wgrad(*list[1]) && wgrad(*list[2]);
 }
@@ -93,7 +93,9 @@ bool launch_gemm_bwd(const GemmArgs &a, hipStream_t st) {
     const GemmParams p = make_gemm_params(a);
     const dim3 grid((unsigned)p.tiles_m * (unsigned)p.tiles_n);
     profile_before(gemm_profile_tag(a), st);
-    if (a.epilogue == EPI_SWIGLU_BWD) hipLaunchKernelGGL((gemm_kernel<EPI_SWIGLU_BWD, kE5M2, 0, 1>), grid, dim3(kThreads), 0, st, p);
+    if (a.epilogue == EPI_SWIGLU_BWD && a.a_fmt == kBF16)
+        hipLaunchKernelGGL((gemm_kernel<EPI_SWIGLU_BWD, kBF16, 0, 0>), grid, dim3(kThreads), 0, st, p);
+    else if (a.epilogue == EPI_SWIGLU_BWD) hipLaunchKernelGGL((gemm_kernel<EPI_SWIGLU_BWD, kE5M2, 0, 1>), grid, dim3(kThreads), 0, st, p);
     else if (a.epilogue == EPI_SWIGLU_BWD_Q) hipLaunchKernelGGL((gemm_kernel<EPI_SWIGLU_BWD_Q, kE5M2, 0, 1>), grid, dim3(kThreads), 0, st, p);
     else if (a.part == 1) hipLaunchKernelGGL((gemm_kernel<EPI_STORE, kE5M2, 1, 1>), grid, dim3(kThreads), 0, st, p);
     else if (a.part == 2) hipLaunchKernelGGL((gemm_kernel<EPI_STORE, kE5M2, 2, 1>), grid, dim3(kThreads), 0, st, p);

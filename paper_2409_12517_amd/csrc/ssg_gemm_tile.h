@@ -91,9 +91,25 @@ __device__ __forceinline__ void dma16_s(const uint8_t *base_uniform, uint32_t la
 #endif
 }
 
+// AFMT = kE4M3 / kE5M2: the 32 bytes of a fragment are 32 FP8 codes of one row, one MFMA with K = 64 per fragment
+// pair.  AFMT = kBF16 (both operands bf16, the comparison variant with the last linear layer left unquantized):
+// the same 32 bytes are 16 bf16 of one row -- two 16-byte pieces of 8 elements each -- and a fragment pair feeds two
+// MFMAs with K = 16 (v_mfma_f32_32x32x16_bf16), the first on the low pieces of both operands, the second on the
+// high ones.  Which elements of K meet in which MFMA does not matter as long as A and B agree, and they do: both
+// fragments come from the same LDS layout through the same lane arithmetic.  Per 128 bytes of K this is twice the
+// MFMA instructions at half the duration each, and K in bytes is twice the element count.
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
 template <int AFMT>
 __device__ __forceinline__ v16f mfma(const v8i &a, const v8i &b, const v16f &c) {
-    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, AFMT, 0, 0, 0, 0, 0);
+    if constexpr (AFMT == kBF16) {
+        const v4i a_lo = {a[0], a[1], a[2], a[3]}, a_hi = {a[4], a[5], a[6], a[7]};
+        const v4i b_lo = {b[0], b[1], b[2], b[3]}, b_hi = {b[4], b[5], b[6], b[7]};
+        const v16f t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a_lo), __builtin_bit_cast(v8bf, b_lo), c, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a_hi), __builtin_bit_cast(v8bf, b_hi), t, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, AFMT, 0, 0, 0, 0, 0);
+    }
 }
 
 // The dequantization factor 1 / (sa * sb).  The product of two binary32 scales can leave the binary32 range
@@ -719,7 +735,8 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
 inline GemmParams make_gemm_params(const GemmArgs &a) {
     GemmParams p;
     p.A = a.A; p.B = a.B; p.B2 = a.B2;
-    p.M = a.M; p.N = a.N; p.K = a.K;
+    p.M = a.M; p.N = a.N;
+    p.K = a.a_fmt == kBF16 ? 2 * a.K : a.K;          // the kernel counts K in bytes
     p.sa = a.sa; p.sb = a.sb; p.sb2 = a.sb2; p.col_scale = a.col_scale;
     p.C = a.C; p.C2 = a.C2;
     p.U = (const uint16_t *)a.U; p.G = (const uint16_t *)a.G;

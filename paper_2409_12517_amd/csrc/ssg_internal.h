@@ -63,6 +63,11 @@ void launch_fold_range(const float *w3_camax, const float *sinv, int64_t f, uint
 
 void launch_swiglu(const void *U, const void *G, int64_t n, float *h, hipStream_t st);
 
+// bf16 [rows, cols] -> transposed copy [cols, rows]; and the SwiGLU product of bf16 U, G [rows, cols] rounded once to
+// bf16, as it stands (h) and transposed (h_t) -- the operands of the last linear layer when it is left in bf16
+void launch_transpose_bf16(const void *src, int64_t rows, int64_t cols, void *dst_t, hipStream_t st);
+void launch_swiglu_bf16(const void *U, const void *G, int64_t rows, int64_t cols, void *h, void *h_t, hipStream_t st);
+
 // Q_E4M3 of a bf16 [rows, cols] matrix whose row i is first multiplied by row_scale[i]; `slots` are
 // kAmaxSlots zeroed slotted range words (scratch)
 void launch_rowscale_quantize(const void *w, const float *row_scale, int64_t rows, int64_t cols, uint32_t *slots,
@@ -80,7 +85,8 @@ enum Epilogue {
 
 struct GemmArgs {
     int epilogue = EPI_STORE;
-    int a_fmt = 0;                      // kE4M3 / kE5M2 (B is always E4M3)
+    int a_fmt = 0;                      // kE4M3 / kE5M2 (B is always E4M3); kBF16 = 2: A and B are bf16 (layout 0,
+                                        // EPI_STORE or EPI_SWIGLU_BWD only; K counts elements)
     int64_t M = 0, N = 0, K = 0;
     const uint8_t *A = nullptr;         // [M, K]   (layout 2: stored K-major, [K, M])
     const uint8_t *B = nullptr;         // [N, K]   (layout 1, 2: stored K-major, [K, N])
@@ -131,7 +137,8 @@ bool launch_gemm_group(const GemmArgs *const *list, int n, hipStream_t st);
 void profile_before(int tag, hipStream_t st, double bytes = 0.0);
 void profile_after(hipStream_t st);
 // tags of the elementwise passes (the GEMM tags are listed with ssg_profile_read)
-constexpr int kTagAmax = 40, kTagCast = 41, kTagCastSwiglu = 42, kTagCastColscale = 43, kTagColAmax = 44, kTagSmall = 45;
+constexpr int kTagAmax = 40, kTagCast = 41, kTagCastSwiglu = 42, kTagCastColscale = 43, kTagColAmax = 44, kTagSmall = 45,
+              kTagTranspose = 46;
 
 // ---- delayed scaling: amax history per tensor (ssg_quant.hip) ----------------------
 // State words: tensor k (0..5 = x, w1, w2, dy, du, dg) owns words [32k, 32k+32): [0] the scale the next

@@ -634,6 +634,65 @@ void launch_swiglu(const void *U, const void *G, int64_t n, float *h, hipStream_
                        LoadSwiglu{(const uint16_t *)U, (const uint16_t *)G}, n8, h);
 }
 
+// ------------------------------------------------------------------ bf16 transposes (last layer left in bf16)
+// The comparison variant of Section 4.3 runs the last linear layer and its two gradient contractions on bf16
+// operands; those contract over the index that is not contiguous in W3 [d,f], dY [T,d] and h [T,f], so transposed
+// bf16 copies are written (64 x 64 tiles through LDS, 16-byte accesses on both sides).  SWIGLU: the source is the
+// SwiGLU product of bf16 U, G, rounded once to bf16; it is written both as it stands and transposed.
+template <bool SWIGLU>
+__global__ void __launch_bounds__(256)
+transpose_bf16_kernel(const uint16_t *__restrict__ src, const uint16_t *__restrict__ src2, int64_t rows, int64_t cols,
+                      uint16_t *__restrict__ dst, uint16_t *__restrict__ dst_t) {
+    __shared__ uint16_t tile[64][64 + 8];
+    const int64_t row0 = (int64_t)blockIdx.y * 64, col0 = (int64_t)blockIdx.x * 64;
+    const int c8 = (threadIdx.x & 7) * 8, r = threadIdx.x >> 3;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int64_t row = row0 + r + 32 * half, col = col0 + c8;
+        uint4 q = make_uint4(0u, 0u, 0u, 0u);
+        if (row < rows && col < cols) {
+            const size_t at = (size_t)row * (size_t)cols + (size_t)col;
+            if (SWIGLU) {
+                float v[8];
+                LoadSwiglu{src, src2}.load8(at, v);
+                q = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+                *reinterpret_cast<uint4 *>(dst + at) = q;
+            } else {
+                q = *reinterpret_cast<const uint4 *>(src + at);
+            }
+        }
+        *reinterpret_cast<uint4 *>(&tile[r + 32 * half][c8]) = q;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int c = r + 32 * half;                          // source column = row of the transposed copy
+        const int64_t col = col0 + c, row = row0 + c8;        // c8 now counts source rows
+        if (col < cols && row < rows) {
+            uint32_t w[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) w[k] = (uint32_t)tile[c8 + 2 * k][c] | ((uint32_t)tile[c8 + 2 * k + 1][c] << 16);
+            *reinterpret_cast<uint4 *>(dst_t + (size_t)col * (size_t)rows + (size_t)row) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+}
+void launch_transpose_bf16(const void *src, int64_t rows, int64_t cols, void *dst_t, hipStream_t st) {
+    if (rows == 0 || cols == 0) return;
+    const dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
+    profile_before(kTagTranspose, st, 4.0 * (double)rows * (double)cols);
+    hipLaunchKernelGGL(transpose_bf16_kernel<false>, grid, dim3(256), 0, st, (const uint16_t *)src, nullptr, rows, cols,
+                       nullptr, (uint16_t *)dst_t);
+    profile_after(st);
+}
+void launch_swiglu_bf16(const void *U, const void *G, int64_t rows, int64_t cols, void *h, void *h_t, hipStream_t st) {
+    if (rows == 0 || cols == 0) return;
+    const dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
+    profile_before(kTagTranspose, st, 8.0 * (double)rows * (double)cols);
+    hipLaunchKernelGGL(transpose_bf16_kernel<true>, grid, dim3(256), 0, st, (const uint16_t *)U, (const uint16_t *)G, rows, cols,
+                       (uint16_t *)h, (uint16_t *)h_t);
+    profile_after(st);
+}
+
 // ------------------------------------------------------------------ per-row factor, then per-tensor Q
 // w1~ = Q(s_i * w1_i) of the inference form (end of Section 4.4): row i of a [rows, cols] bf16 matrix is
 // multiplied by rs[i] (one fp32 multiply), the result is quantized per tensor to E4M3.  Run once per

@@ -24,7 +24,7 @@ HQ_DIFF_FRAC, HQ_DIFF_GT1_FRAC = 4e-3, 6e-5   # fraction of h^ codes that differ
 class Block:
     """Device buffers of one forward+backward call and typed views into saved/workspace."""
 
-    def __init__(self, inp, smooth=1, y_dtype=None, dw_dtype=None, rnd=None, h_scale=None, count=False):
+    def __init__(self, inp, smooth=1, y_dtype=None, dw_dtype=None, rnd=None, h_scale=None, count=False, w3_layer_bf16=0):
         self.T, self.d = inp["x"].shape
         self.f = inp["W1"].shape[0]
         # optional: a given scale of h (plain block) and the overflow / underflow counters of the h cast
@@ -34,7 +34,7 @@ class Block:
                                   rnd=ssg.SSG_ROUND_EXACT_DIV if rnd is None else rnd,
                                   y_dtype=ssg.SSG_BF16 if y_dtype is None else y_dtype,
                                   dw_dtype=ssg.SSG_F32 if dw_dtype is None else dw_dtype,
-                                  h_scale=self.h_scale, h_counters=self.h_counters)
+                                  h_scale=self.h_scale, h_counters=self.h_counters, w3_layer_bf16=w3_layer_bf16)
         self.x, self.W1, self.W2, self.W3 = (gu.dev(inp[k]) for k in ("x", "W1", "W2", "W3"))
         self.dY = gu.dev(inp["dY"]) if inp.get("dY") is not None else None
         ydt = torch.bfloat16 if self.desc.y_dtype == ssg.SSG_BF16 else torch.float32
@@ -254,6 +254,69 @@ def test_plain_block_with_a_given_h_scale_and_device_counters():
     cur_blk = Block(inp, smooth=0, count=True)
     cur_blk.fwd()
     assert int(cur_blk.h_counters[0]) == 0 and int(cur_blk.h_counters[1]) > 10 * max(flushed_s, 1)
+
+
+@pytest.mark.parametrize("T,d,f", [(272, 256, 688), (512, 512, 1024)])
+def test_last_layer_left_in_bf16(T, d, f):
+    """The comparison variant of Section 4.3 / Table 3 ("FP8 + SwiGLU output in BF16"): the FP8 part upstream bit
+    for bit, the bf16 SwiGLU output bit for bit from the device's own fp32 product, the three bf16 contractions
+    and the FP8 ones that follow to the GEMM bar against the oracle continued from the device's stored operands."""
+    inp = synth.make_inputs(T, d, f, seed=T + f)
+    npi = _np_inputs(inp)
+    blk = Block(inp, smooth=0, w3_layer_bf16=1)
+    blk.fwd()
+    ref = mlp.forward(npi["x"], npi["W1"], npi["W2"], npi["W3"], w3_layer_fp8=False)
+    sc = gu.f32(blk.sv("scales", (16,), torch.float32))
+    assert sc[0] == ref.sx and sc[1] == ref.sw1 and sc[2] == ref.sw2
+    x_q = gu.u8(blk.sv("x_q", (T, d), torch.uint8))
+    w1_q, w2_q = gu.u8(blk.sv("w1_q", (f, d), torch.uint8)), gu.u8(blk.sv("w2_q", (f, d), torch.uint8))
+    assert np.array_equal(x_q, ref.x_q) and np.array_equal(w1_q, ref.w1_q) and np.array_equal(w2_q, ref.w2_q)
+    U = gu.f32(blk.sv("U", (T, f), torch.bfloat16)); G = gu.f32(blk.sv("G", (T, f), torch.bfloat16))
+    gu.assert_close_gemm(U, ref.U, True, "U"); gu.assert_close_gemm(G, ref.G, True, "G")
+    # the bf16 SwiGLU output: one rounding of the device's own fp32 product, and its transposed copy
+    h = gu.empty_f32(T, f)
+    ssg.ssg_swiglu(blk.sv("U", (T, f), torch.bfloat16), blk.sv("G", (T, f), torch.bfloat16), T, f, h)
+    torch.cuda.synchronize()
+    h_np = gu.f32(h)
+    h_b = gu.f32(blk.sv("h_b", (T, f), torch.bfloat16))
+    assert np.array_equal(h_b.astype(np.float64), mlp.round_bf16(h_np))
+    assert np.array_equal(gu.f32(blk.sv("h_bT", (f, T), torch.bfloat16)), h_b.T)
+    assert np.array_equal(gu.f32(blk.sv("w3T", (f, d), torch.bfloat16)), npi["W3"].T)
+    # y = h_b W3^T on identical operands
+    y_cont = mlp.round_bf16(h_b.astype(np.float64) @ npi["W3"].astype(np.float64).T)
+    gu.assert_close_gemm(gu.f32(blk.y), y_cont, True, "Y (bf16 last layer)")
+    rel = np.linalg.norm(gu.f32(blk.y) - ref.Y) / np.linalg.norm(ref.Y)
+    assert rel < E2E_NORM_FWD, rel
+    # backward, continued from the device's stored forward state
+    fw_gpu = mlp.Forward(quantized=True, smooth=False, w3_layer_fp8=False, x_q=x_q, sx=np.float32(sc[0]), w1_q=w1_q,
+                         sw1=np.float32(sc[1]), w2_q=w2_q, sw2=np.float32(sc[2]), U=U.astype(np.float64),
+                         G=G.astype(np.float64), h=h_np, h_b=h_b.astype(np.float64), W3=npi["W3"].astype(np.float64))
+    blk.bwd()
+    assert np.array_equal(gu.f32(blk.wv("dyT", (d, T), torch.bfloat16)), npi["dY"].T)
+    cont = mlp.backward(fw_gpu, npi["dY"])
+    dU = gu.f32(blk.wv("dU", (T, f), torch.bfloat16)); dG = gu.f32(blk.wv("dG", (T, f), torch.bfloat16))
+    gu.assert_close_gemm(dU, cont.dU, True, "dU"); gu.assert_close_gemm(dG, cont.dG, True, "dG")
+    cont2 = continue_backward(fw_gpu, npi["dY"], dU, dG, "bf16", "f32")
+    wsc = gu.f32(blk.wv("scales", (8,), torch.float32))
+    assert wsc[1] == cont2.sdu and wsc[2] == cont2.sdg
+    assert np.array_equal(gu.u8(blk.wv("du_q", (T, f), torch.uint8)), cont2.du_q)
+    assert np.array_equal(gu.u8(blk.wv("dg_q", (T, f), torch.uint8)), cont2.dg_q)
+    gu.assert_close_gemm(gu.f32(blk.dx), cont2.dX, True, "dX")
+    gu.assert_close_gemm(gu.f32(blk.dW1), cont2.dW1, False, "dW1")
+    gu.assert_close_gemm(gu.f32(blk.dW2), cont2.dW2, False, "dW2")
+    gu.assert_close_gemm(gu.f32(blk.dW3), cont2.dW3, False, "dW3 (bf16 operands)")
+    pure = mlp.backward(ref, npi["dY"])
+    for name, got in (("dX", blk.dx), ("dW1", blk.dW1), ("dW2", blk.dW2), ("dW3", blk.dW3)):
+        r = getattr(pure, name)
+        assert np.linalg.norm(gu.f32(got) - r) / np.linalg.norm(r) < E2E_NORM_BWD, name
+
+
+def test_last_layer_in_bf16_needs_the_plain_block_and_current_scaling():
+    with pytest.raises(ssg.SsgError):
+        ssg.ssg_mlp_fwd(ssg.make_desc(256, 256, 512, smooth=1, w3_layer_bf16=1), 256, 256, 256, 256, 256, 256, stream=0,
+                        saved_bytes=1 << 40)
+    assert ssg.ssg_mlp_saved_bytes(ssg.make_desc(256, 256, 512, smooth=0, w3_layer_bf16=1)) > \
+        ssg.ssg_mlp_saved_bytes(ssg.make_desc(256, 256, 512, smooth=0)) + 2 * 2 * 256 * 512
 
 
 def test_fp32_outputs_bf16_weight_grads_and_pow2_scales():
