@@ -745,24 +745,31 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     uint32_t *state = static_cast<uint32_t *>(desc->scaling_state);
     auto state_scale = [&](int k) { return reinterpret_cast<float *>(state + (size_t)k * ssg::kScalingStride); };
     auto state_slots = [&](int j) { return state + ssg::kScalingHeaderWords + (size_t)j * ssg::kAmaxSlotWords; };
-    ssg::CastArgs c;
-    c.kind = ssg::SRC_BF16; c.fmt = ssg::kE4M3; c.pow2 = pow2;
-    c.amax_slots = ssg::kAmaxSlots;
-    auto quantize_input = [&](const void *src, int64_t rows, int64_t cols, uint32_t *part, int k, float *amax_out,
-                              float *scale_out, uint8_t *dst) {
+    // x and (unless cached) W1, W2 go through one range launch and one cast launch together
+    ssg::CastArgs casts[3];
+    const void *srcs[3]; size_t counts[3]; uint32_t *slot_ptrs[3];
+    int n_in = 0;
+    auto add_input = [&](const void *src, int64_t rows, int64_t cols, uint32_t *part, int k, float *amax_out,
+                         float *scale_out, uint8_t *dst) {
+        ssg::CastArgs &c = casts[n_in];
+        c.kind = ssg::SRC_BF16; c.fmt = ssg::kE4M3; c.pow2 = pow2; c.amax_slots = ssg::kAmaxSlots;
         c.src = src; c.rows = rows; c.cols = cols; c.scale_out = scale_out; c.dst = dst;
         if (delayed) {
-            c.amax = nullptr; c.amax_out = nullptr; c.scale_in = state_scale(k); c.record = state_slots(k);
+            c.scale_in = state_scale(k); c.record = state_slots(k);
         } else {
-            ssg::launch_amax(src, ssg::SRC_BF16, (size_t)(rows * cols), part, ssg::kAmaxSlots, st);
-            c.amax = reinterpret_cast<float *>(part); c.amax_out = amax_out; c.scale_in = nullptr; c.record = nullptr;
+            c.amax = reinterpret_cast<float *>(part); c.amax_out = amax_out;
         }
-        ssg::launch_cast(c, st);
+        srcs[n_in] = src; counts[n_in] = (size_t)(rows * cols); slot_ptrs[n_in] = part;
+        ++n_in;
     };
-    quantize_input(x, T, dm, part_x, 0, sc + S_AMAX_X, sc + S_SX, b + L.x_q);
+    add_input(x, T, dm, part_x, 0, sc + S_AMAX_X, sc + S_SX, b + L.x_q);
     if (!cached) {
-        quantize_input(W1, f, dm, part_w1, 1, sc + S_AMAX_W1, sc + S_SW1, b + L.w1_q);
-        quantize_input(W2, f, dm, part_w2, 2, sc + S_AMAX_W2, sc + S_SW2, b + L.w2_q);
+        add_input(W1, f, dm, part_w1, 1, sc + S_AMAX_W1, sc + S_SW1, b + L.w1_q);
+        add_input(W2, f, dm, part_w2, 2, sc + S_AMAX_W2, sc + S_SW2, b + L.w2_q);
+    }
+    if (!delayed) ssg::launch_amax_batch(srcs, counts, slot_ptrs, n_in, st);
+    ssg::launch_cast_batch(casts, n_in, st);
+    if (!cached) {
         // per-channel range of w3, needed for the range of s^-1 * w3 (constant between weight updates)
         if (!bf16_last) ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
         // last layer in bf16: its input gradient contracts over d, so W3 [d,f] is also kept transposed
@@ -942,15 +949,19 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     if (grouped) ssg::launch_gemm_group(group_a, 2, st);
     else ssg::launch_gemm(g, st);
 
-    // a11: two tensors, two E5M2 scales (their ranges came out of the epilogue above either way)
-    auto cast_grad = [&](const void *src, float *amax_slots, float *amax_out, float *scale_out, uint8_t *dst) {
-        if (delayed) return;             // done in the epilogue above
-        c.kind = ssg::SRC_BF16; c.rows = T; c.cols = f; c.src = src; c.scale_out = scale_out; c.dst = dst;
-        c.amax = amax_slots; c.amax_out = amax_out; c.scale_in = nullptr;
-        ssg::launch_cast(c, st);
-    };
-    cast_grad(wk + Wl.dU, reinterpret_cast<float *>(part_du), wsc + W_AMAX_DU, wsc + W_SDU, wk + Wl.du_q);
-    cast_grad(wk + Wl.dG, reinterpret_cast<float *>(part_dg), wsc + W_AMAX_DG, wsc + W_SDG, wk + Wl.dg_q);
+    // a11: two tensors, two E5M2 scales (their ranges came out of the epilogue above either way), one launch
+    if (!delayed) {                      // (under delayed scaling the epilogue above wrote the codes already)
+        ssg::CastArgs gc[2];
+        for (int k = 0; k < 2; ++k) {
+            gc[k].kind = ssg::SRC_BF16; gc[k].fmt = ssg::kE5M2; gc[k].pow2 = pow2; gc[k].amax_slots = ssg::kAmaxSlots;
+            gc[k].rows = T; gc[k].cols = f;
+        }
+        gc[0].src = wk + Wl.dU; gc[0].amax = reinterpret_cast<float *>(part_du); gc[0].amax_out = wsc + W_AMAX_DU;
+        gc[0].scale_out = wsc + W_SDU; gc[0].dst = wk + Wl.du_q;
+        gc[1].src = wk + Wl.dG; gc[1].amax = reinterpret_cast<float *>(part_dg); gc[1].amax_out = wsc + W_AMAX_DG;
+        gc[1].scale_out = wsc + W_SDG; gc[1].dst = wk + Wl.dg_q;
+        ssg::launch_cast_batch(gc, 2, st);
+    }
     if (grouped) {
         ssg::launch_gemm_group(group_b, 3, st);
     } else if (grouped_b) {

@@ -23,6 +23,8 @@ constexpr int kAmaxSlots = 64;
 constexpr int kAmaxSlotStride = 32;
 constexpr size_t kAmaxSlotWords = (size_t)kAmaxSlots * kAmaxSlotStride;
 void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, int slots, hipStream_t st);
+// up to three bf16 tensors in one launch, each into its own kAmaxSlots slotted words
+void launch_amax_batch(const void *const *src, const size_t *n, uint32_t *const *amax_bits, int count, hipStream_t st);
 
 struct CastArgs {
     const void *src = nullptr;       // bf16 / f32 [rows, cols]; U for SRC_SWIGLU
@@ -45,6 +47,8 @@ struct CastArgs {
                                      // range under the scale (saturated), [1] += nonzero elements cast to +-0
 };
 void launch_cast(const CastArgs &a, hipStream_t st);
+// up to three casts of the same form (source kind, format, optional parts) in one launch; others are launched singly
+void launch_cast_batch(const CastArgs *list, int n, hipStream_t st);
 
 // camax_bits[c] = max_r |v[r,c]| as float bits (zeroed by the caller).
 void launch_col_amax(const void *src, const void *src2, SrcKind kind, int64_t rows, int64_t cols,

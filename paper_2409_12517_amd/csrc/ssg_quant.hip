@@ -146,8 +146,17 @@ __device__ __forceinline__ uint32_t unbias_max_pk(ssg_i16x2 m) {
 // lane), grid-stride.  Measured on a 90 MB tensor: 13 us (6.9 TB/s) against 27-41 us for the generic kernel above
 // (which widens every element to fp32 and walks 32 KB units); more loads per lane or larger workgroups are slower.
 constexpr int kAmaxBf16Loads = 4;
+struct AmaxBatch {
+    const ssg_u32x4 *src[3];
+    size_t n16[3];
+    uint32_t *amax_bits[3];
+};
+// (up to three tensors per launch, blockIdx.y picks one: the ranges of x, W1, W2 share a launch)
 __global__ void __launch_bounds__(256)
-amax_bf16_kernel(const ssg_u32x4 *__restrict__ src, size_t n16, uint32_t *amax_bits, int slots) {
+amax_bf16_kernel(const AmaxBatch batch, int slots) {
+    const ssg_u32x4 *__restrict__ src = batch.src[blockIdx.y];
+    const size_t n16 = batch.n16[blockIdx.y];
+    uint32_t *amax_bits = batch.amax_bits[blockIdx.y];
     ssg_i16x2 m = {0x7f, 0x7f};
     const size_t run = (size_t)kAmaxBf16Loads * 256;
     for (size_t base = (size_t)blockIdx.x * run; base < n16; base += (size_t)gridDim.x * run) {
@@ -173,14 +182,37 @@ amax_bf16_kernel(const ssg_u32x4 *__restrict__ src, size_t n16, uint32_t *amax_b
     }
 }
 
+void launch_amax_batch(const void *const *src, const size_t *n, uint32_t *const *amax_bits, int count, hipStream_t st) {
+    AmaxBatch batch;
+    size_t largest = 0;
+    double bytes = 0.0;
+    int m = 0;
+    for (int i = 0; i < count && m < 3; ++i) {
+        if (n[i] / 8 == 0) continue;
+        batch.src[m] = (const ssg_u32x4 *)src[i]; batch.n16[m] = n[i] / 8; batch.amax_bits[m] = amax_bits[i];
+        largest = batch.n16[m] > largest ? batch.n16[m] : largest;
+        bytes += 2.0 * (double)n[i];
+        ++m;
+    }
+    if (m == 0) return;
+    for (int i = m; i < 3; ++i) { batch.src[i] = batch.src[0]; batch.n16[i] = 0; batch.amax_bits[i] = batch.amax_bits[0]; }
+    const size_t runs = (largest + kAmaxBf16Loads * 256 - 1) / (kAmaxBf16Loads * 256);
+    const unsigned blocks = (unsigned)(runs < 1024 ? runs : 1024);
+    profile_before(kTagAmax, st, bytes);
+    hipLaunchKernelGGL(amax_bf16_kernel, dim3(blocks, (unsigned)m), dim3(256), 0, st, batch, kAmaxSlots);
+    profile_after(st);
+}
+
 void launch_amax(const void *src, SrcKind kind, size_t n, uint32_t *amax_bits, int slots, hipStream_t st) {
     size_t n8 = n / 8;      // n is a multiple of 16 at every call site (rows, cols multiples of 16)
     if (n8 == 0) return;
     profile_before(kTagAmax, st, (kind == SRC_BF16 ? 2.0 : 4.0) * (double)n);
     if (kind == SRC_BF16) {
+        AmaxBatch batch;
+        for (int i = 0; i < 3; ++i) { batch.src[i] = (const ssg_u32x4 *)src; batch.n16[i] = n8; batch.amax_bits[i] = amax_bits; }
         const size_t runs = (n8 + kAmaxBf16Loads * 256 - 1) / (kAmaxBf16Loads * 256);
         const unsigned blocks = (unsigned)(runs < 1024 ? runs : 1024);
-        hipLaunchKernelGGL(amax_bf16_kernel, dim3(blocks), dim3(256), 0, st, (const ssg_u32x4 *)src, n8, amax_bits, slots);
+        hipLaunchKernelGGL(amax_bf16_kernel, dim3(blocks), dim3(256), 0, st, batch, slots);
     } else {
         const size_t units = (n8 + 2047) / 2048;
         const size_t cap = slots > 1 ? 2048 : 512;
@@ -217,13 +249,42 @@ __device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint3
 // COUNT: also count, into counters[0] and counters[1], the elements whose scaled magnitude lies beyond the
 // rounding interval of the largest finite value (only the clamp keeps them finite: overflow, Section 3) and
 // the nonzero elements whose code is +-0 (underflow).
+// Up to three tensors per launch (blockIdx.z picks the item; workgroups beyond an item's own tile grid leave at
+// once): the casts of x, W1, W2 -- and of dU, dG -- share a launch, which saves the ramp-up and drain of two launches.
+template <class Loader>
+struct CastItem {
+    Loader ld;
+    int64_t rows, cols;
+    const float *col_scale, *amax;
+    int amax_slots;
+    float *amax_out;
+    const float *scale_in;
+    float *scale_out;
+    uint8_t *dst, *dst_t;
+    uint32_t *record;
+    unsigned long long *counters;
+};
+template <class Loader>
+struct CastBatch {
+    CastItem<Loader> item[3];
+    int pow2;
+};
 template <class Loader, int FMT, bool COLSCALE, bool TRANSPOSED, bool RECORD = false, bool COUNT = false>
 __global__ void __launch_bounds__(256)
-cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col_scale,
-            const float *__restrict__ amax, int amax_slots, float *__restrict__ amax_out,
-            const float *__restrict__ scale_in, int pow2,
-            float *__restrict__ scale_out, uint8_t *__restrict__ dst, uint8_t *__restrict__ dst_t,
-            uint32_t *__restrict__ record = nullptr, unsigned long long *__restrict__ counters = nullptr) {
+cast_kernel(const CastBatch<Loader> batch) {
+    const CastItem<Loader> &it = batch.item[blockIdx.z];
+    const Loader ld = it.ld;
+    const int64_t rows = it.rows, cols = it.cols;
+    if ((int64_t)blockIdx.x * kTile >= cols || (int64_t)blockIdx.y * kTile >= rows) return;
+    const float *__restrict__ col_scale = it.col_scale;
+    const float *__restrict__ amax = it.amax;
+    const int amax_slots = it.amax_slots, pow2 = batch.pow2;
+    float *__restrict__ amax_out = it.amax_out;
+    const float *__restrict__ scale_in = it.scale_in;
+    float *__restrict__ scale_out = it.scale_out;
+    uint8_t *__restrict__ dst = it.dst, *__restrict__ dst_t = it.dst_t;
+    uint32_t *__restrict__ record = it.record;
+    unsigned long long *__restrict__ counters = it.counters;
     __shared__ uint32_t tile[TRANSPOSED ? kTile * kTPitchWords : 1];
     uint32_t n_sat = 0, n_flush = 0;
 
@@ -373,35 +434,44 @@ cast_kernel(Loader ld, int64_t rows, int64_t cols, const float *__restrict__ col
     }
 }
 
-template <class Loader, int FMT>
-static void launch_cast_l(const Loader &ld, const CastArgs &a, hipStream_t st) {
-    dim3 grid((unsigned)((a.cols + kTile - 1) / kTile), (unsigned)((a.rows + kTile - 1) / kTile));
+template <class Loader>
+static CastItem<Loader> cast_item(const Loader &ld, const CastArgs &a) {
+    return CastItem<Loader>{ld, a.rows, a.cols, a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.scale_out,
+                            a.dst, a.dst_t, a.record, a.counters};
+}
+
+// All items of a batch share the source kind, the format and the presence of every optional part (per-column
+// factor, transposed copy, range record, counters): one kernel instantiation serves them.
+static bool same_cast_form(const CastArgs &a, const CastArgs &b) {
+    return a.kind == b.kind && a.fmt == b.fmt && a.pow2 == b.pow2 && (a.col_scale != nullptr) == (b.col_scale != nullptr) &&
+           (a.dst_t != nullptr) == (b.dst_t != nullptr) && (a.record != nullptr) == (b.record != nullptr) &&
+           (a.counters != nullptr) == (b.counters != nullptr);
+}
+
+template <class Loader, int FMT, class MakeLoader>
+static void launch_cast_l(const CastArgs *list, int n, MakeLoader make, hipStream_t st) {
+    const CastArgs &a = list[0];
+    CastBatch<Loader> batch;
+    int64_t rows = 0, cols = 0;
+    for (int i = 0; i < 3; ++i) {
+        const CastArgs &x = list[i < n ? i : 0];
+        batch.item[i] = cast_item<Loader>(make(x), x);
+        if (i < n) { rows = x.rows > rows ? x.rows : rows; cols = x.cols > cols ? x.cols : cols; }
+    }
+    batch.pow2 = a.pow2;
+    dim3 grid((unsigned)((cols + kTile - 1) / kTile), (unsigned)((rows + kTile - 1) / kTile), (unsigned)n);
     const bool cs = a.col_scale != nullptr, tr = a.dst_t != nullptr;
-#define SSG_CAST(CS, TR)                                                                               \
-    hipLaunchKernelGGL((cast_kernel<Loader, FMT, CS, TR>), grid, dim3(256), 0, st, ld, a.rows, a.cols, \
-                       a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst, a.dst_t)
+#define SSG_CAST(...) hipLaunchKernelGGL((cast_kernel<Loader, FMT, __VA_ARGS__>), grid, dim3(256), 0, st, batch)
     if constexpr (std::is_same<Loader, LoadBf16>::value) {
         if (a.record && !cs) {
-            if (tr)
-                hipLaunchKernelGGL((cast_kernel<Loader, FMT, false, true, true>), grid, dim3(256), 0, st, ld, a.rows, a.cols,
-                                   a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst,
-                                   a.dst_t, a.record);
-            else
-                hipLaunchKernelGGL((cast_kernel<Loader, FMT, false, false, true>), grid, dim3(256), 0, st, ld, a.rows, a.cols,
-                                   a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst,
-                                   a.dst_t, a.record);
+            if (tr) SSG_CAST(false, true, true);
+            else SSG_CAST(false, false, true);
             return;
         }
     }
     if (a.counters && !tr) {
-        if (cs)
-            hipLaunchKernelGGL((cast_kernel<Loader, FMT, true, false, false, true>), grid, dim3(256), 0, st, ld, a.rows, a.cols,
-                               a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst,
-                               a.dst_t, nullptr, a.counters);
-        else
-            hipLaunchKernelGGL((cast_kernel<Loader, FMT, false, false, false, true>), grid, dim3(256), 0, st, ld, a.rows, a.cols,
-                               a.col_scale, a.amax, a.amax_slots, a.amax_out, a.scale_in, a.pow2, a.scale_out, a.dst,
-                               a.dst_t, nullptr, a.counters);
+        if (cs) SSG_CAST(true, false, false, true);
+        else SSG_CAST(false, false, false, true);
         return;
     }
     if (cs && tr) SSG_CAST(true, true);
@@ -412,26 +482,46 @@ static void launch_cast_l(const Loader &ld, const CastArgs &a, hipStream_t st) {
 }
 
 template <int FMT>
-static void launch_cast_f(const CastArgs &a, hipStream_t st) {
-    switch (a.kind) {
-        case SRC_BF16: launch_cast_l<LoadBf16, FMT>(LoadBf16{(const uint16_t *)a.src}, a, st); break;
-        case SRC_F32: launch_cast_l<LoadF32, FMT>(LoadF32{(const float *)a.src}, a, st); break;
+static void launch_cast_f(const CastArgs *list, int n, hipStream_t st) {
+    switch (list[0].kind) {
+        case SRC_BF16:
+            launch_cast_l<LoadBf16, FMT>(list, n, [](const CastArgs &x) { return LoadBf16{(const uint16_t *)x.src}; }, st);
+            break;
+        case SRC_F32:
+            launch_cast_l<LoadF32, FMT>(list, n, [](const CastArgs &x) { return LoadF32{(const float *)x.src}; }, st);
+            break;
         case SRC_SWIGLU:
-            launch_cast_l<LoadSwiglu, FMT>(LoadSwiglu{(const uint16_t *)a.src, (const uint16_t *)a.src2}, a, st);
+            launch_cast_l<LoadSwiglu, FMT>(list, n, [](const CastArgs &x) {
+                return LoadSwiglu{(const uint16_t *)x.src, (const uint16_t *)x.src2}; }, st);
             break;
     }
 }
 
-void launch_cast(const CastArgs &a, hipStream_t st) {
-    if (a.rows == 0 || a.cols == 0) return;
+static double cast_bytes(const CastArgs &a) {
     // algorithmic bytes: the source once (bf16 2, fp32 4, bf16 U and G 4), one code per element (two with a transposed copy)
-    const double per_element = (a.kind == SRC_BF16 ? 2.0 : 4.0) + (a.dst_t ? 2.0 : 1.0);
-    profile_before(a.kind == SRC_SWIGLU ? kTagCastSwiglu : a.col_scale ? kTagCastColscale : kTagCast, st,
-                   per_element * (double)a.rows * (double)a.cols);
-    if (a.fmt == kE4M3) launch_cast_f<kE4M3>(a, st);
-    else launch_cast_f<kE5M2>(a, st);
+    return ((a.kind == SRC_BF16 ? 2.0 : 4.0) + (a.dst_t ? 2.0 : 1.0)) * (double)a.rows * (double)a.cols;
+}
+
+void launch_cast_batch(const CastArgs *list, int n, hipStream_t st) {
+    // items that are empty or of another form than the first go on their own
+    int m = 0;
+    CastArgs same[3];
+    for (int i = 0; i < n; ++i) {
+        if (list[i].rows == 0 || list[i].cols == 0) continue;
+        if (m < 3 && (m == 0 || same_cast_form(same[0], list[i]))) same[m++] = list[i];
+        else launch_cast(list[i], st);
+    }
+    if (m == 0) return;
+    double bytes = 0.0;
+    for (int i = 0; i < m; ++i) bytes += cast_bytes(same[i]);
+    const CastArgs &a = same[0];
+    profile_before(a.kind == SRC_SWIGLU ? kTagCastSwiglu : a.col_scale ? kTagCastColscale : kTagCast, st, bytes);
+    if (a.fmt == kE4M3) launch_cast_f<kE4M3>(same, m, st);
+    else launch_cast_f<kE5M2>(same, m, st);
     profile_after(st);
 }
+
+void launch_cast(const CastArgs &a, hipStream_t st) { launch_cast_batch(&a, 1, st); }
 
 // ------------------------------------------------------------------ per-column amax
 // Grid (cols/512, rows/128).  A wave reads 1 KB of a row per load; a lane keeps 8 running column
