@@ -31,10 +31,12 @@ METRIC = "FP8 Smooth-SwiGLU MLP fwd+bwd TFLOP/s (7B shape), % of FP8 MFMA peak"
 # epilogue 0 = store, 1 = SwiGLU forward, 2 = SwiGLU backward; part 3 = a sum of two products in one launch;
 # layout 0 = both operands K-contiguous, 1 = B K-major, 2 = A and B K-major.  The backward GEMMs run as two grouped
 # launches; the single-launch tags appear only when the grouping is switched off (SSG_GEMM_GROUPING=0).
-TAG_NAMES = {0: "gemm_kernel<0, 0, 0, 0>", 2: "gemm_kernel<1, 0, 0, 0>", 16: "gemm_group_dh_dw3_kernel<2>",
+TAG_NAMES = {0: "gemm_kernel<0, 0, 0, 0>", 2: "gemm_kernel<1, 0, 0, 0>", 18: "gemm_swiglu_col_range_kernel",
+             16: "gemm_group_dh_dw3_kernel<2>",
              17: "gemm_group_dx_dw_kernel", 5: "gemm_kernel<2, 1, 0, 1>", 1: "gemm_kernel<0, 1, 0, 2>",
              11: "gemm_kernel<0, 1, 3, 1>", 9: "gemm_kernel<0, 1, 1, 1>", 10: "gemm_kernel<0, 1, 2, 1>"}
-TAG_ROLES = {0: "y = h^ w3~^T", 2: "U, G + SwiGLU + channel maxima", 16: "dH + SwiGLU backward, then dW3 (one grid)",
+TAG_ROLES = {0: "y = h^ w3~^T", 2: "U, G + SwiGLU + channel maxima",
+             18: "U, G + SwiGLU + channel maxima, with the per-channel range of W3 in the grid's last round", 16: "dH + SwiGLU backward, then dW3 (one grid)",
              17: "dX (both products), then dW1, dW2 (one grid)", 5: "dH + SwiGLU backward", 1: "dW3, dW1, dW2",
              11: "dX, both products in one launch", 9: "dX, first product (to fp32 scratch)",
              10: "dX, second product + scratch"}
@@ -43,6 +45,7 @@ ELEMENTWISE = {40: ("amax_bf16_kernel", "per-tensor range of x, W1, W2, dY"),
                41: ("cast_kernel<LoadBf16, *, false, ...>", "per-tensor cast of x, W1, W2, dY, dU, dG"),
                42: ("cast_kernel<LoadSwiglu, 0, true, ...>", "h^ = cast(s_i h) from bf16 U, G"),
                43: ("cast_kernel<LoadBf16, 0, true, ...>", "w3~ = Q(s^-1 w3)"),
+               47: ("cast_h_w3_kernel", "h^ = cast(s_i h) from bf16 U, G and w3~ = Q(s^-1 w3), one launch"),
                44: ("col_amax_bf16_kernel", "per-channel range of W3"),
                45: ("reset / fill / channel_factors kernels", "bookkeeping")}
 PEAK_HBM_GBS = 8000.0             # MI355X HBM3E (published: 8 TB/s)
@@ -54,7 +57,7 @@ def gemm_flops_by_tag(T, d, f, grouped=True):
     one = 2.0 * T * d * f
     if grouped:
         return {0: (one, 1),          # y = h^ w3~^T
-                2: (2 * one, 1),      # U and G in one launch
+                18: (2 * one, 1),     # U and G in one launch (the range pass over W3 rides in its grid)
                 16: (2 * one, 1),     # dH and dW3
                 17: (4 * one, 1)}     # dX (two products), dW1, dW2
     return {0: (one, 1), 2: (2 * one, 1), 5: (one, 1), 1: (3 * one, 3), 11: (2 * one, 1)}

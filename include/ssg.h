@@ -318,12 +318,13 @@ ssg_status ssg_adam_view_state(int64_t n, int32_t step, const void *state, ssg_a
  * (y: tag 0; a weight gradient: tag 1), 1 = fused SwiGLU forward (U, G, channel maxima: tag 2), 2 = fused SwiGLU
  * backward (dH: tag 5), 3 = fused SwiGLU product + E4M3 cast of the inference form (tag 6); 11 = the input
  * gradient, both products in one launch (9 and 10: its two launches on shapes where that form is not built);
- * 16 = grouped launch {dH, dW3}; 17 = grouped launch {dX, dW1, dW2}; bf16 operands (w3_layer_bf16 = 1): 20 = plain
+ * 16 = grouped launch {dH, dW3}; 17 = grouped launch {dX, dW1, dW2}; 18 = tag 2 with the per-column range pass over
+ * W3 riding in the same grid; bf16 operands (w3_layer_bf16 = 1): 20 = plain
  * store (y, dW3), 21 = dH with the fused SwiGLU backward.
  * Elementwise passes (bytes = algorithmic bytes moved): 40 = per-tensor range, 41 = per-tensor cast, 42 = cast
  * of the SwiGLU product from bf16 U, G with per-channel factors, 43 = cast of W3 with the inverse factors folded
  * in, 44 = per-column range, 45 = small bookkeeping kernels (resets, factors, history update), 46 = bf16 transposes
- * (w3_layer_bf16 = 1).
+ * (w3_layer_bf16 = 1), 47 = the passes of 42 and 43 in one launch.
  * Adam: 32 = range pass, 33 = update pass. */
 ssg_status ssg_profile_enable(int max_records);
 ssg_status ssg_profile_select(int tag);

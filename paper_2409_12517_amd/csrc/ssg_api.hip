@@ -723,10 +723,16 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
         // Section 4.3: the last linear layer on bf16 operands: y = h_b W3^T, no scales
         g2.a_fmt = ssg::kBF16; g2.A = b + L.h_b; g2.B = static_cast<const uint8_t *>(W3); g2.sa = nullptr; g2.sb = nullptr;
     }
+    const bool cached = desc->weights_cached != 0;
+    // the per-channel range of w3 (needed for the range of s^-1 * w3, constant between weight updates) rides in the
+    // gate/up GEMM's grid, where it fills the last, partly occupied round of tiles
+    const bool w3_range_in_gemm = !cached && !bf16_last && gemm_grouping_enabled();
+    if (w3_range_in_gemm) {
+        g.tail_src = W3; g.tail_rows = dm; g.tail_cols = f; g.tail_camax_bits = reinterpret_cast<uint32_t *>(w3_camax);
+    }
     if (!ssg::gemm_args_ok(g) || !ssg::gemm_args_ok(g2)) return fail(SSG_ERR_ARG, "ssg_mlp_fwd: internal GEMM arguments");
     if ((rc = check_entry("ssg_mlp_fwd")) != SSG_OK) return rc;
 
-    const bool cached = desc->weights_cached != 0;
     // zero the running maxima of this call; with cached weights the slots that belong to W1, W2 and
     // W3 (their scales, ranges and W3's per-channel maxima) are left as the earlier call wrote them
     const uint32_t per_call = (1u << S_AMAX_W3S) | (1u << S_HMAX);
@@ -770,10 +776,11 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     if (!delayed) ssg::launch_amax_batch(srcs, counts, slot_ptrs, n_in, st);
     ssg::launch_cast_batch(casts, n_in, st);
     if (!cached) {
-        // per-channel range of w3, needed for the range of s^-1 * w3 (constant between weight updates)
-        if (!bf16_last) ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
+        // per-channel range of w3 as a launch of its own (unless it rides in the GEMM below)
+        if (!bf16_last && !w3_range_in_gemm)
+            ssg::launch_col_amax(W3, nullptr, ssg::SRC_BF16, dm, f, reinterpret_cast<uint32_t *>(w3_camax), st);
         // last layer in bf16: its input gradient contracts over d, so W3 [d,f] is also kept transposed
-        else ssg::launch_transpose_bf16(W3, dm, f, b + L.w3T, st);
+        if (bf16_last) ssg::launch_transpose_bf16(W3, dm, f, b + L.w3T, st);
     }
 
     ssg::launch_gemm(g, st);
@@ -806,14 +813,18 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     hq.src = b + L.U; hq.src2 = b + L.G; hq.kind = ssg::SRC_SWIGLU; hq.rows = T; hq.cols = f; hq.fmt = ssg::kE4M3;
     hq.col_scale = s; hq.dst = b + L.h_q;
     hq.counters = reinterpret_cast<unsigned long long *>(desc->h_counters);
-    ssg::launch_cast(hq, st);
 
-    // a7: w3~ = Q(s^-1 * w3)
+    // a7: w3~ = Q(s^-1 * w3); independent of a6, so the two share a launch
     ssg::CastArgs wq;
     wq.src = W3; wq.kind = ssg::SRC_BF16; wq.rows = dm; wq.cols = f; wq.fmt = ssg::kE4M3; wq.pow2 = pow2;
     wq.col_scale = sinv; wq.amax = sc + S_AMAX_W3S; wq.scale_out = sc + S_SW3;
     wq.dst = b + L.w3_q;
-    ssg::launch_cast(wq, st);
+    if (gemm_grouping_enabled()) {
+        ssg::launch_cast_h_w3(hq, wq, st);
+    } else {
+        ssg::launch_cast(hq, st);
+        ssg::launch_cast(wq, st);
+    }
 
     ssg::launch_gemm(g2, st);
 

@@ -49,6 +49,8 @@ struct CastArgs {
 void launch_cast(const CastArgs &a, hipStream_t st);
 // up to three casts of the same form (source kind, format, optional parts) in one launch; others are launched singly
 void launch_cast_batch(const CastArgs *list, int n, hipStream_t st);
+// the smooth cast of h (from bf16 U, G) and the fold + cast of w3 in one launch (falls back to two for any other pair)
+void launch_cast_h_w3(const CastArgs &h, const CastArgs &w3, hipStream_t st);
 
 // camax_bits[c] = max_r |v[r,c]| as float bits (zeroed by the caller).
 void launch_col_amax(const void *src, const void *src2, SrcKind kind, int64_t rows, int64_t cols,
@@ -120,6 +122,12 @@ struct GemmArgs {
     float *q_scale_out = nullptr, *q_scale_out2 = nullptr;        //                   where the scales used are recorded
     void *keep_u = nullptr, *keep_g = nullptr;                    //                   optional bf16 [M,N]: the rounded dU, dG
                                                                   //                   the codes were cast from (both or neither)
+    // EPI_SWIGLU, optional: an independent per-column range pass over a bf16 matrix [tail_rows, tail_cols] (columns a
+    // multiple of 8) run by extra workgroups at the end of the grid, where they fill the compute units that the last,
+    // partly occupied round of tiles leaves idle; tail_camax_bits [tail_cols] (float bits, zeroed by the caller)
+    const void *tail_src = nullptr;
+    int64_t tail_rows = 0, tail_cols = 0;
+    uint32_t *tail_camax_bits = nullptr;
 };
 // Whether the argument set is one the kernels are built for (part / add / epilogue / layout combinations).
 bool gemm_args_ok(const GemmArgs &a);
@@ -142,7 +150,7 @@ void profile_before(int tag, hipStream_t st, double bytes = 0.0);
 void profile_after(hipStream_t st);
 // tags of the elementwise passes (the GEMM tags are listed with ssg_profile_read)
 constexpr int kTagAmax = 40, kTagCast = 41, kTagCastSwiglu = 42, kTagCastColscale = 43, kTagColAmax = 44, kTagSmall = 45,
-              kTagTranspose = 46;
+              kTagTranspose = 46, kTagCastHW3 = 47;
 
 // ---- delayed scaling: amax history per tensor (ssg_quant.hip) ----------------------
 // State words: tensor k (0..5 = x, w1, w2, dy, du, dg) owns words [32k, 32k+32): [0] the scale the next

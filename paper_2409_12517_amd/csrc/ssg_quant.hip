@@ -7,8 +7,7 @@
 // per column on the float's bit pattern (|x| orders like an unsigned integer).
 #include <type_traits>
 
-typedef short ssg_i16x2 __attribute__((ext_vector_type(2)));
-
+#include "ssg_col_range.h"
 #include "ssg_device.h"
 #include "ssg_internal.h"
 
@@ -130,18 +129,7 @@ __global__ void __launch_bounds__(256) amax_kernel(Loader ld, size_t n8, uint32_
     }
 }
 
-// bf16 source: the range is taken on the raw 16-bit patterns, two per operation.  (|x| pattern) + 0x7f is below
-// 0x8000 for every number and for infinity and at or above it for NaN, so a signed 16-bit maximum ignores NaN.
-typedef unsigned int ssg_u32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ ssg_i16x2 biased_abs_pk(uint32_t w) {
-    return __builtin_bit_cast(ssg_i16x2, (w & 0x7fff7fffu) + 0x007f007fu);
-}
-// the larger of the two biased patterns as the fp32 bit pattern of the same number
-__device__ __forceinline__ uint32_t unbias_max_pk(ssg_i16x2 m) {
-    const uint32_t lo = (uint32_t)(uint16_t)m[0] - 0x7fu, hi = (uint32_t)(uint16_t)m[1] - 0x7fu;
-    return (lo > hi ? lo : hi) << 16;
-}
-
+// bf16 source: the range is taken on the raw 16-bit patterns, two per operation (biased_abs_pk, ssg_col_range.h).
 // A pure streaming read: every workgroup walks contiguous runs of 4 x 256 16-byte pieces (4 independent loads per
 // lane), grid-stride.  Measured on a 90 MB tensor: 13 us (6.9 TB/s) against 27-41 us for the generic kernel above
 // (which widens every element to fp32 and walks 32 KB units); more loads per lane or larger workgroups are slower.
@@ -269,16 +257,15 @@ struct CastBatch {
     CastItem<Loader> item[3];
     int pow2;
 };
+// The work of one workgroup: tile (bx, by) of item `it`.
 template <class Loader, int FMT, bool COLSCALE, bool TRANSPOSED, bool RECORD = false, bool COUNT = false>
-__global__ void __launch_bounds__(256)
-cast_kernel(const CastBatch<Loader> batch) {
-    const CastItem<Loader> &it = batch.item[blockIdx.z];
+__device__ __forceinline__ void cast_block(const CastItem<Loader> &it, const int pow2, const unsigned bx, const unsigned by) {
     const Loader ld = it.ld;
     const int64_t rows = it.rows, cols = it.cols;
-    if ((int64_t)blockIdx.x * kTile >= cols || (int64_t)blockIdx.y * kTile >= rows) return;
+    if ((int64_t)bx * kTile >= cols || (int64_t)by * kTile >= rows) return;
     const float *__restrict__ col_scale = it.col_scale;
     const float *__restrict__ amax = it.amax;
-    const int amax_slots = it.amax_slots, pow2 = batch.pow2;
+    const int amax_slots = it.amax_slots;
     float *__restrict__ amax_out = it.amax_out;
     const float *__restrict__ scale_in = it.scale_in;
     float *__restrict__ scale_out = it.scale_out;
@@ -301,12 +288,12 @@ cast_kernel(const CastBatch<Loader> batch) {
         const float m = __uint_as_float(mbits);
         sigma = scale_from_amax(m, Fp8Traits<FMT>::fmax, pow2);
         tensor_scale = true;
-        if (amax_out && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *amax_out = m;
+        if (amax_out && bx == 0 && by == 0 && threadIdx.x == 0) *amax_out = m;
     }
-    if (scale_out && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *scale_out = sigma;
+    if (scale_out && bx == 0 && by == 0 && threadIdx.x == 0) *scale_out = sigma;
 
-    const int64_t row0 = (int64_t)blockIdx.y * kTile;
-    const int64_t col0 = (int64_t)blockIdx.x * kTile;
+    const int64_t row0 = (int64_t)by * kTile;
+    const int64_t col0 = (int64_t)bx * kTile;
     const int c8 = threadIdx.x & 15;       // which 8-column chunk
     const int r4 = threadIdx.x >> 4;       // which 4-row group (0..15) inside a 64-row half
     const int64_t col = col0 + c8 * 8;
@@ -399,7 +386,7 @@ cast_kernel(const CastBatch<Loader> batch) {
             uint32_t m = wave_seen[0];
 #pragma unroll
             for (int k = 1; k < 4; ++k) m = m > wave_seen[k] ? m : wave_seen[k];
-            if (m) atomicMax(record + ((blockIdx.y * gridDim.x + blockIdx.x) % kAmaxSlots) * kAmaxSlotStride, m);
+            if (m) atomicMax(record + ((by * gridDim.x + bx) % kAmaxSlots) * kAmaxSlotStride, m);
         }
     }
     if (COUNT) {
@@ -432,6 +419,22 @@ cast_kernel(const CastBatch<Loader> batch) {
             }
         }
     }
+}
+
+template <class Loader, int FMT, bool COLSCALE, bool TRANSPOSED, bool RECORD = false, bool COUNT = false>
+__global__ void __launch_bounds__(256)
+cast_kernel(const CastBatch<Loader> batch) {
+    cast_block<Loader, FMT, COLSCALE, TRANSPOSED, RECORD, COUNT>(batch.item[blockIdx.z], batch.pow2, blockIdx.x, blockIdx.y);
+}
+
+// The two casts between the gate/up GEMM and the last GEMM of the Smooth-SwiGLU forward in one launch: h^ =
+// cast(s_i h) from bf16 U, G (Eq. 2; blockIdx.z = 0) and w3~ = Q(s^-1 w3) (the display after Eq. 2; blockIdx.z = 1).
+// Both depend only on the channel factors, neither on the other.
+template <bool COUNT>
+__global__ void __launch_bounds__(256)
+cast_h_w3_kernel(const CastItem<LoadSwiglu> h, const CastItem<LoadBf16> w3, const int pow2) {
+    if (blockIdx.z == 0) cast_block<LoadSwiglu, kE4M3, true, false, false, COUNT>(h, pow2, blockIdx.x, blockIdx.y);
+    else cast_block<LoadBf16, kE4M3, true, false, false, false>(w3, pow2, blockIdx.x, blockIdx.y);
 }
 
 template <class Loader>
@@ -523,12 +526,33 @@ void launch_cast_batch(const CastArgs *list, int n, hipStream_t st) {
 
 void launch_cast(const CastArgs &a, hipStream_t st) { launch_cast_batch(&a, 1, st); }
 
+bool cast_h_w3_ok(const CastArgs &h, const CastArgs &w3) {
+    return h.kind == SRC_SWIGLU && w3.kind == SRC_BF16 && h.fmt == kE4M3 && w3.fmt == kE4M3 && h.col_scale && w3.col_scale &&
+           !h.dst_t && !w3.dst_t && !h.record && !w3.record && !w3.counters && h.rows > 0 && w3.rows > 0 && h.cols > 0 &&
+           w3.cols > 0;
+}
+
+void launch_cast_h_w3(const CastArgs &h, const CastArgs &w3, hipStream_t st) {
+    if (!cast_h_w3_ok(h, w3)) {             // not the pair this launch is built for: one after the other
+        launch_cast(h, st);
+        launch_cast(w3, st);
+        return;
+    }
+    const CastItem<LoadSwiglu> hi = cast_item<LoadSwiglu>(LoadSwiglu{(const uint16_t *)h.src, (const uint16_t *)h.src2}, h);
+    const CastItem<LoadBf16> wi = cast_item<LoadBf16>(LoadBf16{(const uint16_t *)w3.src}, w3);
+    const int64_t rows = h.rows > w3.rows ? h.rows : w3.rows, cols = h.cols > w3.cols ? h.cols : w3.cols;
+    dim3 grid((unsigned)((cols + kTile - 1) / kTile), (unsigned)((rows + kTile - 1) / kTile), 2u);
+    profile_before(kTagCastHW3, st, cast_bytes(h) + cast_bytes(w3));
+    if (h.counters) hipLaunchKernelGGL(cast_h_w3_kernel<true>, grid, dim3(256), 0, st, hi, wi, w3.pow2);
+    else hipLaunchKernelGGL(cast_h_w3_kernel<false>, grid, dim3(256), 0, st, hi, wi, w3.pow2);
+    profile_after(st);
+}
+
 // ------------------------------------------------------------------ per-column amax
 // Grid (cols/512, rows/128).  A wave reads 1 KB of a row per load; a lane keeps 8 running column
 // maxima over its wave's share of the slab's rows; the four waves of a workgroup meet in LDS and
 // one atomic per column goes to memory.
 constexpr int kSlabRows = 128;
-constexpr int kColTile = 512;     // one wave reads 1 KB of a row per load: 64 lanes x 8 bf16
 
 template <class Loader>
 __global__ void __launch_bounds__(256)
@@ -575,49 +599,11 @@ col_amax_kernel(Loader ld, int64_t rows, int64_t cols, uint32_t *__restrict__ ca
     }
 }
 
-// bf16 source on the raw patterns (see amax_bf16_kernel): a lane owns 8 columns (one 16-byte piece per row), a wave
-// 512 columns, and walks down its share of a 256-row slab with 8 row loads in flight; the four waves of a
-// workgroup take every fourth row.  The running maxima stay packed (two columns per register).
-constexpr int kColSlabBf16 = 256;
+// bf16 source: the workgroup's work is col_range_bf16_block (ssg_col_range.h), shared with the gate/up GEMM's grid.
 __global__ void __launch_bounds__(256)
 col_amax_bf16_kernel(const uint16_t *__restrict__ src, int64_t rows, int64_t cols, uint32_t *__restrict__ camax_bits) {
     __shared__ uint32_t cmax[kColTile];
-    cmax[threadIdx.x] = 0;
-    cmax[threadIdx.x + 256] = 0;
-    __syncthreads();
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int64_t col = (int64_t)blockIdx.x * kColTile + lane * 8;
-    const int64_t row0 = (int64_t)blockIdx.y * kColSlabBf16;
-    const int64_t row1 = row0 + kColSlabBf16 < rows ? row0 + kColSlabBf16 : rows;
-    if (col < cols) {
-        ssg_i16x2 m[4] = {{0x7f, 0x7f}, {0x7f, 0x7f}, {0x7f, 0x7f}, {0x7f, 0x7f}};
-        for (int64_t r = row0 + w; r < row1; r += 32) {
-            ssg_u32x4 v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int64_t rr = r + 4 * u;
-                v[u] = rr < row1 ? __builtin_nontemporal_load(reinterpret_cast<const ssg_u32x4 *>(src + (size_t)rr * (size_t)cols + (size_t)col))
-                                 : ssg_u32x4{0u, 0u, 0u, 0u};
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-#pragma unroll
-                for (int k = 0; k < 4; ++k) m[k] = __builtin_elementwise_max(m[k], biased_abs_pk(v[u][k]));
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t lo = ((uint32_t)(uint16_t)m[k][0] - 0x7fu) << 16, hi = ((uint32_t)(uint16_t)m[k][1] - 0x7fu) << 16;
-            if (lo) atomicMax(&cmax[lane * 8 + 2 * k], lo);
-            if (hi) atomicMax(&cmax[lane * 8 + 2 * k + 1], hi);
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int t = threadIdx.x + 256 * h;
-        const int64_t c = (int64_t)blockIdx.x * kColTile + t;
-        if (c < cols && cmax[t]) atomicMax(&camax_bits[c], cmax[t]);
-    }
+    col_range_bf16_block<8>(src, rows, cols, camax_bits, (int)blockIdx.x, (int)blockIdx.y, cmax);
 }
 
 void launch_col_amax(const void *src, const void *src2, SrcKind kind, int64_t rows, int64_t cols,
@@ -627,7 +613,7 @@ void launch_col_amax(const void *src, const void *src2, SrcKind kind, int64_t ro
     profile_before(kTagColAmax, st, (double)rows * (double)cols * (kind == SRC_F32 ? 4.0 : kind == SRC_SWIGLU ? 4.0 : 2.0));
     switch (kind) {
         case SRC_BF16:
-            grid.y = (unsigned)((rows + kColSlabBf16 - 1) / kColSlabBf16);
+            grid.y = (unsigned)col_range_blocks_y(rows);
             hipLaunchKernelGGL(col_amax_bf16_kernel, grid, dim3(256), 0, st, (const uint16_t *)src, rows, cols, camax_bits);
             break;
         case SRC_F32:
