@@ -36,8 +36,8 @@ TAG_NAMES = {0: "gemm_kernel<0, 0, 0, 0>", 2: "gemm_kernel<1, 0, 0, 0>", 18: "ge
              17: "gemm_group_dx_dw_kernel", 5: "gemm_kernel<2, 1, 0, 1>", 1: "gemm_kernel<0, 1, 0, 2>",
              11: "gemm_kernel<0, 1, 3, 1>", 9: "gemm_kernel<0, 1, 1, 1>", 10: "gemm_kernel<0, 1, 2, 1>"}
 TAG_ROLES = {0: "y = h^ w3~^T", 2: "U, G + SwiGLU + channel maxima",
-             18: "U, G + SwiGLU + channel maxima, with the per-channel range of W3 in the grid's last round", 16: "dH + SwiGLU backward, then dW3 (one grid)",
-             17: "dX (both products), then dW1, dW2 (one grid)", 5: "dH + SwiGLU backward", 1: "dW3, dW1, dW2",
+             18: "U, G + SwiGLU + channel maxima, with the per-channel range of W3 in the grid's last round", 16: "dH + SwiGLU backward, then the first part of dW3 (one grid)",
+             17: "dX (both products), then dW1, dW2 and the rest of dW3 (one grid)", 5: "dH + SwiGLU backward", 1: "dW3, dW1, dW2",
              11: "dX, both products in one launch", 9: "dX, first product (to fp32 scratch)",
              10: "dX, second product + scratch"}
 # elementwise passes: tag -> (kernel family as rocprofv3 prints it, role)
@@ -53,7 +53,9 @@ TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "bench_7b_hbm_traffic.txt")
 
 
 def gemm_flops_by_tag(T, d, f, grouped=True):
-    """Algorithmic flops per step and launches per step of each GEMM launch tag."""
+    """Algorithmic flops per step and launches per step of each GEMM launch tag, every GEMM whole in its launch.  (In
+    the grouped form the library moves part of dW3 from tag 16 to tag 17; the run itself prices each launch by the
+    flop count the library reports for it.)"""
     one = 2.0 * T * d * f
     if grouped:
         return {0: (one, 1),          # y = h^ w3~^T
@@ -236,7 +238,9 @@ def summarize_profiles(src: str) -> int:
     legend = ("gemm_kernel<epilogue, A format, part, layout>: epilogue 0 = store, 1 = SwiGLU forward (U, G, channel maxima), 2 = SwiGLU "
               "backward, 3 = SwiGLU + E4M3 cast (inference form), 4 = SwiGLU backward + E5M2 cast (delayed scaling); A format 0 = E4M3, "
               "1 = E5M2; part 3 = a sum of two products in one launch; layout 0 = both operands K-contiguous, 1 = B K-major, 2 = A and B "
-              "K-major.  gemm_group_dh_dw3_kernel = dH then dW3 in one grid; gemm_group_dx_dw_kernel = dX then dW1, dW2 in one grid.")
+              "K-major.  gemm_group_dh_dw3_kernel = dH then the first part of dW3 in one grid; gemm_group_dx_dw_kernel = dX, then dW1, dW2 and "
+              "the rest of dW3 in one grid; gemm_swiglu_col_range_kernel = gemm_kernel<1, 0, 0, 0> with the per-channel range pass over W3 "
+              "as extra workgroups of the same grid; cast_h_w3_kernel = the casts of h and w3 in one launch.")
     # 1. per-kernel durations
     stats = find("stats", "kernel_stats.csv")
     if stats:
@@ -296,10 +300,24 @@ def summarize_profiles(src: str) -> int:
                 a = sum(fe.get(k, [0])) / max(1, len(fe.get(k, [0]))) * ff * 1024 / 1e6
                 b = sum(wr.get(k, [0])) / max(1, len(wr.get(k, [0]))) * fw * 1024 / 1e6
                 fo.write("%s\t%d\t%.1f\t%.1f\t%.1f\n" % (short(k), len(fe.get(k, [])), a, b, a + b))
-            fo.write("\nalgorithmic bytes for comparison (MB): gemm_group_dx_dw_kernel reads dU^, dG^ (2 x 45.1), w1^, w2^ (2 x 45.1), x^ (16.8) "
-                     "and writes dX bf16 (33.6) + dW1, dW2 fp32 (2 x 180.4) = 591.6; gemm_group_dh_dw3_kernel reads dY^ (16.8), w3~ (45.1), "
-                     "h^ (45.1), bf16 U, G (180.4) and writes bf16 dU, dG (180.4) + dW3 fp32 (180.4) = 648.2; gemm_kernel<1, 0, 0, 0> reads "
-                     "x^, w1^, w2^ (107.0) and writes bf16 U, G (180.4) = 287.4; adam_update_kernel at 45.09 M elements: 18 B/element = 811.6.\n")
+            # the library moves some of dW3's tiles from the first grouped launch to the second: the share, from the flop
+            # counts the bench line of the stats run reports per launch
+            moved = None
+            log = find("stats", "bench.json") or os.path.join(src, "stats.json")
+            if os.path.exists(log):
+                lines = [l for l in open(log) if l.startswith('{"metric"')]
+                k17 = json.loads(lines[-1])["roofline"]["kernels"].get(TAG_NAMES[17]) if lines else None
+                if k17 and "flops_per_launch" in k17:
+                    moved = k17["flops_per_launch"] / (2.0 * 4096 * 4096 * 11008) - 4.0
+            fo.write("\nalgorithmic bytes for comparison (MB), every GEMM whole in its launch: gemm_group_dx_dw_kernel reads dU^, dG^ "
+                     "(2 x 45.1), w1^, w2^ (2 x 45.1), x^ (16.8) and writes dX bf16 (33.6) + dW1, dW2 fp32 (2 x 180.4) = 591.6; "
+                     "gemm_group_dh_dw3_kernel reads dY^ (16.8), w3~ (45.1), h^ (45.1), bf16 U, G (180.4) and writes bf16 dU, dG (180.4) + "
+                     "dW3 fp32 (180.4) = 648.2; the gate/up GEMM (gemm_swiglu_col_range_kernel) reads x^, w1^, w2^ (107.0) and W3 (90.2, the "
+                     "range pass in its grid) and writes bf16 U, G (180.4) = 377.6; adam_update_kernel at 45.09 M elements: 18 B/element = 811.6.\n")
+            if moved is not None:
+                fo.write("The library runs %.1f %% of dW3's tiles in gemm_group_dx_dw_kernel (by the flop counts it reports per launch): "
+                         "that share of dW3's 180.4 MB output, and h^, dY^ reads for those tiles, moves from the first launch to the second: "
+                         "about %.1f MB written there instead of here.\n" % (100 * moved, 180.4 * moved))
     # 3. MFMA / LDS counters of the GEMMs
     mf_p = find("mfma", "counter_collection.csv")
     if mf_p:
@@ -411,8 +429,12 @@ def main() -> int:
     # dominant kernel = the GEMM launch with the largest share of the step
     DOMINANT_TAG = max(gemm_tags, key=lambda tg: sum(m for m, _ in per_tag[tg]))
 
+    # flops and launches per step of every GEMM tag, as the library reports them for each launch (one weight gradient
+    # may be shared out between the two grouped launches of the backward); they must add up to 18 T d f
+    fl = {tg: (sum(nb for _, nb in per_tag[tg]) / bsteps, len(per_tag[tg]) // bsteps) for tg in gemm_tags}
+    assert abs(sum(v[0] for v in fl.values()) / (18.0 * T * d * f) - 1.0) < 1e-9, fl
+    assert grouped or fl == gemm_flops_by_tag(T, d, f, False), fl
     # the timed region: exactly K steps; only the launches of the dominant kernel are bracketed by HIP events
-    fl = gemm_flops_by_tag(T, d, f, grouped)
     dom_launches = fl[DOMINANT_TAG][1]
     ssg.ssg_profile_select(DOMINANT_TAG)
     ssg.ssg_profile_enable(dom_launches * args.steps)
@@ -545,7 +567,7 @@ def main() -> int:
         flops_per_launch = fl[tg][0] / fl[tg][1]
         avg = sum(v) / len(v)
         kernels[TAG_NAMES.get(tg, str(tg))] = {
-            "role": TAG_ROLES.get(tg, ""), "launches_per_step": fl[tg][1], "avg_ms": avg,
+            "role": TAG_ROLES.get(tg, ""), "launches_per_step": fl[tg][1], "avg_ms": avg, "flops_per_launch": flops_per_launch,
             "tflops": flops_per_launch / (avg * 1e-3) / 1e12}
     elementwise = {}
     for tg, (kname, role) in ELEMENTWISE.items():

@@ -34,6 +34,30 @@ bool gemm_grouping_enabled() {
     return on;
 }
 
+// Split of dW3 between the two grouped launches of the backward (see gemm_group_split_sets), remembered for the last
+// few problem shapes: the replay costs a few milliseconds of host time.
+int dw3_split_sets(const ssg::GemmArgs &dh, const ssg::GemmArgs &dw3, const ssg::GemmArgs *const *second) {
+    struct Entry { int64_t M, N, K; int epilogue, c_f32, device, split; };
+    static std::mutex mu;
+    static Entry cache[8];
+    static int used = 0, next = 0;
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return ssg::gemm_tile_sets(dw3);
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < used; ++i) {
+        const Entry &e = cache[i];
+        if (e.M == dh.M && e.N == dh.N && e.K == dh.K && e.epilogue == dh.epilogue && e.c_f32 == dw3.c_f32 && e.device == device)
+            return e.split;
+    }
+    int units = 0;
+    if (hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) units = 0;
+    const int split = ssg::gemm_group_split_sets(dh, dw3, second, 3, units);
+    cache[next] = Entry{dh.M, dh.N, dh.K, dh.epilogue, dw3.c_f32, device, split};
+    next = (next + 1) % 8;
+    used = used < 8 ? used + 1 : 8;
+    return split;
+}
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool extent_ok(int64_t v) { return v > 0 && (v % 16) == 0; }
 constexpr int64_t kMaxElems = (int64_t)1 << 32;   // kernels address operand tiles with 32-bit byte offsets
@@ -934,10 +958,14 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     // Grouped launches: {dH, dW3} (both read dY^; dW3 does not wait for dU, dG) and {dX, dW1, dW2} share one grid
     // each, so that a partly filled last round of workgroups is paid once per group and the epilogue traffic of one
     // GEMM runs under the main loops of the others
-    const ssg::GemmArgs *group_a[2] = {&g, &g3}, *group_b[3] = {&g4a, &g5a, &g5b};
+    const ssg::GemmArgs *group_a[2] = {&g, &g3}, *group_b[4] = {&g4a, &g5a, &g5b, &g3};
     const bool grouped_b = gemm_grouping_enabled() && dx_one && ssg::gemm_group_ok(group_b, 3);
-    const bool grouped = grouped_b && ssg::gemm_group_ok(group_a, 2);
+    const bool grouped = grouped_b && ssg::gemm_group_ok(group_a, 2) && ssg::gemm_group_ok(group_b, 4);
     if ((rc = check_entry("ssg_mlp_bwd")) != SSG_OK) return rc;
+    // dW3 depends only on dY^ and h^, so its tiles may run in either grouped launch: the first takes as many sets of
+    // them as fill its last round, the second the rest
+    const int dw3_sets = ssg::gemm_tile_sets(g3);
+    const int dw3_split = grouped ? dw3_split_sets(g, g3, group_b) : dw3_sets;
 
     ssg::launch_fill_u32(wscb, (Wl.partials - Wl.scalars) / 4 + 3 * ssg::kAmaxSlotWords, 0u, st);
 
@@ -957,7 +985,7 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     if (!bf16_last) ssg::launch_cast(c, st);
     c.record = nullptr;
 
-    if (grouped) ssg::launch_gemm_group(group_a, 2, st);
+    if (grouped) ssg::launch_gemm_group(group_a, 2, dw3_split, st);
     else ssg::launch_gemm(g, st);
 
     // a11: two tensors, two E5M2 scales (their ranges came out of the epilogue above either way), one launch
@@ -974,10 +1002,11 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
         ssg::launch_cast_batch(gc, 2, st);
     }
     if (grouped) {
-        ssg::launch_gemm_group(group_b, 3, st);
+        if (dw3_split < dw3_sets) ssg::launch_gemm_group(group_b, 4, dw3_split, st);
+        else ssg::launch_gemm_group(group_b, 3, -1, st);
     } else if (grouped_b) {
         ssg::launch_gemm(g3, st);
-        ssg::launch_gemm_group(group_b, 3, st);
+        ssg::launch_gemm_group(group_b, 3, -1, st);
     } else {
         ssg::launch_gemm(g3, st);
         ssg::launch_gemm(g4a, st);

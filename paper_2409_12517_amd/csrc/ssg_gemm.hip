@@ -81,7 +81,7 @@ bool launch_gemm(const GemmArgs &a, hipStream_t st) {
     if (a.part != 0 || a.epilogue == EPI_SWIGLU_BWD || a.epilogue == EPI_SWIGLU_BWD_Q) return launch_gemm_bwd(a, st);
     const GemmParams p = make_gemm_params(a);
     const unsigned blocks = (unsigned)p.tiles_m * (unsigned)p.tiles_n;
-    profile_before(gemm_profile_tag(a), st);
+    profile_before(gemm_profile_tag(a), st, gemm_flops(a));
     switch (a.epilogue) {
         case EPI_STORE:
             if (a.a_fmt == kBF16) hipLaunchKernelGGL((gemm_kernel<EPI_STORE, kBF16, 0, 0>), dim3(blocks), dim3(kThreads), 0, st, p);

@@ -731,6 +731,13 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(GemmParams p) {
     gemm_tile<EPI, AFMT, PART, LAY>(p, (int)blockIdx.x, smem);
 }
 
+// Host side: algorithmic flops of the whole contraction (both weight matrices of the SwiGLU forms, both products
+// of the one-launch sum)
+inline double gemm_flops(const GemmArgs &a) {
+    const bool dual = a.epilogue == EPI_SWIGLU || a.epilogue == EPI_SWIGLU_Q;
+    return 2.0 * (double)a.M * (double)a.N * (double)a.K * (dual ? 2.0 : 1.0) * (a.part == 3 ? 2.0 : 1.0);
+}
+
 // Host side: the kernel's parameter block from the launch interface's argument set.
 inline GemmParams make_gemm_params(const GemmArgs &a) {
     GemmParams p;

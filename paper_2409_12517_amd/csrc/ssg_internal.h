@@ -138,14 +138,21 @@ bool gemm_sum_in_one_launch_ok(int64_t N, int64_t K);           // shapes for wh
 int gemm_profile_tag(const GemmArgs &a);
 // Several independent GEMMs in one grid, the workgroups of one following those of the other.  Built groups:
 //   { dH (EPI_SWIGLU_BWD or _Q), weight gradient (EPI_STORE, layout 2, A E5M2) }
-//   { input gradient as one launch (part = 3), weight gradient, weight gradient }
+//   { input gradient as one launch (part = 3), one to three weight gradients }
 // gemm_group_ok tells whether `list` is one of them with every member valid; launch_gemm_group returns false
 // (nothing launched) otherwise.  Timing tags: 16 and 17.
+// split_sets >= 0 splits the LAST member (workgroups come in sets of 8 tiles, gemm_tile_sets of them per GEMM): the
+// two-member group runs its sets [0, split_sets), the other group the rest, so that one weight gradient can be
+// shared out between the two launches; split_sets < 0: every member whole.
+// gemm_group_split_sets picks that split for {dh, dw_split} followed by {second..., rest of dw_split} on `units`
+// compute units, from a replay of the in-order dispatch with per-tile times estimated from K steps and epilogues.
 bool gemm_group_ok(const GemmArgs *const *list, int n);
-bool launch_gemm_group(const GemmArgs *const *list, int n, hipStream_t st);
+bool launch_gemm_group(const GemmArgs *const *list, int n, int split_sets, hipStream_t st);
+int gemm_tile_sets(const GemmArgs &a);
+int gemm_group_split_sets(const GemmArgs &dh, const GemmArgs &dw_split, const GemmArgs *const *second, int n_second, int units);
 
 // Benchmark hook: called by the launchers before and after a kernel launch (no-ops unless enabled).  `bytes`: the
-// algorithmic bytes the launch moves (elementwise passes), 0 where the caller prices the launch itself (GEMMs).
+// algorithmic bytes the launch moves (elementwise passes) or its algorithmic flops (GEMMs).
 void profile_before(int tag, hipStream_t st, double bytes = 0.0);
 void profile_after(hipStream_t st);
 // tags of the elementwise passes (the GEMM tags are listed with ssg_profile_read)
