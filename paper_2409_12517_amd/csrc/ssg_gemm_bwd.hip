@@ -85,11 +85,14 @@ bool gemm_group_ok(const GemmArgs *const *list, int n) {
 // from the first launch to the second (or back) shifts work between the two launches' last rounds.
 static double tile_cost(const GemmArgs &a) {
     const GemmParams p = make_gemm_params(a);
+    // microseconds, from per-workgroup time stamps at the Llama2-7B shape with all compute units busy: 1.33 per K
+    // step (1.45 in the long tiles of the one-launch sum, which all run at once), 2.5 before the first step, and the
+    // epilogue: 33 with the SwiGLU derivative (42 when it also casts), 10 for an fp32 store, 6 for bf16
     const double ksteps = (double)((p.K + BK - 1) / BK) * (a.part == 3 ? 2.0 : 1.0);
-    double epilogue = a.c_f32 ? 10.0 : 6.0;                       // microseconds at the Llama2-7B shape, measured
-    if (a.epilogue == EPI_SWIGLU_BWD) epilogue = 30.0;
-    if (a.epilogue == EPI_SWIGLU_BWD_Q) epilogue = 39.0;
-    return 2.5 + 1.3 * ksteps + epilogue;
+    double epilogue = a.c_f32 ? 10.0 : 6.0;
+    if (a.epilogue == EPI_SWIGLU_BWD) epilogue = 33.0;
+    if (a.epilogue == EPI_SWIGLU_BWD_Q) epilogue = 42.0;
+    return 2.5 + (a.part == 3 ? 1.45 : 1.33) * ksteps + epilogue;
 }
 
 static double replay_dispatch(const double *cost, const int *tiles, int n, int units, std::vector<double> &free_at) {
