@@ -591,6 +591,9 @@ def main() -> int:
                 "avg_launch_ms": dom_avg, "flops_per_launch": dom_flops, "all_gemm_ms_per_step": gemm_ms,
                 "non_gemm_ms_per_step": ms_per_step - gemm_ms, "elementwise_ms_per_step_bracketed": ew_ms,
                 "kernels": kernels, "elementwise": elementwise}
+    # how the library shares dW3 between its two grouped backward launches on this GPU (sets of 8 tiles)
+    first_sets, total_sets = ssg.ssg_mlp_bwd_plan(desc, torch.cuda.get_device_properties(0).multi_processor_count)
+    roofline["backward_plan"] = {"dw3_sets_in_first_launch": first_sets, "dw3_sets": total_sets}
 
     out = {
         "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,

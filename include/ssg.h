@@ -221,6 +221,15 @@ typedef struct {
                                                             desc.keep_bf16_grads = 1 */
     const void *dyT;                                     /* w3_layer_bf16 = 1 only (else NULL): bf16 dY transposed [d,T] */
 } ssg_mlp_workspace_view;
+/* How ssg_mlp_bwd shares the weight gradient of the last layer (dW3, derived from the display after Eq. 2) between
+ * its two grouped GEMM launches on a GPU with `compute_units` compute units: workgroups come in sets of 8 output
+ * tiles; *dw3_sets_total receives the number of sets of dW3, *dw3_sets_first how many of them run in the first
+ * launch (beside dH), the rest running in the second (beside dX, dW1, dW2).  The choice minimises the predicted
+ * time of the two launches; it changes no result.  Host pointers; nothing is launched and no GPU is needed (the
+ * call ssg_mlp_bwd makes uses the compute unit count of the current device).  *dw3_sets_first = *dw3_sets_total
+ * where the grouped launches are not used (w3_layer_bf16 = 1, shapes whose input gradient takes two launches). */
+ssg_status ssg_mlp_bwd_plan(const ssg_mlp_desc *desc, int32_t compute_units, int32_t *dw3_sets_first,
+                            int32_t *dw3_sets_total);
 ssg_status ssg_mlp_view_saved(const ssg_mlp_desc *desc, const void *saved, ssg_mlp_saved_view *out);
 ssg_status ssg_mlp_view_workspace(const ssg_mlp_desc *desc, const void *workspace, ssg_mlp_workspace_view *out);
 

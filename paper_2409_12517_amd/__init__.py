@@ -32,7 +32,7 @@ SSG_ROUND_EXACT_DIV, SSG_ROUND_POW2 = 0, 1
 EXPORTS = [
     "ssg_last_error", "ssg_version", "ssg_amax", "ssg_quantize", "ssg_gemm_fp8", "ssg_gemm_fp8_layout", "ssg_swiglu",
     "ssg_smooth_swiglu_quantize", "ssg_fold_w3", "ssg_mlp_saved_bytes", "ssg_mlp_workspace_bytes",
-    "ssg_mlp_fwd", "ssg_mlp_bwd", "ssg_mlp_view_saved", "ssg_mlp_view_workspace",
+    "ssg_mlp_fwd", "ssg_mlp_bwd", "ssg_mlp_bwd_plan", "ssg_mlp_view_saved", "ssg_mlp_view_workspace",
     "ssg_mlp_scaling_state_bytes", "ssg_mlp_scaling_init",
     "ssg_infer_prepared_bytes", "ssg_infer_workspace_bytes", "ssg_infer_prepare", "ssg_infer_fwd", "ssg_infer_view",
     "ssg_infer_noalloc_max_bytes", "ssg_infer_fwd_noalloc",
@@ -92,6 +92,7 @@ _lib.ssg_mlp_workspace_bytes.argtypes = [POINTER(ssg_mlp_desc)]
 _lib.ssg_mlp_workspace_bytes.restype = c_size_t
 _lib.ssg_mlp_fwd.argtypes = [POINTER(ssg_mlp_desc)] + [c_void_p] * 6 + [c_size_t, c_void_p]
 _lib.ssg_mlp_bwd.argtypes = [POINTER(ssg_mlp_desc), c_void_p, c_void_p, c_size_t] + [c_void_p] * 5 + [c_size_t, c_void_p]
+_lib.ssg_mlp_bwd_plan.argtypes = [POINTER(ssg_mlp_desc), ctypes.c_int32, POINTER(ctypes.c_int32), POINTER(ctypes.c_int32)]
 _lib.ssg_mlp_view_saved.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_saved_view)]
 _lib.ssg_mlp_view_workspace.argtypes = [POINTER(ssg_mlp_desc), c_void_p, POINTER(ssg_mlp_workspace_view)]
 _lib.ssg_profile_enable.argtypes = [c_int]
@@ -227,6 +228,13 @@ def ssg_mlp_fwd(desc, x, W1, W2, W3, y, saved, stream=None, saved_bytes=None):
 def ssg_mlp_bwd(desc, dy, saved, dx, dW1, dW2, dW3, workspace, stream=None, saved_bytes=None, workspace_bytes=None):
     _check(_lib.ssg_mlp_bwd(ctypes.byref(desc), _ptr(dy), _ptr(saved), _nbytes(saved, saved_bytes), _ptr(dx), _ptr(dW1),
                             _ptr(dW2), _ptr(dW3), _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream)))
+
+
+def ssg_mlp_bwd_plan(desc, compute_units: int):
+    """(sets of dW3 run in the first grouped launch, sets of dW3 in all)"""
+    first, total = ctypes.c_int32(), ctypes.c_int32()
+    _check(_lib.ssg_mlp_bwd_plan(ctypes.byref(desc), int(compute_units), ctypes.byref(first), ctypes.byref(total)))
+    return first.value, total.value
 
 
 def ssg_mlp_view_saved(desc, saved) -> ssg_mlp_saved_view:

@@ -34,6 +34,33 @@ bool gemm_grouping_enabled() {
     return on;
 }
 
+// Shapes, formats and layouts of the five GEMM launches of the backward pass (a10, a12, a13, a14): everything that
+// decides how many tiles they have and what a tile costs.  Operand and result pointers are filled in by ssg_mlp_bwd.
+struct BackwardGemms { ssg::GemmArgs dh, dw3, dx, dw1, dw2; };
+void backward_gemm_shapes(const ssg_mlp_desc &desc, BackwardGemms &b) {
+    const int64_t T = desc.T, dm = desc.d, f = desc.f;
+    const int dw_f32 = desc.dw_dtype == SSG_F32;
+    // a10: dH = s_i * dY^ w3~ / (sdy sw3), then through the SwiGLU product; B = w3~ as stored, [d,f] = [K,N]
+    b.dh.epilogue = desc.scale_mode == SSG_SCALE_DELAYED ? ssg::EPI_SWIGLU_BWD_Q : ssg::EPI_SWIGLU_BWD;
+    b.dh.a_fmt = ssg::kE5M2; b.dh.M = T; b.dh.N = f; b.dh.K = dm; b.dh.layout = 1;
+    // a12: dW3[j,i] = sinv_i * sum_t dY^[t,j] h^[t,i] / sdy; dY^ [T,d] = [K,M], h^ [T,f] = [K,N]
+    b.dw3.epilogue = ssg::EPI_STORE; b.dw3.a_fmt = ssg::kE5M2; b.dw3.M = dm; b.dw3.N = f; b.dw3.K = T; b.dw3.layout = 2;
+    b.dw3.c_f32 = dw_f32;
+    // a13: dX = dU^ w1^ / (sdu sw1) + dG^ w2^ / (sdg sw2); w1^ [f,d] = [K,N]
+    b.dx.epilogue = ssg::EPI_STORE; b.dx.a_fmt = ssg::kE5M2; b.dx.M = T; b.dx.N = dm; b.dx.K = f; b.dx.layout = 1;
+    b.dx.part = ssg::gemm_sum_in_one_launch_ok(dm, f) ? 3 : 1;
+    b.dx.c_f32 = b.dx.part == 3 ? desc.y_dtype == SSG_F32 : 1;
+    // a14: dW1 = dU^T x^ / (sdu sx), dW2 = dG^T x^ / (sdg sx); dU^ [T,f] = [K,M], x^ [T,d] = [K,N]
+    b.dw1.epilogue = ssg::EPI_STORE; b.dw1.a_fmt = ssg::kE5M2; b.dw1.M = f; b.dw1.N = dm; b.dw1.K = T; b.dw1.layout = 2;
+    b.dw1.c_f32 = dw_f32;
+    b.dw2 = b.dw1;
+    if (desc.w3_layer_bf16) {
+        // Section 4.3: dH = dY W3 and dW3 = dY^T h_b on bf16 operands, every operand with its contraction index contiguous
+        b.dh.epilogue = ssg::EPI_SWIGLU_BWD; b.dh.a_fmt = ssg::kBF16; b.dh.layout = 0;
+        b.dw3.a_fmt = ssg::kBF16; b.dw3.layout = 0;
+    }
+}
+
 // Split of dW3 between the two grouped launches of the backward (see gemm_group_split_sets), remembered for the last
 // few problem shapes: the replay costs a few milliseconds of host time.
 int dw3_split_sets(const ssg::GemmArgs &dh, const ssg::GemmArgs &dw3, const ssg::GemmArgs *const *second) {
@@ -867,6 +894,26 @@ ssg_status ssg_mlp_fwd(const ssg_mlp_desc *desc, const void *x, const void *W1, 
     return check_launch("ssg_mlp_fwd");
 }
 
+ssg_status ssg_mlp_bwd_plan(const ssg_mlp_desc *desc, int32_t compute_units, int32_t *dw3_sets_first,
+                            int32_t *dw3_sets_total) {
+    ssg_status rc = check_desc(desc, "ssg_mlp_bwd_plan");
+    if (rc != SSG_OK) return rc;
+    if (!dw3_sets_first || !dw3_sets_total) return fail(SSG_ERR_ARG, "ssg_mlp_bwd_plan: output pointers must not be NULL");
+    if (compute_units <= 0 || compute_units > 4096)
+        return fail(SSG_ERR_ARG, "ssg_mlp_bwd_plan: compute_units = %d (1 .. 4096)", (int)compute_units);
+    BackwardGemms bg;
+    backward_gemm_shapes(*desc, bg);
+    const int all = ssg::gemm_tile_sets(bg.dw3);
+    *dw3_sets_total = all;
+    *dw3_sets_first = all;
+    // the split exists only where both grouped launches are built: FP8 operands, the input gradient in one launch
+    if (gemm_grouping_enabled() && !desc->w3_layer_bf16 && bg.dx.part == 3) {
+        const ssg::GemmArgs *second[3] = {&bg.dx, &bg.dw1, &bg.dw2};
+        *dw3_sets_first = ssg::gemm_group_split_sets(bg.dh, bg.dw3, second, 3, compute_units);
+    }
+    return SSG_OK;
+}
+
 ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *saved, size_t saved_bytes, void *dx,
                        void *dW1, void *dW2, void *dW3, void *workspace, size_t workspace_bytes, void *stream) {
     ssg_status rc = check_desc(desc, "ssg_mlp_bwd");
@@ -899,57 +946,49 @@ ssg_status ssg_mlp_bwd(const ssg_mlp_desc *desc, const void *dy, const void *sav
     auto state_scale = [&](int k) { return reinterpret_cast<float *>(state + (size_t)k * ssg::kScalingStride); };
     uint32_t *state_dy_slots = state ? state + ssg::kScalingHeaderWords + 3 * ssg::kAmaxSlotWords : nullptr;
 
-    // every GEMM argument set is built and checked before the first launch
-    // a10: dH = s_i * dY^ w3~ / (sdy sw3), then through the SwiGLU product
-    ssg::GemmArgs g;
-    g.epilogue = ssg::EPI_SWIGLU_BWD; g.a_fmt = ssg::kE5M2; g.M = T; g.N = f; g.K = dm;
-    g.A = wk + Wl.dy_q; g.B = sv + L.w3_q; g.layout = 1; g.sa = wsc + W_SDY; g.sb = sc + S_SW3;   // B = w3~ as stored, [d,f] = [K,N]
-    // plain block: dH = acc / (sdy sw3), no channel factor
+    // every GEMM argument set is built and checked before the first launch: shapes, formats and layouts from
+    // backward_gemm_shapes, operands, scales and results here
+    BackwardGemms bg;
+    backward_gemm_shapes(*desc, bg);
+    const bool bf16_last = desc->w3_layer_bf16 != 0;
+    // a10: dH; plain block: dH = acc / (sdy sw3), no channel factor
+    ssg::GemmArgs &g = bg.dh;
+    g.A = wk + Wl.dy_q; g.B = sv + L.w3_q; g.sa = wsc + W_SDY; g.sb = sc + S_SW3;
     g.col_scale = desc->smooth ? s : nullptr;
     g.U = sv + L.U; g.G = sv + L.G; g.C = wk + Wl.dU; g.C2 = wk + Wl.dG; g.amax_bits = part_du; g.amax_bits2 = part_dg;
-    if (delayed) {
+    if (delayed && !bf16_last) {
         // the scales of dU, dG are known beforehand: the epilogue writes their E5M2 codes directly (a11 is fused
         // away; bf16 dU, dG are not stored) and still folds their ranges for the history
-        g.epilogue = ssg::EPI_SWIGLU_BWD_Q;
         g.C = wk + Wl.du_q; g.C2 = wk + Wl.dg_q;
         g.q_scale = state_scale(4); g.q_scale2 = state_scale(5); g.q_scale_out = wsc + W_SDU; g.q_scale_out2 = wsc + W_SDG;
         if (desc->keep_bf16_grads) { g.keep_u = wk + Wl.dU; g.keep_g = wk + Wl.dG; }
     }
-    // a12: dW3[j,i] = sinv_i * sum_t dY^[t,j] h^[t,i] / sdy   (plain: / (sdy * sigma_h))
-    ssg::GemmArgs g3;
-    g3.epilogue = ssg::EPI_STORE; g3.a_fmt = ssg::kE5M2; g3.M = dm; g3.N = f; g3.K = T;
-    g3.layout = 2;                                                                     // dY^ [T,d] = [K,M], h^ [T,f] = [K,N]
+    // a12: dW3 (plain: / (sdy * sigma_h))
+    ssg::GemmArgs &g3 = bg.dw3;
     g3.A = wk + Wl.dy_q; g3.B = sv + L.h_q; g3.sa = wsc + W_SDY; g3.sb = desc->smooth ? nullptr : s;
-    g3.col_scale = desc->smooth ? sinv : nullptr; g3.C = dW3; g3.c_f32 = dw_f32;
-    // a13: dX = dU^ w1^ / (sdu sw1) + dG^ w2^ / (sdg sw2).  One launch that runs both products into the same
-    // accumulators where the shape allows (whole K steps and tile columns); otherwise two launches, the first
-    // product through fp32 scratch
+    g3.col_scale = desc->smooth ? sinv : nullptr; g3.C = dW3;
+    // a13: dX.  One launch that runs both products into the same accumulators where the shape allows (whole K steps
+    // and tile columns); otherwise two launches, the first product through fp32 scratch
     float *dx_tmp = reinterpret_cast<float *>(wk + Wl.dx_tmp);
-    const bool dx_one = ssg::gemm_sum_in_one_launch_ok(dm, f);
-    ssg::GemmArgs g4a, g4b;
-    g4a.epilogue = ssg::EPI_STORE; g4a.a_fmt = ssg::kE5M2; g4a.M = T; g4a.N = dm; g4a.K = f; g4a.part = 1;
-    g4a.layout = 1;                                                                    // w1^ [f,d] = [K,N]
-    g4a.A = wk + Wl.du_q; g4a.B = sv + L.w1_q; g4a.sa = wsc + W_SDU; g4a.sb = sc + S_SW1; g4a.C = dx_tmp; g4a.c_f32 = 1;
-    g4b = g4a; g4b.part = 2;
+    ssg::GemmArgs &g4a = bg.dx;
+    const bool dx_one = g4a.part == 3;
+    g4a.A = wk + Wl.du_q; g4a.B = sv + L.w1_q; g4a.sa = wsc + W_SDU; g4a.sb = sc + S_SW1; g4a.C = dx_tmp;
+    ssg::GemmArgs g4b = g4a;
+    g4b.part = 2;
     g4b.A = wk + Wl.dg_q; g4b.B = sv + L.w2_q; g4b.sa = wsc + W_SDG; g4b.sb = sc + S_SW2; g4b.add = dx_tmp;
     g4b.C = dx; g4b.c_f32 = desc->y_dtype == SSG_F32;
     if (dx_one) {
-        g4a.part = 3; g4a.C = dx; g4a.c_f32 = g4b.c_f32;
+        g4a.C = dx;
         g4a.A_ph2 = g4b.A; g4a.B_ph2 = g4b.B; g4a.sa_ph2 = g4b.sa; g4a.sb_ph2 = g4b.sb;
     }
-    // a14: dW1 = dU^T x^ / (sdu sx), dW2 = dG^T x^ / (sdg sx)
-    ssg::GemmArgs g5a, g5b;
-    g5a.epilogue = ssg::EPI_STORE; g5a.a_fmt = ssg::kE5M2; g5a.M = f; g5a.N = dm; g5a.K = T;
-    g5a.layout = 2;                                                                    // dU^ [T,f] = [K,M], x^ [T,d] = [K,N]
-    g5a.A = wk + Wl.du_q; g5a.B = sv + L.x_q; g5a.sa = wsc + W_SDU; g5a.sb = sc + S_SX; g5a.C = dW1; g5a.c_f32 = dw_f32;
-    g5b = g5a; g5b.A = wk + Wl.dg_q; g5b.sa = wsc + W_SDG; g5b.C = dW2;
-    const bool bf16_last = desc->w3_layer_bf16 != 0;
+    // a14: dW1, dW2
+    ssg::GemmArgs &g5a = bg.dw1, &g5b = bg.dw2;
+    g5a.A = wk + Wl.du_q; g5a.B = sv + L.x_q; g5a.sa = wsc + W_SDU; g5a.sb = sc + S_SX; g5a.C = dW1;
+    g5b.A = wk + Wl.dg_q; g5b.B = sv + L.x_q; g5b.sa = wsc + W_SDG; g5b.sb = sc + S_SX; g5b.C = dW2;
     if (bf16_last) {
         // Section 4.3: dH = dY W3 and dW3 = dY^T h_b on bf16 operands (the transposed copies give every operand its
         // contraction index contiguous), no scales, no channel factors
-        g.a_fmt = ssg::kBF16; g.layout = 0; g.K = dm;
         g.A = static_cast<const uint8_t *>(dy); g.B = sv + L.w3T; g.sa = nullptr; g.sb = nullptr; g.col_scale = nullptr;
-        g3.a_fmt = ssg::kBF16; g3.layout = 0;
         g3.A = wk + Wl.dyT; g3.B = sv + L.h_bT; g3.sa = nullptr; g3.sb = nullptr; g3.col_scale = nullptr;
     }
     for (const ssg::GemmArgs *a : {&g, &g3, &g4a, &g5a, &g5b})

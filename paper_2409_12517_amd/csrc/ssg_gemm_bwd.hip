@@ -138,6 +138,7 @@ int gemm_group_split_sets(const GemmArgs &dh, const GemmArgs &dw_split, const Ge
         t[(size_t)s] = replay_dispatch(cost_a, ta, 2, units, heap) + replay_dispatch(cost_b, tiles_b, n_second + 1, units, heap);
         if (s == 0 || t[(size_t)s] < best) best = t[(size_t)s];
     }
+    if (t[(size_t)all] <= best + 1e-9) return all;             // nothing to gain: dW3 stays whole in the first launch
     int best_lo = all, best_len = 0;
     for (int s = 0; s <= all;) {
         if (t[(size_t)s] > best + 1e-9) { ++s; continue; }

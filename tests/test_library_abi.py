@@ -115,6 +115,51 @@ def test_given_h_scale_and_counters_are_validated():
     assert ssg.ssg_mlp_saved_bytes(ssg.make_desc(256, 256, 688, h_counters=4100)) == 0   # misaligned counters
 
 
+def test_backward_plan_shares_dw3_between_the_grouped_launches():
+    """Host logic only: how many sets (of 8 tiles) of dW3 run beside dH.  At the Llama2-7B shape on 256 compute
+    units dH has 688 tiles, dW3 688 = 86 sets; with all of dW3 in the first launch its last 16 tiles would start a
+    round of their own, so some sets must move, but never so many that the second launch gains a round."""
+    import paper_2409_12517_amd as ssg
+    first, total = ssg.ssg_mlp_bwd_plan(ssg.make_desc(4096, 4096, 11008), 256)
+    assert total == 86
+    # first launch: 688 dH tiles fill 2 rounds + 176 units; the dW3 tiles that fit without a round of their own are
+    # bounded by a whole number of rounds of the units free by then; the second launch's last round (96 of 256 tiles)
+    # has room for 160 more tiles = 20 sets
+    assert 86 - 20 <= first < 86
+    # independent restatement of the objective: replay an in-order dispatch with one time per kind of tile and
+    # check that no other split is predicted faster than the chosen one by more than a rounding
+    import heapq
+
+    def end_of(launch, units=256):
+        free = [0.0] * units
+        heapq.heapify(free)
+        end = 0.0
+        for cost, n in launch:
+            for _ in range(n):
+                t = heapq.heappop(free) + cost
+                end = max(end, t)
+                heapq.heappush(free, t)
+        return end
+    dh, dw, dx = 2.5 + 1.33 * 32 + 33, 2.5 + 1.33 * 32 + 10, 2.5 + 1.45 * 172 + 6
+
+    def predicted(sets):
+        a = min(8 * sets, 688)
+        return end_of([(dh, 688), (dw, a)]) + end_of([(dx, 256), (dw, 688), (dw, 688), (dw, 688 - a)])
+    best = min(predicted(k) for k in range(87))
+    assert predicted(first) <= best + 1e-6 and predicted(86) > best + 10.0
+    # a device with a single compute unit has no rounds to fill: any split costs the same, nothing moves
+    assert ssg.ssg_mlp_bwd_plan(ssg.make_desc(4096, 4096, 11008), 1) == (86, 86)
+    # tiny and ragged shapes: the answer is a valid split
+    for shape in ((256, 256, 688), (272, 304, 688), (4096, 4096, 11008 + 16)):
+        f1, t1 = ssg.ssg_mlp_bwd_plan(ssg.make_desc(*shape), 256)
+        assert 0 <= f1 <= t1 and t1 >= 1
+    # the bf16 comparison variant does not use the grouped launches
+    f2, t2 = ssg.ssg_mlp_bwd_plan(ssg.make_desc(4096, 4096, 11008, smooth=0, w3_layer_bf16=1), 256)
+    assert f2 == t2
+    with pytest.raises(ssg.SsgError):
+        ssg.ssg_mlp_bwd_plan(ssg.make_desc(4096, 4096, 11008), 0)
+
+
 def test_adam_entry_points_validate_before_launching():
     """No GPU here: every call must be refused on its arguments alone."""
     import paper_2409_12517_amd as ssg
