@@ -212,6 +212,7 @@ PROFILE_COMMANDS = {
     "fetch": "rocprofv3 --pmc FETCH_SIZE --output-format csv -d DIR/fetch -o fetch -- python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --copy-probe",
     "write": "rocprofv3 --pmc WRITE_SIZE --output-format csv -d DIR/write -o write -- python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --copy-probe",
     "mfma": "rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_F8 SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE GRBM_GUI_ACTIVE --output-format csv -d DIR/mfma -o mfma -- python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline",
+    "sq": "rocprofv3 --pmc SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_WAIT_ANY SQ_WAIT_INST_ANY SQ_WAIT_INST_LDS SQ_VALU_MFMA_BUSY_CYCLES --output-format csv -d DIR/sq -o sq -- python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline",
 }
 
 
@@ -346,6 +347,45 @@ def summarize_profiles(src: str) -> int:
                 fo.write("%-44s %5d %10.1f %10.2f %9.1f%% %16.0f %16.0f\n"
                          % (short(k)[:44], n, t / 1e3, g / 8 / t, 100 * sum(c["SQ_VALU_MFMA_BUSY_CYCLES"]) / n / 1024 / (g / 8),
                             sum(c["SQ_LDS_BANK_CONFLICT"]) / n, sum(c["SQ_LDS_IDX_ACTIVE"]) / n))
+    # 4. the compute units' own clock and what the waves wait for
+    sq_p = find("sq", "counter_collection.csv")
+    if sq_p:
+        sq = collections.defaultdict(lambda: collections.defaultdict(list))
+        dur = collections.defaultdict(list)
+        seen = set()
+        for r in csv.DictReader(open(sq_p)):
+            sq[r["Kernel_Name"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
+            key = (r["Kernel_Name"], r.get("Dispatch_Id"))
+            if key not in seen:
+                seen.add(key)
+                dur[r["Kernel_Name"]].append(float(r["End_Timestamp"]) - float(r["Start_Timestamp"]))
+        with open(os.path.join(out_dir, "gemm_7b_sq_clock.txt"), "w") as fo:
+            fo.write(f"Clock of the compute units and wave wait cycles of the GEMM kernels at the {shape}; library at commit {commit}\n"
+                     "command (from /tmp, TMPDIR=/tmp):\n  " + PROFILE_COMMANDS["sq"] + "\n")
+            fo.write("SQ_BUSY_CYCLES is summed over the 32 shader engines, each counting the cycles of its own clock while it has waves: "
+                     "clock = SQ_BUSY_CYCLES / 32 / duration (the register-only MFMA loop, mfma_rate_kernel, is the check: on constant "
+                     "operands it reads the full clock, on this workload's operand bytes the clock that 100 % MFMA utilisation leaves).  "
+                     "MFMA utilisation = SQ_VALU_MFMA_BUSY_CYCLES / 1024 SIMDs / (SQ_BUSY_CYCLES / 32).  SQ_WAIT_ANY (a wave waits at "
+                     "s_waitcnt or a barrier) and SQ_WAIT_INST_ANY (a wave waits for an instruction to issue, e.g. behind a running MFMA) as "
+                     "shares of SQ_WAVE_CYCLES.\n" + legend + "\n\n")
+            fo.write("%-44s %5s %10s %10s %10s %10s %10s %10s\n" % ("kernel", "n", "dur_us", "clock_GHz", "mfma_util", "wait_any", "wait_inst", "wait_lds"))
+            def row(name, c, d, lo, hi):
+                n = hi - lo
+                busy = sum(c["SQ_BUSY_CYCLES"][lo:hi]) / n / 32
+                t = sum(d[lo:hi]) / n
+                wc = sum(c["SQ_WAVE_CYCLES"][lo:hi]) / n
+                fo.write("%-44s %5d %10.1f %10.2f %9.1f%% %9.1f%% %9.1f%% %9.1f%%\n"
+                         % (name[:44], n, t / 1e3, busy / t, 100 * sum(c["SQ_VALU_MFMA_BUSY_CYCLES"][lo:hi]) / n / 1024 / busy,
+                            100 * sum(c["SQ_WAIT_ANY"][lo:hi]) / n / wc, 100 * sum(c["SQ_WAIT_INST_ANY"][lo:hi]) / n / wc,
+                            100 * sum(c["SQ_WAIT_INST_LDS"][lo:hi]) / n / wc))
+            for k, c in sq.items():
+                n = len(c["SQ_BUSY_CYCLES"])
+                if "mfma_rate" in k and n == 4:
+                    # bench.py launches the loop twice on constant operands, then twice on this workload's operand bytes
+                    row("mfma_rate_kernel, constant operands", c, dur[k], 0, 2)
+                    row("mfma_rate_kernel, workload operands", c, dur[k], 2, 4)
+                elif "gemm" in k:
+                    row(short(k), c, dur[k], 0, n)
     print("profiles written under", out_dir)
     return 0
 
