@@ -167,6 +167,12 @@ bool launch_gemm_group(const GemmArgs *const *list, int n, int split_sets, hipSt
         if (n == 2) g.sets[1] = cut;
         else { g.first[n - 1] = cut; g.sets[n - 1] = all - cut; }
     }
+    // The fp32 weight gradients of the second launch go out through non-temporal stores: nothing reads them before
+    // the optimizer, and kept out of the caches they leave in place what the passes after this launch read (measured
+    // at the Llama2-7B shape: -10 us per step, in the launches that follow, not in this one).  In the first launch,
+    // beside dH's epilogue traffic, the same stores cost 3-7 us: left as they are.
+    if (n >= 3)
+        for (int i = 1; i < n; ++i) g.p[i].nt_store = 1;
     for (int i = 0; i < n; ++i) {
         // flops of the tiles this launch runs (a last set may be partly beyond the GEMM's tile count)
         const int tiles = g.p[i].tiles_m * g.p[i].tiles_n;

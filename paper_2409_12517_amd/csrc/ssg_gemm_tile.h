@@ -60,6 +60,7 @@ struct GemmParams {
     // PART = 3 (a sum of two products in one tile): operands and scales of the second product, same shapes
     const uint8_t *A_ph2, *B_ph2;
     const float *sa_ph2, *sb_ph2;
+    int nt_store;        // EPI_STORE, fp32 output: 1 = non-temporal stores (the output is not read again soon)
 };
 
 // An LDS row holds the 128 bytes (eight 16-byte chunks, one full cache line) of one matrix row for one
@@ -577,7 +578,12 @@ __device__ __forceinline__ void gemm_tile(const GemmParams &p, const int vblock,
                     float *out = reinterpret_cast<float *>(p.C) + (size_t)row * (size_t)p.N + (size_t)col4;
                     float4 o = make_float4(__fmul_rn(a.x, f4[0]), __fmul_rn(a.y, f4[1]), __fmul_rn(a.z, f4[2]), __fmul_rn(a.w, f4[3]));
                     if (post) o = make_float4(o.x * dq.post, o.y * dq.post, o.z * dq.post, o.w * dq.post);
-                    *reinterpret_cast<float4 *>(out) = o;
+                    if (p.nt_store) {
+                        typedef float f32x4 __attribute__((ext_vector_type(4)));
+                        __builtin_nontemporal_store(f32x4{o.x, o.y, o.z, o.w}, reinterpret_cast<f32x4 *>(out));
+                    } else {
+                        *reinterpret_cast<float4 *>(out) = o;
+                    }
                 }
                 continue;
             }
@@ -754,6 +760,7 @@ inline GemmParams make_gemm_params(const GemmArgs &a) {
     p.q_scale = a.q_scale; p.q_scale2 = a.q_scale2; p.q_scale_out = a.q_scale_out; p.q_scale_out2 = a.q_scale_out2;
     p.keep_u = (uint16_t *)a.keep_u; p.keep_g = (uint16_t *)a.keep_g;
     p.A_ph2 = a.A_ph2; p.B_ph2 = a.B_ph2; p.sa_ph2 = a.sa_ph2; p.sb_ph2 = a.sb_ph2;
+    p.nt_store = 0;
     p.tiles_m = (int)((a.M + BM - 1) / BM);
     const int n_per_tile = (a.epilogue == EPI_SWIGLU || a.epilogue == EPI_SWIGLU_Q) ? BN / 2 : BN;
     p.tiles_n = (int)((a.N + n_per_tile - 1) / n_per_tile);
