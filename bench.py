@@ -596,6 +596,16 @@ def main() -> int:
     dt_infer = time.perf_counter() - t3
     del prep, iwork
 
+    # the training forward alone (the forward-only configuration of the same shape): ssg_mlp_fwd as in the headline
+    for _ in range(3):
+        ssg.ssg_mlp_fwd(desc, x, W1, W2, W3, y, saved, stream)
+    torch.cuda.synchronize()
+    t4 = time.perf_counter()
+    for _ in range(args.steps):
+        ssg.ssg_mlp_fwd(desc, x, W1, W2, W3, y, saved, stream)
+    torch.cuda.synchronize()
+    dt_fwd = time.perf_counter() - t4
+
     ms_per_step = dt * 1e3 / args.steps
     flops_step = 18.0 * T * d * f
     value = flops_step / (ms_per_step * 1e-3) / 1e12
@@ -658,6 +668,10 @@ def main() -> int:
                                     "bf16 SwiGLU output, y, dH and dW3 on bf16 operands, transposed bf16 copies written), the "
                                     "row 'FP8 + SwiGLU output in BF16' of the paper's Table 3; Smooth-SwiGLU (the headline) sits "
                                     "between it and plain_fp8, as in that table"},
+        "training_forward_only": {"value": 6.0 * T * d * f / (dt_fwd / args.steps) / 1e12, "unit": "TFLOP/s",
+                                  "ms_per_call": dt_fwd * 1e3 / args.steps,
+                                  "note": "ssg_mlp_fwd alone (current scaling, W1/W2 quantized every call, U, G and the codes "
+                                          "stored for a backward pass): 6 T d f flops; not the headline"},
         "inference_forward": {"value": 6.0 * T * d * f / (dt_infer / args.steps) / 1e12, "unit": "TFLOP/s",
                               "ms_per_call": dt_infer * 1e3 / args.steps,
                               "note": "forward only with the calibrated factors folded into w1 and w3 "
